@@ -1,0 +1,47 @@
+"""CPU oracle: Parle on a network = oracle/nets.py gradients fed to oracle/parle.py updates.
+
+TEST INFRASTRUCTURE ONLY (tests, smoke check, CPU-baseline timing).  One call
+of :func:`inner_step` is what Section 3 of the paper does per mini-batch for
+all replicas: gradient of the mini-batch loss at y^a, then (8a)-(8b);
+:func:`outer_step` is (8c)-(8d), the reset, and rule (9).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import nets, parle
+
+
+class ParleNet:
+    def __init__(self, a, cfg: parle.ParleConfig, x0, dtype=np.float64):
+        self.a, self.cfg, self.dtype = a, cfg, dtype
+        self.st = parle.init_state(x0, cfg, dtype=dtype)
+        self.bn = [nets.new_bn_state(a, dtype) for _ in range(cfg.n_replicas)]
+
+    def inner_step(self, images, labels):
+        """images ``[n, B, H, W, C]``, labels ``[n, B]``; returns the per-replica losses at y^a."""
+        n = self.cfg.n_replicas
+        losses = np.zeros(n)
+        G = np.zeros_like(self.st.y)
+        for a_i in range(n):
+            losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.y[a_i], images[a_i], labels[a_i],
+                                                     bn_state=self.bn[a_i], dtype=self.dtype)
+        parle.inner_update(self.st, G, self.cfg)
+        self.last_grad = G
+        return losses
+
+    def outer_step(self):
+        parle.outer_step(self.st, self.cfg)
+
+    def eval(self, which, images, labels):
+        """Loss / error count of the reference (which = -1, batch-norm statistics averaged over the
+        replicas) or of replica ``which`` (its x^a), plus the ensemble spread."""
+        if which < 0:
+            flat = self.st.x_ref
+            bn = {k: [np.mean([b[k][0] for b in self.bn], axis=0), np.mean([b[k][1] for b in self.bn], axis=0)]
+                  for k in self.bn[0]}
+        else:
+            flat, bn = self.st.x[which], self.bn[which]
+        loss, nerr = nets.evaluate(self.a, flat, images, labels, bn_state=bn, dtype=self.dtype)
+        sp = float(sum(np.sum((self.st.x[i] - self.st.x_ref) ** 2) for i in range(self.cfg.n_replicas)))
+        return loss, nerr, sp

@@ -1,0 +1,252 @@
+"""Pins for oracle/nets.py: finite differences, brute force, library routines, closed forms.
+
+The paper fixes the loss only as "average cross-entropy of a deep network"
+(Section 1.1) and names the networks through citations; what can be pinned
+without an implementation to compare against is that every layer computes its
+textbook definition and that the hand-derived backward pass is the gradient of
+the forward pass.
+"""
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+from oracle import nets
+from paper_1707_00424_amd import synth
+
+TINY = {
+    "mlp": nets.arch("mlp", H=3, W=2, C=1, hidden=5, classes=3),
+    "lenet": nets.arch("lenet", H=10, W=10, C=1, c1=2, c2=3, k=3, fc=7, classes=4),
+    "allcnn": nets.arch("allcnn", H=8, W=8, C=2, ca=3, cb=4, classes=3),
+    "wrn": nets.arch("wrn", H=8, W=8, C=2, base=2, widen=2, nb=2, classes=3),
+}
+
+
+def _data(a, B, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, a["H"], a["W"], a["C"]))
+    y = rng.integers(0, a["classes"], B)
+    return x, y
+
+
+@pytest.mark.parametrize("model", ["mlp", "lenet", "allcnn", "wrn"])
+def test_gradient_matches_central_differences(model):
+    a = TINY[model]
+    p = synth.init_params(nets.layout(a), seed=11).astype(np.float64)
+    x, y = _data(a, 3, 12)
+    _, g = nets.loss_and_grad(a, p, x, y, bn_state=nets.new_bn_state(a))
+    h = 1e-6
+    rng = np.random.default_rng(13)
+    idx = np.arange(p.size) if p.size <= 400 else rng.choice(p.size, 400, replace=False)
+    bad = 0
+    for i in idx:
+        pp, pm = p.copy(), p.copy()
+        pp[i] += h
+        pm[i] -= h
+        lp = nets.loss_and_grad(a, pp, x, y, bn_state=nets.new_bn_state(a))[0]
+        lm = nets.loss_and_grad(a, pm, x, y, bn_state=nets.new_bn_state(a))[0]
+        fd = (lp - lm) / (2 * h)
+        if abs(fd - g[i]) > 1e-6 * max(1.0, abs(fd)) + 1e-8:
+            bad += 1
+    assert bad == 0
+
+
+def test_every_segment_receives_gradient():
+    for model, a in TINY.items():
+        p = synth.init_params(nets.layout(a), seed=1).astype(np.float64)
+        x, y = _data(a, 4, 2)
+        _, g = nets.loss_and_grad(a, p, x, y, bn_state=nets.new_bn_state(a))
+        off = 0
+        for s in nets.layout(a):
+            size = int(np.prod(s["shape"]))
+            assert np.abs(g[off:off + size]).max() > 0, (model, s["name"])
+            off += size
+
+
+def test_parameter_counts_of_full_architectures():
+    assert nets.n_params(nets.arch("mlp")) == 784 * 128 + 128 + 128 * 10 + 10 == 101770
+    assert nets.n_params(nets.arch("lenet")) == 520 + 25050 + 400500 + 5010 == 431080
+    assert nets.n_params(nets.arch("allcnn")) == 1369738
+    assert nets.n_params(nets.arch("wrn")) == 2742704 + 2570 + 3616 == 2748890
+    # WRN-16-4: 16 = 6 * 2 + 4 weight layers on the main path: conv1 + 12 block convs + fc = 14, + 3 shortcuts
+    names = [s["name"] for s in nets.layout(nets.arch("wrn")) if s["kind"] == "weight"]
+    assert len(names) == 1 + 12 + 3 + 1
+
+
+def test_forward_flop_counts():
+    assert nets.flops_forward_per_image(nets.arch("mlp")) == 2 * (784 * 128 + 128 * 10)
+    # conv1 24*24*20*25, conv2 8*8*50*500, fc 800*500, fc 500*10 multiply-adds
+    assert nets.flops_forward_per_image(nets.arch("lenet")) == 2 * (288000 + 1600000 + 400000 + 5000)
+    assert abs(nets.flops_forward_per_image(nets.arch("allcnn")) / 1e6 - 562) < 5
+    assert abs(nets.flops_forward_per_image(nets.arch("wrn")) / 1e6 - 785) < 8
+
+
+# ---- single layers against independent definitions ------------------------------------------------------------
+def _conv_bruteforce(x, w, b, stride, pad):
+    B, H, W, Cin = x.shape
+    Cout, kh, kw, _ = w.shape
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    out = np.zeros((B, Ho, Wo, Cout))
+    for n in range(B):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for co in range(Cout):
+                    s = b[co] if b is not None else 0.0
+                    for i in range(kh):
+                        for j in range(kw):
+                            hi, wi = ho * stride - pad + i, wo * stride - pad + j
+                            if 0 <= hi < H and 0 <= wi < W:
+                                for ci in range(Cin):
+                                    s += x[n, hi, wi, ci] * w[co, i, j, ci]
+                    out[n, ho, wo, co] = s
+    return out
+
+
+@pytest.mark.parametrize("stride,pad,k", [(1, 0, 3), (1, 1, 3), (2, 1, 3), (2, 0, 1), (1, 0, 5)])
+def test_conv_forward_bruteforce(stride, pad, k):
+    rng = np.random.default_rng(20)
+    x, w, b = rng.standard_normal((2, 7, 6, 3)), rng.standard_normal((4, k, k, 3)), rng.standard_normal(4)
+    o = nets.conv2d(nets.Tape(), nets.Var(x), nets.Var(w), nets.Var(b), stride, pad).v
+    assert np.allclose(o, _conv_bruteforce(x, w, b, stride, pad), atol=1e-12)
+
+
+def test_conv_forward_against_scipy_correlate():
+    rng = np.random.default_rng(21)
+    x, w = rng.standard_normal((1, 9, 8, 2)), rng.standard_normal((3, 3, 3, 2))
+    o = nets.conv2d(nets.Tape(), nets.Var(x), nets.Var(w), None, 1, 0).v
+    for co in range(3):
+        ref = sum(correlate2d(x[0, :, :, ci], w[co, :, :, ci], mode="valid") for ci in range(2))
+        assert np.allclose(o[0, :, :, co], ref, atol=1e-12)
+    # padding 1 = scipy's "same" for a 3x3 kernel
+    o = nets.conv2d(nets.Tape(), nets.Var(x), nets.Var(w), None, 1, 1).v
+    ref = sum(correlate2d(x[0, :, :, ci], w[1, :, :, ci], mode="same") for ci in range(2))
+    assert np.allclose(o[0, :, :, 1], ref, atol=1e-12)
+
+
+def test_conv_backward_is_adjoint():
+    """<conv(x), u> = <x, conv^T(u)> and the weight gradient is the same bilinear form."""
+    rng = np.random.default_rng(22)
+    for stride, pad in [(1, 1), (2, 1), (2, 0)]:
+        x, w = rng.standard_normal((2, 6, 7, 3)), rng.standard_normal((4, 3, 3, 3))
+        t = nets.Tape()
+        xv, wv = nets.Var(x), nets.Var(w)
+        o = nets.conv2d(t, xv, wv, None, stride, pad)
+        u = rng.standard_normal(o.v.shape)
+        o.g = u
+        t.backward()
+        assert np.isclose(np.sum(o.v * u), np.sum(x * xv.g))
+        assert np.isclose(np.sum(o.v * u), np.sum(w * wv.g))
+
+
+def test_linear_flatten_order_is_hwc():
+    x = np.arange(2 * 2 * 3 * 2, dtype=float).reshape(2, 2, 3, 2)
+    w = np.zeros((1, 12))
+    w[0, (1 * 3 + 2) * 2 + 1] = 1.0                    # picks h=1, w=2, c=1
+    o = nets.linear(nets.Tape(), nets.Var(x), nets.Var(w), nets.Var(np.zeros(1))).v
+    assert np.array_equal(o[:, 0], x[:, 1, 2, 1])
+
+
+def test_maxpool_bruteforce_and_tie_rule():
+    rng = np.random.default_rng(23)
+    x = rng.standard_normal((2, 5, 6, 3))
+    t = nets.Tape()
+    xv = nets.Var(x)
+    o = nets.maxpool2(t, xv)
+    assert o.v.shape == (2, 2, 3, 3)
+    for n in range(2):
+        for i in range(2):
+            for j in range(3):
+                for c in range(3):
+                    assert o.v[n, i, j, c] == x[n, 2 * i:2 * i + 2, 2 * j:2 * j + 2, c].max()
+    o.g = np.ones_like(o.v)
+    t.backward()
+    assert xv.g.sum() == o.v.size and set(np.unique(xv.g)) <= {0.0, 1.0}
+    # all-equal window: the gradient goes to the first element in row-major order
+    t = nets.Tape()
+    xv = nets.Var(np.zeros((1, 2, 2, 1)))
+    o = nets.maxpool2(t, xv)
+    o.g = np.ones_like(o.v)
+    t.backward()
+    assert xv.g[0, :, :, 0].tolist() == [[1.0, 0.0], [0.0, 0.0]]
+
+
+def test_relu_zero_has_zero_slope():
+    t = nets.Tape()
+    xv = nets.Var(np.array([[-1.0, 0.0, 2.0]]))
+    o = nets.relu(t, xv)
+    o.g = np.ones_like(o.v)
+    t.backward()
+    assert o.v.tolist() == [[0.0, 0.0, 2.0]] and xv.g.tolist() == [[0.0, 0.0, 1.0]]
+
+
+def test_softmax_xent_closed_forms():
+    t = nets.Tape()
+    lv = nets.Var(np.full((4, 10), 0.7))
+    loss, _ = nets.softmax_xent(t, lv, np.array([0, 3, 9, 5]))
+    assert np.isclose(loss, np.log(10.0), atol=1e-15)
+    t.backward()
+    assert np.abs(lv.g.sum(axis=1)).max() < 1e-16
+    # against scipy's log-sum-exp on random logits
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(24)
+    lg, lab = rng.standard_normal((6, 5)) * 4, rng.integers(0, 5, 6)
+    loss, pred = nets.softmax_xent(nets.Tape(), nets.Var(lg), lab)
+    assert np.isclose(loss, np.mean(logsumexp(lg, axis=1) - lg[np.arange(6), lab]), atol=1e-14)
+    assert np.array_equal(pred, lg.argmax(axis=1))
+
+
+def test_batchnorm_statistics_and_running_buffers():
+    rng = np.random.default_rng(25)
+    x = rng.standard_normal((4, 3, 5, 6)) * 3 + 2
+    stats = [np.zeros(6), np.ones(6)]
+    o = nets.batchnorm(nets.Tape(), nets.Var(x), nets.Var(np.ones(6)), nets.Var(np.zeros(6)), stats, True).v
+    flat = o.reshape(-1, 6)
+    assert np.abs(flat.mean(axis=0)).max() < 1e-14
+    assert np.allclose(flat.var(axis=0), x.reshape(-1, 6).var(axis=0) / (x.reshape(-1, 6).var(axis=0) + 1e-5))
+    assert np.allclose(stats[0], 0.1 * x.reshape(-1, 6).mean(axis=0))
+    assert np.allclose(stats[1], 0.9 + 0.1 * x.reshape(-1, 6).var(axis=0, ddof=1))
+    # evaluation mode uses the buffers, not the batch
+    st = [np.full(6, 2.0), np.full(6, 9.0)]
+    o = nets.batchnorm(nets.Tape(), nets.Var(x), nets.Var(np.full(6, 2.0)), nets.Var(np.ones(6)), st, False).v
+    assert np.allclose(o, (x - 2.0) / np.sqrt(9.0 + 1e-5) * 2.0 + 1.0)
+    assert st[0][0] == 2.0 and st[1][0] == 9.0
+
+
+def test_gap_is_spatial_mean():
+    x = np.random.default_rng(26).standard_normal((2, 3, 4, 5))
+    assert np.allclose(nets.gap(nets.Tape(), nets.Var(x)).v, x.mean(axis=(1, 2)))
+
+
+def test_mlp_logits_against_direct_matmul():
+    a = TINY["mlp"]
+    p = synth.init_params(nets.layout(a), seed=3).astype(np.float64)
+    x, _ = _data(a, 5, 4)
+    W1, b1 = p[:30].reshape(5, 6), p[30:35]
+    W2, b2 = p[35:50].reshape(3, 5), p[50:53]
+    ref = np.maximum(x.reshape(5, 6) @ W1.T + b1, 0) @ W2.T + b2
+    assert np.allclose(nets.logits_only(a, p, x), ref, atol=1e-14)
+
+
+def test_wrn_block_structure():
+    """Identity blocks add the block input; shape-changing blocks add a strided 1x1 conv of the
+    pre-activated input: zeroing both 3x3 convs of a block leaves exactly that shortcut."""
+    a = TINY["wrn"]
+    blocks = nets.wrn_blocks(a)
+    assert [(b[1], b[2], b[3]) for b in blocks] == [(2, 4, 1), (4, 4, 1), (4, 8, 2), (8, 8, 1), (8, 16, 2), (16, 16, 1)]
+    names = [s["name"] for s in nets.layout(a)]
+    assert "g1b1.sc.w" in names and "g2b1.sc.w" in names and "g3b1.sc.w" in names
+    assert "g1b2.sc.w" not in names and "g2b2.sc.w" not in names
+
+
+def test_trainer_with_one_replica_and_no_coupling_is_sgd_on_the_network():
+    """n = 1, g = r = 0, mu = 0: the y-chain of (8a) is plain mini-batch SGD on the network loss."""
+    from oracle import parle, trainer
+    a = TINY["lenet"]
+    p0 = synth.init_params(nets.layout(a), seed=5).astype(np.float64)
+    cfg = parle.ParleConfig(n_replicas=1, gamma0=0.0, rho0=0.0, momentum=0.0, eta_inner=0.05)
+    net = trainer.ParleNet(a, cfg, p0[None])
+    p = p0.copy()
+    for s in range(3):
+        x, y = _data(a, 4, 30 + s)
+        net.inner_step(x[None], y[None])
+        p = p - 0.05 * nets.loss_and_grad(a, p, x, y)[1]
+        assert np.allclose(net.st.y[0], p, atol=1e-14)
