@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the Parle hot path on one MI355X.
+
+Headline workload (`config.workload = "flat_update_n8_36.5M"`): n = 8 replicas of a flat fp32
+parameter vector of 36.5M elements; a step is one fused inner update (8a)+(8b) on all replicas,
+and after every 25th step the outer step (replica mean (8d) + fused outer update (8c) + reset).
+Inputs are synthetic (params ~ N(0, 0.05^2), gradients ~ N(0, 1e-4)), resident in HBM before the
+timed region.  `value` is algorithmic bytes of the timed steps divided by elapsed time.
+
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build runs on one GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+N_REPLICAS, N_PARAMS, L = 8, 36_500_000, 25
+# algorithmic bytes per element-replica: inner reads grad,y,x,vy,z and writes y,vy,z
+INNER_B = 32
+# replica mean reads n rows and writes one: (4n + 4) bytes per column
+# outer update reads x,z,vx (+ x_ref once per column) and writes x,vx,y,z,vy
+OUTER_B = 32
+
+
+def algorithmic_bytes(n, n_elem, inner_steps, outer_steps, fused):
+    inner = inner_steps * n * n_elem * INNER_B
+    mean = 0 if fused else outer_steps * n_elem * (4 * n + 4)
+    outer = outer_steps * (n * n_elem * OUTER_B + n_elem * (4 if not fused else 4))
+    return inner + mean + outer
+
+
+def cpu_baseline(sample_elems=4_000_000, inner=4):
+    """The oracle as it stands (float32 mode), on a column sample of the same workload."""
+    from oracle import parle as oparle
+    from paper_1707_00424_amd import synth
+    n = N_REPLICAS
+    cfg = oparle.ParleConfig(n_replicas=n, gamma0=0.03, rho0=1.0)
+    x0 = synth.flat_params(0, n, sample_elems)
+    G = synth.flat_grads(0, 0, n, sample_elems)
+    st = oparle.init_state(x0, cfg, dtype=np.float32)
+    oparle.inner_update(st, G, cfg)            # warm-up (page faults, allocator)
+    t0 = time.perf_counter()
+    for _ in range(inner):
+        oparle.inner_update(st, G, cfg)
+    oparle.outer_step(st, cfg)
+    dt = time.perf_counter() - t0
+    byt = algorithmic_bytes(n, sample_elems, inner, 1, fused=False)
+    return {"value": round(byt / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"n={n}, {sample_elems} of {N_PARAMS} columns, {inner} inner updates + 1 outer step, "
+                      f"float32 numpy, {dt:.1f} s", "host_cpus": os.cpu_count()}
+
+
+def read_traffic():
+    """HBM bytes per inner-update launch from the committed rocprofv3 counter summary, if present."""
+    p = os.path.join(ROOT, "profiles", "inner_update_flat_n8_36p5M_pmc.txt")
+    try:
+        for line in open(p):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--fuse-outer", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the Parle step on ONE GPU (all replicas stacked on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1707_00424_amd import binding as pb
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    pb.lib()
+    torch.cuda.set_device(0)
+    n, N = N_REPLICAS, N_PARAMS
+    cfg = pb.make_config(model=pb.MODEL_FLAT, n_replicas=n, n_params=N, L=L, eta_inner=0.1, eta_outer=0.1,
+                         momentum=0.9, alpha=0.75, gamma0=0.03, rho0=1.0, fuse_outer=args.fuse_outer)
+    # seeded synthetic inputs, generated on the device (host generation of 292M normals is slow)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    x0 = torch.empty((n, N), dtype=torch.float32, device="cuda").normal_(0.0, 0.05, generator=gen)
+    P = pb.Parle(cfg, x0)
+    del x0
+    P.grad[:, :N].normal_(0.0, 1e-2, generator=gen)
+    n_pad = P.sizes.n_pad
+
+    def step(i):
+        P.parle_inner_step()
+        if (i + 1) % L == 0:
+            P.parle_outer_step()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    outer_steps = 0
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        P.parle_inner_step()
+        ev[i][1].record()
+        if (args.warmup + i + 1) % L == 0:
+            P.parle_outer_step()
+            outer_steps += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    inner_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    total_bytes = algorithmic_bytes(n, n_pad, args.steps, outer_steps, bool(args.fuse_outer))
+    value = total_bytes / elapsed / 1e9
+    inner_bytes = n * n_pad * INNER_B
+    achieved = inner_bytes / (inner_ms * 1e-3) / 1e9
+    out = {
+        "metric": "fused update HBM GB/s (algorithmic bytes / elapsed), Parle update-only workload",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "flat_update_n8_36.5M", "n_replicas": n, "n_params": N, "L": L,
+                   "outer_steps_timed": outer_steps, "fuse_outer": args.fuse_outer,
+                   "inner_updates_per_sec": round(args.steps / elapsed, 2)},
+        "roofline": {"bound": "hbm", "kernel": "k_inner_update", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "avg_launch_ms": round(inner_ms, 4), "algorithmic_bytes_per_launch": inner_bytes,
+                     "traffic": read_traffic()},
+    }
+    P.close()
+    del P
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,219 @@
+/*
+ * parle.h -- C ABI of the Parle replica-coupled training step on one MI355X (gfx950).
+ *
+ * All n replicas of a network live on one GPU as rows of stacked [n, n_pad] fp32 tensors.
+ * The library runs, with hand-written HIP kernels only:
+ *   - the replica-batched forward / loss / backward that yields grad f(y^a) of update (8a),
+ *   - the fused inner update: (8a) with Nesterov momentum and the running average (8b),
+ *   - the replica mean: (8d) with eta'' = rho/n (Section 3.1),
+ *   - the fused outer update: (8c) with Nesterov momentum and the reset y^a <- x^a,
+ *   - the scoping rule (9) on the host.
+ * Equation, section and remark numbers refer to "Parle: parallelizing stochastic gradient
+ * descent" (arXiv 1707.00424).
+ *
+ * COUPLING CONVENTION.  The paper writes the couplings as 1/gamma and 1/rho and decays gamma, rho.
+ * This ABI uses the multipliers g = 1/gamma, r = 1/rho: the proximal force of (8a) is
+ * g * (y - x^a), the elastic force of (8c) is r * (x^a - x_ref); scoping makes g and r grow
+ * up to gamma_max, rho_max.
+ *
+ * GENERAL RULES.  Plain C types only.  Every function returns a parle_status and never throws.
+ * Pointers named "dev" are DEVICE pointers owned by the caller (any allocator; PyTorch tensors in
+ * the bundled binding); pointers named "host" are host pointers.  The library allocates no
+ * device memory and frees none.  All device work is enqueued on the HIP stream given at init
+ * and is asynchronous unless stated.  Buffers must not alias.  Calls on one context must not
+ * overlap in time.  Non-finite values are not trapped by the step calls (parle_eval reports them).
+ */
+#ifndef PARLE_H
+#define PARLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct parle_ctx parle_ctx; /* opaque, host memory, owned by the library */
+
+typedef enum {
+  PARLE_OK = 0,
+  PARLE_EINVAL = -1,     /* bad argument or configuration field */
+  PARLE_ENOMEM = -2,     /* host allocation failed */
+  PARLE_EALIGN = -3,     /* a device pointer is not 256-byte aligned */
+  PARLE_ESIZE = -4,      /* a size exceeds what the kernels index (see parle_query_sizes) */
+  PARLE_EHIP = -5,       /* a HIP call failed; parle_last_error has the text */
+  PARLE_ESTATE = -6,     /* call order violated (outer step without an inner step since the last) */
+  PARLE_ENONFINITE = -7  /* parle_eval found a NaN/Inf loss */
+} parle_status;
+
+typedef enum {
+  PARLE_MODEL_FLAT = 0,     /* no network: the caller writes buffers.grad before each inner step */
+  PARLE_MODEL_MLP = 1,      /* in - hidden - classes, ReLU;                    arch = {hidden} */
+  PARLE_MODEL_LENET = 2,    /* conv-pool-conv-pool-fc-fc;                      arch = {c1, c2, k, fc} */
+  PARLE_MODEL_ALLCNN_C = 3, /* All-CNN-C, nine convs + global average pool;    arch = {ca, cb} */
+  PARLE_MODEL_WRN = 4       /* pre-activation wide ResNet, depth 6*nb+4;       arch = {base, widen, nb} */
+} parle_model;
+
+/*
+ * Network definitions (Section 4 names the families; sizes default to the paper's workloads).
+ * Activations are channels-last [B, H, W, C].  A conv weight is [Cout, kh, kw, Cin] row-major,
+ * an fc weight is [out, in] with the input flattened in (h, w, c) order.  One replica's row of
+ * every state tensor packs the segments in execution order, weight before bias, then zero
+ * padding up to n_pad; parle_query_layout enumerates the segments.
+ *   MLP      fc(H*W*C -> hidden) ReLU fc(hidden -> classes).           default 28x28x1, hidden 128
+ *   LENET    conv k x k (no padding, c1) ReLU maxpool2  conv k x k (c2) ReLU maxpool2
+ *            fc(fc) ReLU fc(classes).                                   default 28x28x1, 20/50, k 5, fc 500
+ *   ALLCNN_C 3x3 convs ca, ca, ca (stride 2), cb, cb, cb (stride 2), cb, all padding 1;
+ *            1x1 convs cb, classes; ReLU after every conv but the last; global average pool.
+ *                                                                       default 32x32x3, 96/192
+ *   WRN      conv3x3(C -> base); three groups of nb blocks, widths base*widen*{1,2,4}, first
+ *            block of groups 2 and 3 has stride 2; block = BN ReLU conv3x3 BN ReLU conv3x3 plus
+ *            the block input, or plus a strided 1x1 conv of the first BN-ReLU output when the
+ *            shape changes; BN ReLU, global average pool, fc.  No conv bias.  BN: batch statistics
+ *            per replica (biased variance), eps 1e-5, running statistics with momentum 0.1 and
+ *            unbiased variance.                                         default 32x32x3, 16/4/2 (WRN-16-4)
+ * Loss: mean over the replica's mini-batch of the softmax cross-entropy (Section 1.1).
+ * ReLU'(0) = 0.  maxpool2 = 2x2 window, stride 2, floor; gradient to the first maximum in
+ * row-major window order.
+ */
+typedef struct {
+  int32_t model;         /* parle_model */
+  int32_t n_replicas;    /* n >= 1 */
+  int32_t batch;         /* mini-batch per replica (ignored for FLAT) */
+  int32_t L;             /* inner steps per outer step (Section 3.1: 25); advisory, see parle_outer_step */
+  int32_t compute_bf16;  /* 0: fp32 activations and MFMA; 1: bf16 activations/weights in the
+                            contractions, fp32 accumulation, fp32 master state */
+  int32_t in_h, in_w, in_c, n_classes; /* 0 = model default */
+  int32_t arch[4];       /* model-specific sizes listed at parle_model; 0 = default */
+  int64_t n_params;      /* FLAT only: elements per replica; ignored otherwise */
+  float eta_inner;       /* eta'  of (8a) */
+  float eta_outer;       /* eta   of (8c) */
+  float momentum;        /* Nesterov momentum of the y^a and x^a updates (remark in Section 3): 0.9 */
+  float alpha;           /* averaging constant of (8b): 0.75 */
+  float weight_decay;    /* coefficient of the 0.5*||y||^2 regulariser inside f (Section 1.1) */
+  float gamma0, rho0;    /* initial multipliers g, r (paper: 1/100 and 1) */
+  float gamma_max, rho_max; /* caps on g, r (paper clips gamma at 1, rho at 0.1: caps 1 and 10) */
+  int64_t scoping_B;     /* B of rule (9), mini-batches in the data set; 0 = g, r stay constant */
+  int32_t xa_mode;       /* coefficient on (x^a - z^a) in (8c): 0 = g (unscaled local-entropy
+                            gradient of the scoping remark), 1 = 1 (equation as printed) */
+  int32_t xref_mode;     /* 0 = (8c) uses the mean of the current replicas; 1 = uses the stored
+                            reference, which is then refreshed from the replicas before the move */
+  int32_t reset_flags;   /* at the outer step: bit 0 z^a <- x^a, bit 1 momentum of y^a <- 0 */
+  int32_t fuse_outer;    /* 0 = replica-mean kernel then outer-update kernel; 1 = one kernel */
+} parle_config;
+
+typedef struct {
+  int64_t n_params;        /* parameters per replica */
+  int64_t n_pad;           /* row stride in elements: n_params rounded up to a multiple of 1024 */
+  int64_t state_bytes;     /* bytes of ONE [n, n_pad] fp32 tensor (x, y, z, vy, vx, grad each) */
+  int64_t shadow_bytes;    /* bytes of the [n, n_pad] bf16 copy of y; 0 when compute_bf16 == 0 */
+  int64_t bn_bytes;        /* bytes of the batch-norm running statistics; 0 without BN */
+  int64_t workspace_bytes; /* bytes of scratch the kernels need (activations, partial sums) */
+  int32_t n_segments;      /* entries parle_query_layout can return */
+  int32_t image_elems;     /* H*W*C of one input image; 0 for FLAT */
+} parle_sizes;
+
+typedef enum { PARLE_SEG_WEIGHT = 0, PARLE_SEG_BIAS = 1, PARLE_SEG_BN_GAMMA = 2, PARLE_SEG_BN_BETA = 3 } parle_seg_kind;
+
+typedef struct {
+  char name[32];      /* e.g. "conv1.w", "g2b1.bn1.g" */
+  int64_t offset;     /* first element inside a replica row */
+  int64_t size;       /* elements */
+  int32_t kind;       /* parle_seg_kind */
+  int32_t shape[4];   /* [Cout,kh,kw,Cin], [out,in,0,0] or [C,0,0,0] */
+  int32_t fan_in;     /* inputs feeding one output unit */
+} parle_segment;
+
+typedef struct {            /* DEVICE pointers, caller-owned, each 256-byte aligned */
+  float *x;                 /* [n, n_pad] replicas x^a; the caller fills it before parle_init */
+  float *y;                 /* [n, n_pad] inner iterates y^a */
+  float *z;                 /* [n, n_pad] running averages z^a */
+  float *vy;                /* [n, n_pad] momentum of y^a */
+  float *vx;                /* [n, n_pad] momentum of x^a */
+  float *grad;              /* [n, n_pad] grad f(y^a); written by the backward kernels, or by the caller (FLAT) */
+  float *x_ref;             /* [n_pad] reference x */
+  void *y_bf16;             /* [n, n_pad] bf16 copy of y, or NULL when compute_bf16 == 0 */
+  void *bn_stats;           /* bn_bytes: per replica, per BN layer in order, mean[C] then var[C] (fp32); or NULL */
+  void *workspace;          /* workspace_bytes of scratch; contents are undefined between calls */
+} parle_buffers;
+
+/* Sizes implied by a configuration.  Pure host code; works without a GPU. */
+parle_status parle_query_sizes(const parle_config *cfg, parle_sizes *out);
+
+/* Segment `index` (0 <= index < n_segments) of the packing of one replica row.  Pure host code. */
+parle_status parle_query_layout(const parle_config *cfg, int32_t index, parle_segment *out);
+
+/*
+ * Start of training (Section 3): takes x (all n rows filled by the caller, padding zero) and
+ * enqueues y <- x, z <- x, vy <- 0, vx <- 0, grad <- 0, x_ref <- replica mean (8d), bf16 copy,
+ * BN running statistics <- (0, 1); sets k = 0, g = gamma0, r = rho0.
+ * `hip_stream` is a hipStream_t (NULL = the default stream).  *out is freed by parle_destroy.
+ */
+parle_status parle_init(const parle_config *cfg, const parle_buffers *buf, void *hip_stream, parle_ctx **out);
+
+/*
+ * One inner step for all replicas: forward, loss, backward into buffers.grad, then
+ *   d = grad + weight_decay*y + g*(y - x);  vy <- mu*vy + d;  y <- y - eta_inner*(d + mu*vy)   (8a)
+ *   z <- alpha*z + (1 - alpha)*y                                                               (8b)
+ * images_dev: [n, batch, H, W, C] fp32, labels_dev: [n, batch] int32 in [0, classes);
+ * loss_dev: [n] fp32 mean loss of each replica at y before the step, or NULL.
+ * FLAT: images_dev and labels_dev must be NULL; only the update runs on the caller's grad.
+ */
+parle_status parle_inner_step(parle_ctx *ctx, const float *images_dev, const int32_t *labels_dev, float *loss_dev);
+
+/*
+ * The outer step, meant to follow every L inner steps (any count >= 1 is accepted, else ESTATE):
+ *   x_ref <- (1/n) sum_a x^a                                                   (8d), eta'' = rho/n
+ *   d = c_z*(x^a - z^a) + r*(x^a - x_ref);  vx <- mu*vx + d;  x^a <- x^a - eta_outer*(d + mu*vx)   (8c)
+ *   y^a <- x^a (and z^a, vy per reset_flags), bf16 copy refreshed
+ *   g <- min(g / (1 - 1/(2B)), gamma_max), r likewise                         rule (9)
+ */
+parle_status parle_outer_step(parle_ctx *ctx);
+
+/*
+ * Forward only, at the reference (which = -1; BN uses running statistics averaged over the
+ * replicas) or at replica `which`'s x^a.  images_dev [count, H, W, C], labels_dev [count],
+ * 1 <= count <= n*batch.  Writes to HOST: mean loss, number of misclassified samples, and (if
+ * not NULL) spread = sum_a ||x^a - x_ref||^2.  Blocks until the stream is idle.
+ * FLAT: images/labels must be NULL, count 0; only spread is produced.
+ */
+parle_status parle_eval(parle_ctx *ctx, int32_t which, const float *images_dev, const int32_t *labels_dev,
+                        int32_t count, float *loss_host, int32_t *n_err_host, float *spread_host);
+
+/* Scalars a caller needs to checkpoint / resume: inner steps taken, completed outer steps, g, r. */
+parle_status parle_get_state(const parle_ctx *ctx, int64_t *k, int64_t *outer_done, float *g, float *r);
+parle_status parle_set_state(parle_ctx *ctx, int64_t k, int64_t outer_done, float g, float r);
+
+/* Text of the last error on this context (or of the last failed init when ctx == NULL). */
+const char *parle_last_error(const parle_ctx *ctx);
+
+/* Frees the host context.  Never touches the caller's device buffers.  NULL is allowed. */
+void parle_destroy(parle_ctx *ctx);
+
+/* ------------------------------------------------------------------------------------------
+ * Single-kernel entry points (the steps above, one launch each, on arbitrary caller state).
+ * All pointers are DEVICE pointers, 16-byte aligned; n_pad must be a multiple of 4 and
+ * n*n_pad < 2^40.  Enqueued on `hip_stream`; asynchronous.
+ * ------------------------------------------------------------------------------------------ */
+
+/* (8a) + Nesterov + (8b) on [n, n_pad]; y_bf16 may be NULL. */
+parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, const float *x,
+                                  float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
+                                  float alpha, float weight_decay, float g);
+
+/* (8d) with eta'' = rho/n: x_ref[i] = (sum_{a=0..n-1} x[a][i]) / n, summed in replica order. */
+parle_status parle_k_replica_mean(void *hip_stream, int32_t n, int64_t n_pad, const float *x, float *x_ref);
+
+/* (8c) + Nesterov + reset.  c_z is the coefficient on (x - z).  fuse_mean = 1 computes the
+ * replica mean inside the kernel and writes it to x_ref; lagged = 1 applies xref_mode 1. */
+parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, float *x, float *z, float *vx,
+                                  float *y, float *vy, float *x_ref, void *y_bf16, float eta_outer, float momentum,
+                                  float c_z, float r, int32_t reset_flags, int32_t fuse_mean, int32_t lagged);
+
+/* sum_a ||x^a - x_ref||^2 -> out_dev[0] (fp32).  partial_dev: scratch of >= 4096 doubles. */
+parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
+                            double *partial_dev, float *out_dev);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARLE_H */

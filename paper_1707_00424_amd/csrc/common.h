@@ -1,0 +1,39 @@
+// Shared host/device helpers of the Parle library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/parle.h"
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef unsigned short us4 __attribute__((ext_vector_type(4)));
+typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+#define PARLE_WAVE 64
+
+// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ unsigned short f32_to_bf16(float f) {
+  unsigned int u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float(((unsigned int)h) << 16); }
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) v += __shfl_down(v, off, PARLE_WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) v += __shfl_down(v, off, PARLE_WAVE);
+  return v;
+}
+
+static inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// fp32 -> bf16 (round to nearest even) copy of `count` elements (count % 4 == 0), enqueued on `st`.
+parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst, int64_t count);

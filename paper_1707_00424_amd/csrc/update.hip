@@ -1,0 +1,397 @@
+// Memory-bound kernels of the Parle step: fused inner update (8a)+(8b), replica mean (8d),
+// fused outer update (8c) + reset, ensemble spread.  Every tensor is streamed once with 16-byte
+// accesses; nothing is reused, so loads and stores are non-temporal.
+#include <stdlib.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+struct Tuning {
+  int inner_unroll;   // float4 per thread per trip
+  int blocks_per_cu;  // 0 = one trip per thread (grid covers the tensor)
+  int nontemporal;
+};
+
+const Tuning &tuning() {
+  static Tuning t = [] {
+    Tuning v{2, 0, 1};
+    if (const char *s = getenv("PARLE_UPD_UNROLL")) v.inner_unroll = atoi(s);
+    if (const char *s = getenv("PARLE_UPD_BLOCKS_PER_CU")) v.blocks_per_cu = atoi(s);
+    if (const char *s = getenv("PARLE_UPD_NT")) v.nontemporal = atoi(s);
+    return v;
+  }();
+  return t;
+}
+
+template <bool NT>
+__device__ __forceinline__ f4 ld4(const f4 *p) {
+  if (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st4(f4 *p, f4 v) {
+  if (NT)
+    __builtin_nontemporal_store(v, p);
+  else
+    *p = v;
+}
+__device__ __forceinline__ us4 to_bf16x4(f4 v) {
+  us4 o;
+  o.x = f32_to_bf16(v.x);
+  o.y = f32_to_bf16(v.y);
+  o.z = f32_to_bf16(v.z);
+  o.w = f32_to_bf16(v.w);
+  return o;
+}
+
+// ---------------------------------------------------------------------------------------------
+// (8a) with Nesterov momentum, then (8b).  One flat pass over n*n_pad elements.
+// ---------------------------------------------------------------------------------------------
+template <int U, bool NT, bool BF>
+__global__ __launch_bounds__(kThreads) void k_inner_update(const f4 *__restrict__ G, const f4 *__restrict__ X,
+                                                           f4 *__restrict__ Y, f4 *__restrict__ VY,
+                                                           f4 *__restrict__ Z, us4 *__restrict__ Y16, int64_t n4,
+                                                           float eta, float mu, float alpha, float wd, float g) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const float one_m_alpha = 1.0f - alpha;
+  for (int64_t q0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; q0 < n4; q0 += stride * U) {
+    f4 gr[U], x[U], y[U], v[U], z[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      if (q < n4) {
+        gr[u] = ld4<NT>(G + q);
+        x[u] = ld4<NT>(X + q);
+        y[u] = ld4<NT>(Y + q);
+        v[u] = ld4<NT>(VY + q);
+        z[u] = ld4<NT>(Z + q);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * stride;
+      if (q < n4) {
+        const f4 d = gr[u] + wd * y[u] + g * (y[u] - x[u]);
+        const f4 vn = mu * v[u] + d;
+        const f4 yn = y[u] - eta * (d + mu * vn);
+        const f4 zn = alpha * z[u] + one_m_alpha * yn;
+        st4<NT>(VY + q, vn);
+        st4<NT>(Y + q, yn);
+        st4<NT>(Z + q, zn);
+        if (BF) __builtin_nontemporal_store(to_bf16x4(yn), Y16 + q);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// (8d) with eta'' = rho/n: column mean of the stacked replicas, summed in replica order.
+// ---------------------------------------------------------------------------------------------
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void k_replica_mean(const f4 *__restrict__ X, f4 *__restrict__ XR, int n,
+                                                           int64_t np4) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const float fn = (float)n;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+    f4 s = ld4<NT>(X + q);
+    for (int a = 1; a < n; ++a) s += ld4<NT>(X + (int64_t)a * np4 + q);
+    XR[q] = s / fn;  // kept cacheable: the outer update reads it right away
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// (8c) with Nesterov momentum and the reset of y (z, vy per flags).  blockIdx.y = replica.
+// ---------------------------------------------------------------------------------------------
+template <bool NT, bool BF>
+__global__ __launch_bounds__(kThreads) void k_outer_update(f4 *__restrict__ X, f4 *__restrict__ Z,
+                                                           f4 *__restrict__ VX, f4 *__restrict__ Y,
+                                                           f4 *__restrict__ VY, const f4 *__restrict__ XR,
+                                                           us4 *__restrict__ Y16, int64_t np4, float eta, float mu,
+                                                           float cz, float r, int reset_flags) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const int64_t base = (int64_t)blockIdx.y * np4;
+  const f4 zero = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+    const f4 x = ld4<NT>(X + base + q);
+    const f4 z = ld4<NT>(Z + base + q);
+    const f4 v = ld4<NT>(VX + base + q);
+    const f4 xr = XR[q];
+    const f4 d = cz * (x - z) + r * (x - xr);
+    const f4 vn = mu * v + d;
+    const f4 xn = x - eta * (d + mu * vn);
+    st4<NT>(VX + base + q, vn);
+    st4<NT>(X + base + q, xn);
+    st4<NT>(Y + base + q, xn);
+    if (reset_flags & 1) st4<NT>(Z + base + q, xn);
+    if (reset_flags & 2) st4<NT>(VY + base + q, zero);
+    if (BF) __builtin_nontemporal_store(to_bf16x4(xn), Y16 + base + q);
+  }
+}
+
+// Same update with the replica mean formed in registers: every x^a[i] is read once, the mean is
+// written to x_ref, and no second pass over x is needed.  N > 0: compile-time replica count.
+template <int N, bool NT, bool BF>
+__global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4 *__restrict__ Z, f4 *__restrict__ VX,
+                                                          f4 *__restrict__ Y, f4 *__restrict__ VY,
+                                                          f4 *__restrict__ XR, us4 *__restrict__ Y16, int n_rt,
+                                                          int64_t np4, float eta, float mu, float cz, float r,
+                                                          int reset_flags, int lagged) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const f4 zero = {0.f, 0.f, 0.f, 0.f};
+  const int n = N > 0 ? N : n_rt;
+  const float fn = (float)n;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+    f4 xs[N > 0 ? N : 1];
+    f4 s;
+    if (N > 0) {
+#pragma unroll
+      for (int a = 0; a < N; ++a) xs[a] = ld4<NT>(X + (int64_t)a * np4 + q);
+      s = xs[0];
+#pragma unroll
+      for (int a = 1; a < N; ++a) s += xs[a];
+    } else {
+      s = X[q];
+      for (int a = 1; a < n; ++a) s += X[(int64_t)a * np4 + q];
+    }
+    const f4 mean = s / fn;
+    const f4 xr = lagged ? XR[q] : mean;
+    st4<NT>(XR + q, mean);
+#pragma unroll
+    for (int a = 0; a < n; ++a) {
+      const int64_t o = (int64_t)a * np4 + q;
+      const f4 x = N > 0 ? xs[N > 0 ? a : 0] : X[o];
+      const f4 z = ld4<NT>(Z + o);
+      const f4 v = ld4<NT>(VX + o);
+      const f4 d = cz * (x - z) + r * (x - xr);
+      const f4 vn = mu * v + d;
+      const f4 xn = x - eta * (d + mu * vn);
+      st4<NT>(VX + o, vn);
+      st4<NT>(X + o, xn);
+      st4<NT>(Y + o, xn);
+      if (reset_flags & 1) st4<NT>(Z + o, xn);
+      if (reset_flags & 2) st4<NT>(VY + o, zero);
+      if (BF) __builtin_nontemporal_store(to_bf16x4(xn), Y16 + o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// sum_a ||x^a - x_ref||^2: per-thread fp32 partial over a few elements, fp64 from the wavefront
+// reduction on; per-block partials are summed by one block in a fixed order (deterministic).
+// ---------------------------------------------------------------------------------------------
+constexpr int kSpreadBlocks = 4096;
+
+__global__ __launch_bounds__(kThreads) void k_spread_partial(const f4 *__restrict__ X, const f4 *__restrict__ XR,
+                                                             int n, int64_t np4, double *__restrict__ partial) {
+  __shared__ double lds[kThreads / PARLE_WAVE];
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  double acc = 0.0;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+    const f4 xr = XR[q];
+    float part = 0.f;
+    for (int a = 0; a < n; ++a) {
+      const f4 d = X[(int64_t)a * np4 + q] - xr;
+      part += d.x * d.x + d.y * d.y + d.z * d.z + d.w * d.w;
+    }
+    acc += (double)part;
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) lds[threadIdx.x / PARLE_WAVE] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int w = 0; w < kThreads / PARLE_WAVE; ++w) s += lds[w];
+    partial[blockIdx.x] = s;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_spread_final(const double *__restrict__ partial, int count,
+                                                           float *__restrict__ out) {
+  __shared__ double lds[kThreads / PARLE_WAVE];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < count; i += kThreads) acc += partial[i];
+  acc = wave_sum(acc);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) lds[threadIdx.x / PARLE_WAVE] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int w = 0; w < kThreads / PARLE_WAVE; ++w) s += lds[w];
+    out[0] = (float)s;
+  }
+}
+
+int num_cus() {
+  static int cus = [] {
+    int dev = 0, v = 256;
+    if (hipGetDevice(&dev) == hipSuccess) {
+      int q = 0;
+      if (hipDeviceGetAttribute(&q, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && q > 0) v = q;
+    }
+    return v;
+  }();
+  return cus;
+}
+
+int grid_for(int64_t items, int per_thread_trip) {
+  const Tuning &t = tuning();
+  int64_t need = (items + (int64_t)kThreads * per_thread_trip - 1) / ((int64_t)kThreads * per_thread_trip);
+  if (need < 1) need = 1;
+  if (t.blocks_per_cu > 0) {
+    const int64_t cap = (int64_t)num_cus() * t.blocks_per_cu;
+    if (need > cap) need = cap;
+  }
+  if (need > 0x7fffffff) need = 0x7fffffff;
+  return (int)need;
+}
+
+parle_status check_flat_args(int32_t n, int64_t n_pad) {
+  if (n < 1 || n_pad < 4 || (n_pad & 3)) return PARLE_EINVAL;
+  if ((double)n * (double)n_pad >= 1099511627776.0) return PARLE_ESIZE;
+  return PARLE_OK;
+}
+
+parle_status launched() { return hipGetLastError() == hipSuccess ? PARLE_OK : PARLE_EHIP; }
+
+}  // namespace
+
+namespace {
+__global__ __launch_bounds__(kThreads) void k_to_bf16(const f4 *__restrict__ src, us4 *__restrict__ dst, int64_t n4) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < n4; q += stride) dst[q] = to_bf16x4(src[q]);
+}
+}  // namespace
+
+parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst, int64_t count) {
+  if (count < 4 || (count & 3) || !src || !dst) return PARLE_EINVAL;
+  const int64_t n4 = count / 4;
+  hipLaunchKernelGGL(k_to_bf16, dim3(grid_for(n4, 1)), dim3(kThreads), 0, st, (const f4 *)src, (us4 *)dst, n4);
+  return launched();
+}
+
+extern "C" {
+
+parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, const float *x,
+                                  float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
+                                  float alpha, float weight_decay, float g) {
+  if (parle_status s = check_flat_args(n, n_pad)) return s;
+  if (!grad || !x || !y || !vy || !z) return PARLE_EINVAL;
+  if (!aligned_to(grad, 16) || !aligned_to(x, 16) || !aligned_to(y, 16) || !aligned_to(vy, 16) || !aligned_to(z, 16) ||
+      !aligned_to(y_bf16, 8))
+    return PARLE_EALIGN;
+  const int64_t n4 = (int64_t)n * n_pad / 4;
+  const Tuning &t = tuning();
+  hipStream_t st = (hipStream_t)hip_stream;
+#define LAUNCH_INNER(U, NT, BF)                                                                                   \
+  hipLaunchKernelGGL((k_inner_update<U, NT, BF>), dim3(grid_for(n4, U)), dim3(kThreads), 0, st, (const f4 *)grad, \
+                     (const f4 *)x, (f4 *)y, (f4 *)vy, (f4 *)z, (us4 *)y_bf16, n4, eta_inner, momentum, alpha,    \
+                     weight_decay, g)
+#define PICK_INNER(U)                   \
+  do {                                  \
+    if (t.nontemporal) {                \
+      if (y_bf16)                       \
+        LAUNCH_INNER(U, true, true);    \
+      else                              \
+        LAUNCH_INNER(U, true, false);   \
+    } else {                            \
+      if (y_bf16)                       \
+        LAUNCH_INNER(U, false, true);   \
+      else                              \
+        LAUNCH_INNER(U, false, false);  \
+    }                                   \
+  } while (0)
+  switch (t.inner_unroll) {
+    case 1: PICK_INNER(1); break;
+    case 4: PICK_INNER(4); break;
+    default: PICK_INNER(2); break;
+  }
+#undef PICK_INNER
+#undef LAUNCH_INNER
+  return launched();
+}
+
+parle_status parle_k_replica_mean(void *hip_stream, int32_t n, int64_t n_pad, const float *x, float *x_ref) {
+  if (parle_status s = check_flat_args(n, n_pad)) return s;
+  if (!x || !x_ref) return PARLE_EINVAL;
+  if (!aligned_to(x, 16) || !aligned_to(x_ref, 16)) return PARLE_EALIGN;
+  const int64_t np4 = n_pad / 4;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (tuning().nontemporal)
+    hipLaunchKernelGGL((k_replica_mean<true>), dim3(grid_for(np4, 1)), dim3(kThreads), 0, st, (const f4 *)x,
+                       (f4 *)x_ref, n, np4);
+  else
+    hipLaunchKernelGGL((k_replica_mean<false>), dim3(grid_for(np4, 1)), dim3(kThreads), 0, st, (const f4 *)x,
+                       (f4 *)x_ref, n, np4);
+  return launched();
+}
+
+parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, float *x, float *z, float *vx,
+                                  float *y, float *vy, float *x_ref, void *y_bf16, float eta_outer, float momentum,
+                                  float c_z, float r, int32_t reset_flags, int32_t fuse_mean, int32_t lagged) {
+  if (parle_status s = check_flat_args(n, n_pad)) return s;
+  if (!x || !z || !vx || !y || !vy || !x_ref) return PARLE_EINVAL;
+  if (n > 65535) return PARLE_ESIZE;
+  if (!aligned_to(x, 16) || !aligned_to(z, 16) || !aligned_to(vx, 16) || !aligned_to(y, 16) || !aligned_to(vy, 16) ||
+      !aligned_to(x_ref, 16) || !aligned_to(y_bf16, 8))
+    return PARLE_EALIGN;
+  if (lagged && !fuse_mean) return PARLE_EINVAL;  // the unfused path takes whatever x_ref holds
+  const int64_t np4 = n_pad / 4;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool nt = tuning().nontemporal != 0;
+  if (!fuse_mean) {
+    dim3 grid(grid_for(np4, 1), n);
+#define LAUNCH_OUTER(NT, BF)                                                                                       \
+  hipLaunchKernelGGL((k_outer_update<NT, BF>), grid, dim3(kThreads), 0, st, (f4 *)x, (f4 *)z, (f4 *)vx, (f4 *)y,   \
+                     (f4 *)vy, (const f4 *)x_ref, (us4 *)y_bf16, np4, eta_outer, momentum, c_z, r, reset_flags)
+    if (nt) {
+      if (y_bf16) LAUNCH_OUTER(true, true); else LAUNCH_OUTER(true, false);
+    } else {
+      if (y_bf16) LAUNCH_OUTER(false, true); else LAUNCH_OUTER(false, false);
+    }
+#undef LAUNCH_OUTER
+    return launched();
+  }
+  dim3 grid(grid_for(np4, 1));
+#define LAUNCH_FUSED(N, BF)                                                                                          \
+  hipLaunchKernelGGL((k_outer_fused<N, true, BF>), grid, dim3(kThreads), 0, st, (f4 *)x, (f4 *)z, (f4 *)vx, (f4 *)y, \
+                     (f4 *)vy, (f4 *)x_ref, (us4 *)y_bf16, n, np4, eta_outer, momentum, c_z, r, reset_flags, lagged)
+#define PICK_FUSED(N)                                               \
+  case N:                                                           \
+    if (y_bf16) LAUNCH_FUSED(N, true); else LAUNCH_FUSED(N, false); \
+    break
+  switch (n) {
+    PICK_FUSED(1);
+    PICK_FUSED(2);
+    PICK_FUSED(3);
+    PICK_FUSED(4);
+    PICK_FUSED(5);
+    PICK_FUSED(6);
+    PICK_FUSED(7);
+    PICK_FUSED(8);
+    default:
+      if (y_bf16) LAUNCH_FUSED(0, true); else LAUNCH_FUSED(0, false);
+      break;
+  }
+#undef PICK_FUSED
+#undef LAUNCH_FUSED
+  return launched();
+}
+
+parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
+                            double *partial_dev, float *out_dev) {
+  if (parle_status s = check_flat_args(n, n_pad)) return s;
+  if (!x || !x_ref || !partial_dev || !out_dev) return PARLE_EINVAL;
+  if (!aligned_to(x, 16) || !aligned_to(x_ref, 16) || !aligned_to(partial_dev, 8)) return PARLE_EALIGN;
+  const int64_t np4 = n_pad / 4;
+  int64_t blocks = (np4 + kThreads - 1) / kThreads;
+  if (blocks > kSpreadBlocks) blocks = kSpreadBlocks;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(k_spread_partial, dim3((int)blocks), dim3(kThreads), 0, st, (const f4 *)x, (const f4 *)x_ref, n,
+                     np4, partial_dev);
+  hipLaunchKernelGGL(k_spread_final, dim3(1), dim3(kThreads), 0, st, (const double *)partial_dev, (int)blocks, out_dev);
+  return launched();
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/parle.h declares, and its
+host-side logic (sizes, packing, argument validation) agrees with the oracle's independent layout."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import nets
+from paper_1707_00424_amd import binding as pb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "parle.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(parle_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = pb.lib()
+    names = _declared_functions()
+    assert "parle_init" in names and "parle_inner_step" in names and "parle_outer_step" in names
+    assert "parle_eval" in names
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(names) == pb.EXPORTS
+
+
+def test_flat_sizes():
+    s = pb.parle_query_sizes(pb.make_config(n_replicas=8, n_params=36_500_000))
+    assert s.n_params == 36_500_000 and s.n_pad % 1024 == 0 and 0 <= s.n_pad - s.n_params < 1024
+    assert s.state_bytes == 8 * s.n_pad * 4 and s.shadow_bytes == 0 and s.bn_bytes == 0
+    s = pb.parle_query_sizes(pb.make_config(n_replicas=2, n_params=1024, compute_bf16=1))
+    assert s.n_pad == 1024 and s.shadow_bytes == 2 * 1024 * 2
+
+
+ORACLE_ARCH = {
+    pb.MODEL_MLP: ("mlp", {}),
+    pb.MODEL_LENET: ("lenet", {}),
+    pb.MODEL_ALLCNN_C: ("allcnn", {}),
+    pb.MODEL_WRN: ("wrn", {}),
+}
+
+
+@pytest.mark.parametrize("model", [pb.MODEL_MLP, pb.MODEL_LENET, pb.MODEL_ALLCNN_C, pb.MODEL_WRN])
+def test_layout_matches_oracle_default_sizes(model):
+    cfg = pb.make_config(model=model, n_replicas=3, batch=128)
+    segs = pb.parle_query_layout(cfg)
+    ref = nets.layout(nets.arch(ORACLE_ARCH[model][0]))
+    assert len(segs) == len(ref)
+    off = 0
+    for s, r in zip(segs, ref):
+        assert s["name"] == r["name"] and s["shape"] == r["shape"] and s["kind"] == r["kind"]
+        assert s["fan_in"] == r["fan_in"] and s["offset"] == off and s["size"] == int(np.prod(r["shape"]))
+        off += s["size"]
+    sizes = pb.parle_query_sizes(cfg)
+    assert sizes.n_params == off == nets.n_params(nets.arch(ORACLE_ARCH[model][0]))
+
+
+def test_layout_matches_oracle_small_sizes():
+    cases = [
+        (pb.make_config(model=pb.MODEL_MLP, n_replicas=1, batch=4, in_h=3, in_w=2, in_c=1, n_classes=3, arch=(5,)),
+         nets.arch("mlp", H=3, W=2, C=1, hidden=5, classes=3)),
+        (pb.make_config(model=pb.MODEL_LENET, n_replicas=1, batch=4, in_h=10, in_w=10, in_c=1, n_classes=4,
+                        arch=(2, 3, 3, 7)), nets.arch("lenet", H=10, W=10, C=1, c1=2, c2=3, k=3, fc=7, classes=4)),
+        (pb.make_config(model=pb.MODEL_ALLCNN_C, n_replicas=1, batch=4, in_h=8, in_w=8, in_c=2, n_classes=3,
+                        arch=(3, 4)), nets.arch("allcnn", H=8, W=8, C=2, ca=3, cb=4, classes=3)),
+        (pb.make_config(model=pb.MODEL_WRN, n_replicas=1, batch=4, in_h=8, in_w=8, in_c=2, n_classes=3,
+                        arch=(2, 2, 1)), nets.arch("wrn", H=8, W=8, C=2, base=2, widen=2, nb=1, classes=3)),
+    ]
+    for cfg, a in cases:
+        segs = pb.parle_query_layout(cfg)
+        ref = nets.layout(a)
+        assert [(s["name"], s["shape"], s["kind"], s["fan_in"]) for s in segs] == \
+               [(r["name"], r["shape"], r["kind"], r["fan_in"]) for r in ref]
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n_replicas=0, n_params=10), dict(n_replicas=1, n_params=0), dict(n_replicas=1, n_params=8, L=0),
+    dict(n_replicas=1, n_params=8, eta_inner=-1.0), dict(n_replicas=1, n_params=8, momentum=1.0),
+    dict(n_replicas=1, n_params=8, alpha=1.5), dict(n_replicas=1, n_params=8, xa_mode=2),
+    dict(n_replicas=1, n_params=8, reset_flags=4), dict(n_replicas=1, n_params=8, xref_mode=1, fuse_outer=0),
+    dict(n_replicas=1, n_params=8, gamma0=float("nan")), dict(model=9, n_replicas=1, n_params=8),
+    dict(model=pb.MODEL_MLP, n_replicas=1, batch=0),
+    dict(model=pb.MODEL_LENET, n_replicas=1, batch=2, in_h=6, in_w=6),
+])
+def test_bad_configurations_are_rejected(kw):
+    with pytest.raises(pb.ParleError) as e:
+        pb.parle_query_sizes(pb.make_config(**kw))
+    assert e.value.status == pb.PARLE_EINVAL
+
+
+def test_too_large_is_esize():
+    with pytest.raises(pb.ParleError) as e:
+        pb.parle_query_sizes(pb.make_config(n_replicas=65535, n_params=2 ** 36))
+    assert e.value.status == pb.PARLE_ESIZE
+
+
+def test_null_arguments_do_not_crash():
+    L = pb.lib()
+    assert L.parle_query_sizes(None, None) == pb.PARLE_EINVAL
+    assert L.parle_outer_step(None) == pb.PARLE_EINVAL
+    assert L.parle_inner_step(None, None, None, None) == pb.PARLE_EINVAL
+    L.parle_destroy(None)
+    cfg = pb.make_config(n_replicas=2, n_params=100)
+    h = C.c_void_p()
+    assert L.parle_init(C.byref(cfg), None, None, C.byref(h)) == pb.PARLE_EINVAL
+    bufs = pb.parle_buffers()              # all NULL
+    assert L.parle_init(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == pb.PARLE_EINVAL
+    assert b"NULL" in L.parle_last_error(None)
+    bufs = pb.parle_buffers(*([256 + 8] * 10))   # misaligned fake pointers: rejected before any use
+    assert L.parle_init(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == pb.PARLE_EALIGN
