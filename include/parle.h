@@ -213,6 +213,31 @@ parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, fl
 parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
                             double *partial_dev, float *out_dev);
 
+/* ------------------------------------------------------------------------------------------
+ * The replica-grouped convolution kernels behind grad f(y^a) of (8a), one launch each.
+ * Tensors are DEVICE pointers, 16-byte aligned, channels-last, one block per replica:
+ *   x  [n][batch, h, w, cin]      w  [n][cout, k, k, cin]      y, dy [n][batch, ho, wo, cout]
+ * with ho = (h + 2 pad - k)/stride + 1.  dtype 0: fp32 tensors; dtype 1: bf16 tensors (raw 16-bit),
+ * products accumulated in fp32 on the MFMA units.  stride is 1 or 2.  A fully connected layer is
+ * h = w = k = 1.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t dtype, n, batch, h, w, cin, cout, k, stride, pad;
+} parle_conv_desc;
+
+/* y = [relu]( conv(x, w) + bias + resid ); bias [n][cout] fp32 or NULL; resid like y or NULL. */
+parle_status parle_k_conv_forward(void *hip_stream, const parle_conv_desc *desc, const void *x, const void *w,
+                                  const float *bias, const void *resid, int32_t relu, void *y);
+/* dx (+)= conv^T(dy, w), multiplied by (relu_mask > 0) when relu_mask (like x) is given.
+ * wt_scratch: n*cout*k*k*cin elements of the tensor dtype (receives the transposed weights). */
+parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *w,
+                                        const void *relu_mask, int32_t accumulate, void *wt_scratch, void *dx);
+/* dw [n][cout, k, k, cin] fp32 = sum over batch and positions of dy (x) x.  The sum is split over
+ * workgroups and reduced in a fixed order; scratch must hold parle_k_conv_scratch_bytes(desc). */
+parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *x,
+                                          float *scratch, int64_t scratch_bytes, float *dw);
+int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc); /* -1 on a bad descriptor */
+
 #ifdef __cplusplus
 }
 #endif

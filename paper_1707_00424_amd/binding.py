@@ -49,6 +49,10 @@ class parle_buffers(C.Structure):
                 ("workspace", C.c_void_p)]
 
 
+class parle_conv_desc(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("dtype", "n", "batch", "h", "w", "cin", "cout", "k", "stride", "pad")]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -69,8 +73,14 @@ _SIGNATURES = {
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float,
                              C.c_int32, C.c_int32, C.c_int32],
     "parle_k_spread": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_k_conv_forward": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_int32, C.c_void_p],
+    "parle_k_conv_backward_data": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_int32, C.c_void_p, C.c_void_p],
+    "parle_k_conv_backward_weight": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_void_p],
 }
-EXPORTS = sorted(list(_SIGNATURES) + ["parle_last_error", "parle_destroy"])
+EXPORTS = sorted(list(_SIGNATURES) + ["parle_last_error", "parle_destroy", "parle_k_conv_scratch_bytes"])
 
 
 def lib():
@@ -89,6 +99,8 @@ def lib():
         L.parle_last_error.restype = C.c_char_p
         L.parle_destroy.argtypes = [C.c_void_p]
         L.parle_destroy.restype = None
+        L.parle_k_conv_scratch_bytes.argtypes = [C.POINTER(parle_conv_desc)]
+        L.parle_k_conv_scratch_bytes.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -166,6 +178,26 @@ def parle_k_outer_update(x, z, vx, y, vy, x_ref, y_bf16, eta_outer, momentum, c_
 def parle_k_spread(x, x_ref, partial, out, stream=None):
     n, n_pad = x.shape
     _check(lib().parle_k_spread(_stream_handle(stream), n, n_pad, _ptr(x), _ptr(x_ref), _ptr(partial), _ptr(out)))
+
+
+def parle_k_conv_forward(desc, x, w, bias, resid, relu, y, stream=None):
+    _check(lib().parle_k_conv_forward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(resid),
+                                      int(relu), _ptr(y)))
+
+
+def parle_k_conv_backward_data(desc, dy, w, relu_mask, accumulate, wt_scratch, dx, stream=None):
+    _check(lib().parle_k_conv_backward_data(_stream_handle(stream), C.byref(desc), _ptr(dy), _ptr(w), _ptr(relu_mask),
+                                            int(accumulate), _ptr(wt_scratch), _ptr(dx)))
+
+
+def parle_k_conv_backward_weight(desc, dy, x, scratch, dw, stream=None):
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(lib().parle_k_conv_backward_weight(_stream_handle(stream), C.byref(desc), _ptr(dy), _ptr(x), _ptr(scratch),
+                                              nbytes, _ptr(dw)))
+
+
+def parle_k_conv_scratch_bytes(desc) -> int:
+    return int(lib().parle_k_conv_scratch_bytes(C.byref(desc)))
 
 
 class Parle:

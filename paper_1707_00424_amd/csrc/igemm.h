@@ -1,0 +1,94 @@
+// Replica-grouped implicit-GEMM convolutions on MFMA (gfx950): forward / backward-data share one
+// gather kernel, backward-weight is a split-K kernel.  Fully connected layers are 1x1 convolutions
+// on a 1x1 image.  blockIdx.z walks the replicas (and the K-splits of backward-weight).
+#pragma once
+#include "common.h"
+
+// n / d for 0 <= n < 2^31 by multiply-high (no integer division on the device).
+struct FastDiv {
+  uint32_t d, magic, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t s = 0;
+  while ((1u << s) < d) ++s;
+  f.shift = 31 + s;
+  f.magic = (uint32_t)((((uint64_t)1 << (31 + s)) + d - 1) / d);
+  return f;
+}
+
+// Rows m = (b, p, q) over a P x Q grid; contraction index k = (r, s, c) over an R x S window and
+// Cc channels of a channels-last tensor [*, Hin, Win, Cc].  Tap position along h:
+//   t = p*sp + off + r*sr;  valid iff t >= 0, t divisible by 2^dshift, (t >> dshift) < Hin
+// forward conv:   sp = stride, off = -pad, sr = +1, dshift = 0   (gathers the layer input)
+// backward data:  sp = 1, off = +pad, sr = -1, dshift = log2(stride) (gathers the output gradient)
+struct ConvGeom {
+  int Hin, Win, Cc;
+  int P, Q;
+  int R, S;
+  int sp, off, sr, dshift;
+  int M, N, K;  // per replica: rows, output columns, contraction length (K = R*S*Cc)
+  FastDiv dPQ, dQ, dCc, dS;
+};
+
+struct GemmIO {
+  const void *in;    // gathered tensor
+  long long in_rs;   // replica stride, elements
+  const void *w;     // [N][K] row-major
+  long long w_rs;
+  void *out;         // [M][ldc]
+  long long out_rs;
+  int ldc;
+  const float *bias;  // [N] fp32 or NULL
+  long long bias_rs;
+  const void *resid;  // [M][ldc], added before the ReLU, or NULL
+  long long resid_rs;
+  const void *mask;   // [M][ldc]: result multiplied by (mask > 0), or NULL
+  long long mask_rs;
+  int relu, accumulate;
+  int vecA, vecB;     // 16-byte loads allowed for the gathered operand / the weight matrix
+};
+
+struct WgradIO {
+  const void *dy;  // [M][N] output gradient
+  long long dy_rs;
+  const void *x;   // layer input, gathered with the forward geometry
+  long long x_rs;
+  float *out;      // [N][K] fp32 per (replica, split)
+  long long out_rs, split_stride;
+  int splits, chunk;  // K-splits over M and rows of M per split (multiple of 32)
+  int pairA, pairB;   // packed loads allowed for dy / x
+};
+
+// A convolution layer as the kernels see it: [B, H, W, Cin] -> [B, Ho, Wo, Cout], R x R window.
+struct ConvShape {
+  int B, H, W, Cin, Cout, R, stride, pad;
+  int Ho() const { return (H + 2 * pad - R) / stride + 1; }
+  int Wo() const { return (W + 2 * pad - R) / stride + 1; }
+};
+inline ConvGeom conv_fwd_geom(const ConvShape &c) {
+  ConvGeom g{};
+  g.Hin = c.H, g.Win = c.W, g.Cc = c.Cin;
+  g.P = c.Ho(), g.Q = c.Wo(), g.R = c.R, g.S = c.R;
+  g.sp = c.stride, g.off = -c.pad, g.sr = 1, g.dshift = 0;
+  g.M = c.B * g.P * g.Q, g.N = c.Cout, g.K = c.R * c.R * c.Cin;
+  g.dPQ = make_fastdiv(g.P * g.Q), g.dQ = make_fastdiv(g.Q), g.dCc = make_fastdiv(g.Cc), g.dS = make_fastdiv(g.S);
+  return g;
+}
+// Gradient w.r.t. the input: gathers the output gradient; stride must be 1 or 2.
+inline ConvGeom conv_bwd_geom(const ConvShape &c) {
+  ConvGeom g{};
+  g.Hin = c.Ho(), g.Win = c.Wo(), g.Cc = c.Cout;
+  g.P = c.H, g.Q = c.W, g.R = c.R, g.S = c.R;
+  g.sp = 1, g.off = c.pad, g.sr = -1, g.dshift = c.stride == 2 ? 1 : 0;
+  g.M = c.B * c.H * c.W, g.N = c.Cin, g.K = c.R * c.R * c.Cout;
+  g.dPQ = make_fastdiv(g.P * g.Q), g.dQ = make_fastdiv(g.Q), g.dCc = make_fastdiv(g.Cc), g.dS = make_fastdiv(g.S);
+  return g;
+}
+
+// dtype: 0 = fp32 (v_mfma_f32_32x32x2_f32), 1 = bf16 (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom &g, const WgradIO &io);
+// Rows of M per split so that the launch has enough workgroups; returns the split count.
+int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out);

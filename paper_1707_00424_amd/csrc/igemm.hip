@@ -1,0 +1,530 @@
+// Implicit-GEMM convolution kernels on MFMA for gfx950 (see igemm.h for the index conventions).
+//
+// Tiling: a workgroup of 4 wavefronts owns a BM x BN output tile; each wavefront owns TM x TN
+// MFMA tiles of 32x32 (accumulators in registers, fp32).  The contraction runs in steps of
+// BK = 64 bytes of the operand type (16 fp32 / 32 bf16); both operand tiles are staged in LDS as
+// [row][BK + 16 bytes of padding] so that the 16-byte fragment reads of 8 consecutive rows hit 32
+// distinct banks, and LDS is double-buffered: global loads of step t+1 are in flight while the
+// MFMAs of step t run, one barrier per step.
+//
+// MFMA register layouts relied upon (lane l of 64):
+//   A, B operands: row (resp. column) l % 32, contraction slice l / 32 (the order of the contraction
+//                  elements inside a step is irrelevant as long as A and B agree, which they do
+//                  because both are read from LDS with the same offsets);
+//   D (32x32 fp32, 16 registers v): column l % 32, row 8*(v/4) + 4*(l/32) + v%4.
+#include "igemm.h"
+
+namespace {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
+  return (uint32_t)(((uint64_t)n * f.magic) >> f.shift);
+}
+
+template <typename T>
+__device__ __forceinline__ float to_f32(T v);
+template <>
+__device__ __forceinline__ float to_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) {
+  return bf16_to_f32(v);
+}
+template <typename T>
+__device__ __forceinline__ T from_f32(float v);
+template <>
+__device__ __forceinline__ float from_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) {
+  return f32_to_bf16(v);
+}
+
+// One contraction sub-step on a 32x32 accumulator from two 16-byte fragments.
+template <typename T>
+__device__ __forceinline__ void mma(const u4 &a, const u4 &b, f16v &acc);
+template <>
+__device__ __forceinline__ void mma<float>(const u4 &a, const u4 &b, f16v &acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mma<bf16_t>(const u4 &a, const u4 &b, f16v &acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), acc, 0, 0, 0);
+}
+
+template <typename T, int VW>
+__device__ __forceinline__ u4 pack_vec(const T *tmp) {
+  u4 r;
+  if (sizeof(T) == 4) {
+    const uint32_t *p = (const uint32_t *)tmp;
+    r.x = p[0], r.y = p[1], r.z = p[2], r.w = p[3];
+  } else {
+    const unsigned short *p = (const unsigned short *)tmp;
+    r.x = p[0] | ((uint32_t)p[1] << 16);
+    r.y = p[2] | ((uint32_t)p[3] << 16);
+    r.z = p[4] | ((uint32_t)p[5] << 16);
+    r.w = p[6] | ((uint32_t)p[7] << 16);
+  }
+  return r;
+}
+
+__device__ __forceinline__ bool tap(int t, int dshift, int lim, int &idx) {
+  const int dm = (1 << dshift) - 1;
+  idx = t >> dshift;
+  return t >= 0 && (t & dm) == 0 && idx < lim;
+}
+
+// Shared MFMA inner step: every wavefront multiplies its TM x TN fragments for both halves of BK.
+template <typename T, int TM, int TN, int LK, int VW>
+__device__ __forceinline__ void mma_tile(const T *As, const T *Bs, int arow0, int brow0, int lane, f16v (&acc)[TM][TN]) {
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    u4 af[TM], bf[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&As[(arow0 + tm * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&Bs[(brow0 + tn * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma<T>(af[tm], bf[tn], acc[tm][tn]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// forward / backward-data: out[m, n] = epilogue( sum_k gather(m, k) * w[n, k] )
+// ---------------------------------------------------------------------------------------------
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32>
+__global__ __launch_bounds__(kThreads) void k_igemm(const ConvGeom g, const GemmIO io) {
+  constexpr int VW = 16 / sizeof(T);
+  constexpr int BK = 4 * VW;
+  constexpr int LK = BK + VW;
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  constexpr int A_IT = (BM + 63) / 64, B_IT = (BN + 63) / 64;
+  __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
+  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int rep = blockIdx.z;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const T *__restrict__ in = (const T *)io.in + rep * io.in_rs;
+  const T *__restrict__ w = (const T *)io.w + rep * io.w_rs;
+  const int lrow = tid >> 2, lkv = tid & 3;
+  const int PQ = g.P * g.Q;
+
+  int a_boff[A_IT], a_h0[A_IT], a_w0[A_IT];
+  bool a_ok[A_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) {
+    const int row = i * 64 + lrow, m = m0 + row;
+    a_ok[i] = row < BM && m < g.M;
+    const uint32_t mm = a_ok[i] ? m : 0;
+    const uint32_t b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
+    const uint32_t p = fdiv(rem, g.dQ), q = rem - p * g.Q;
+    a_boff[i] = b * g.Hin * g.Win * g.Cc;
+    a_h0[i] = p * g.sp + g.off;
+    a_w0[i] = q * g.sp + g.off;
+  }
+  int kk = lkv * VW, kr, ks, kc;
+  {
+    const uint32_t rs = fdiv(kk, g.dCc);
+    kc = kk - rs * g.Cc;
+    kr = fdiv(rs, g.dS);
+    ks = rs - kr * g.S;
+  }
+
+  u4 areg[A_IT], breg[B_IT];
+  const u4 zero4 = {0u, 0u, 0u, 0u};
+
+  auto load_tiles = [&]() {
+    if (io.vecA) {
+      const bool kok = kk < g.K;
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) {
+        int ih, iw;
+        const bool ok = tap(a_h0[i] + kr * g.sr, g.dshift, g.Hin, ih) & tap(a_w0[i] + ks * g.sr, g.dshift, g.Win, iw) &
+                        a_ok[i] & kok;
+        areg[i] = ok ? *(const u4 *)(in + a_boff[i] + (ih * g.Win + iw) * g.Cc + kc) : zero4;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) {
+        T tmp[VW];
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+          const int ke = kk + e;
+          const uint32_t rs = fdiv(ke < g.K ? ke : 0, g.dCc);
+          const int c = (ke < g.K ? ke : 0) - rs * g.Cc;
+          const int r = fdiv(rs, g.dS), s = rs - r * g.S;
+          int ih, iw;
+          const bool ok = tap(a_h0[i] + r * g.sr, g.dshift, g.Hin, ih) & tap(a_w0[i] + s * g.sr, g.dshift, g.Win, iw) &
+                          a_ok[i] & (ke < g.K);
+          tmp[e] = ok ? in[a_boff[i] + (ih * g.Win + iw) * g.Cc + c] : (T)0;
+        }
+        areg[i] = pack_vec<T, VW>(tmp);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = i * 64 + lrow, nrow = n0 + row;
+      const bool rok = row < BN && nrow < g.N;
+      if (io.vecB) {
+        breg[i] = (rok && kk < g.K) ? *(const u4 *)(w + (long long)nrow * g.K + kk) : zero4;
+      } else {
+        T tmp[VW];
+#pragma unroll
+        for (int e = 0; e < VW; ++e) tmp[e] = (rok && kk + e < g.K) ? w[(long long)nrow * g.K + kk + e] : (T)0;
+        breg[i] = pack_vec<T, VW>(tmp);
+      }
+    }
+  };
+  auto advance_k = [&]() {
+    kk += BK;
+    kc += BK;
+    while (kc >= g.Cc) {
+      kc -= g.Cc;
+      if (++ks == g.S) {
+        ks = 0;
+        ++kr;
+      }
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int row = i * 64 + lrow;
+      if (BM % 64 == 0 || row < BM) *(u4 *)&As[buf][row * LK + lkv * VW] = areg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = i * 64 + lrow;
+      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf][row * LK + lkv * VW] = breg[i];
+    }
+  };
+
+  f16v acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+  const int KT = (g.K + BK - 1) / BK;
+  load_tiles();
+  store_tiles(0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) {
+      advance_k();
+      load_tiles();
+    }
+    mma_tile<T, TM, TN, LK, VW>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+    if (kt + 1 < KT) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue
+  const int col_l = lane & 31, h = lane >> 5;
+  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
+  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
+  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int n = n0 + wn * TN * 32 + tn * 32 + col_l;
+    if (n >= g.N) continue;
+    const float bv = bias ? bias[n] : 0.f;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wm * TM * 32 + tm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (m >= g.M) continue;
+        const long long o = (long long)m * io.ldc + n;
+        float val = acc[tm][tn][v] + bv;
+        if (resid) val += to_f32<T>(resid[o]);
+        if (io.relu) val = val > 0.f ? val : 0.f;
+        if (mask) val = to_f32<T>(mask[o]) > 0.f ? val : 0.f;
+        if (OUT_F32) {
+          float *out = (float *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += out[o];
+          out[o] = val;
+        } else {
+          T *out = (T *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += to_f32<T>(out[o]);
+          out[o] = from_f32<T>(val);
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward-weight: out[n, k] = sum_{m in split} dy[m, n] * gather(m, k)   (fp32 partial per split)
+// Both operands arrive contraction-major from memory; each thread loads VW consecutive rows m of a
+// 4-byte column group and writes them to LDS as 16-byte contraction-contiguous fragments.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN>
+__global__ __launch_bounds__(kThreads) void k_wgrad(const ConvGeom g, const WgradIO io) {
+  constexpr int VW = 16 / sizeof(T);
+  constexpr int CP = 4 / sizeof(T);  // columns per 4-byte load
+  constexpr int BK = 4 * VW;
+  constexpr int LK = BK + VW;
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  constexpr int A_TASKS = BM / CP * 4, B_TASKS = BN / CP * 4;
+  constexpr int A_IT = (A_TASKS + kThreads - 1) / kThreads, B_IT = (B_TASKS + kThreads - 1) / kThreads;
+  __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
+  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int rep = blockIdx.z / io.splits, split = blockIdx.z % io.splits;
+  const int n0 = blockIdx.y * BM;  // rows of the output = output channels
+  const int k0 = blockIdx.x * BN;  // columns of the output = (r, s, c)
+  const T *__restrict__ dy = (const T *)io.dy + rep * io.dy_rs;
+  const T *__restrict__ x = (const T *)io.x + rep * io.x_rs;
+  const int m_begin = split * io.chunk;
+  const int m_end = min(g.M, m_begin + io.chunk);
+  const int PQ = g.P * g.Q;
+
+  // per-thread fixed column info of the gathered operand
+  int b_r[B_IT][CP], b_s[B_IT][CP], b_c[B_IT][CP];
+  bool b_ok[B_IT][CP];
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) {
+    const int t = i * kThreads + tid;
+    const int kp = t % (BN / CP);
+#pragma unroll
+    for (int e = 0; e < CP; ++e) {
+      const int k = k0 + kp * CP + e;
+      b_ok[i][e] = t < B_TASKS && k < g.K;
+      const uint32_t kk = b_ok[i][e] ? k : 0;
+      const uint32_t rs = fdiv(kk, g.dCc);
+      b_c[i][e] = kk - rs * g.Cc;
+      b_r[i][e] = fdiv(rs, g.dS);
+      b_s[i][e] = rs - b_r[i][e] * g.S;
+    }
+  }
+
+  uint32_t areg[A_IT][VW], breg[B_IT][VW];  // one 4-byte column group per contraction row
+
+  auto load_tiles = [&](int mbase) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int t = i * kThreads + tid;
+      const int cp = t % (BM / CP), mg = t / (BM / CP);
+      const int n = n0 + cp * CP;
+#pragma unroll
+      for (int j = 0; j < VW; ++j) {
+        const int m = mbase + mg * VW + j;
+        const bool mok = t < A_TASKS && m < m_end;
+        if (sizeof(T) == 4) {
+          areg[i][j] = (mok && n < g.N) ? ((const uint32_t *)dy)[(long long)m * g.N + n] : 0u;
+        } else if (io.pairA) {
+          areg[i][j] = (mok && n < g.N) ? *(const uint32_t *)((const unsigned short *)dy + (long long)m * g.N + n) : 0u;
+        } else {
+          const unsigned short *p = (const unsigned short *)dy + (long long)m * g.N + n;
+          const uint32_t lo = (mok && n < g.N) ? p[0] : 0u;
+          const uint32_t hi = (mok && n + 1 < g.N) ? p[1] : 0u;
+          areg[i][j] = lo | (hi << 16);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int t = i * kThreads + tid;
+      const int mg = t / (BN / CP);
+      const int mfirst = mbase + mg * VW;
+      uint32_t mm = mfirst < g.M ? mfirst : 0;
+      uint32_t b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
+      uint32_t p = fdiv(rem, g.dQ), q = rem - p * g.Q;
+#pragma unroll
+      for (int j = 0; j < VW; ++j) {
+        const bool mok = (mfirst + j) < m_end;
+        const int boff = b * g.Hin * g.Win * g.Cc;
+        const int h0 = p * g.sp + g.off, w0 = q * g.sp + g.off;
+        if (sizeof(T) == 4) {
+          int ih, iw;
+          const bool ok = tap(h0 + b_r[i][0], 0, g.Hin, ih) & tap(w0 + b_s[i][0], 0, g.Win, iw) & mok & b_ok[i][0];
+          breg[i][j] = ok ? ((const uint32_t *)x)[boff + (ih * g.Win + iw) * g.Cc + b_c[i][0]] : 0u;
+        } else if (io.pairB) {
+          int ih, iw;
+          const bool ok = tap(h0 + b_r[i][0], 0, g.Hin, ih) & tap(w0 + b_s[i][0], 0, g.Win, iw) & mok & b_ok[i][0];
+          breg[i][j] =
+              ok ? *(const uint32_t *)((const unsigned short *)x + boff + (ih * g.Win + iw) * g.Cc + b_c[i][0]) : 0u;
+        } else {
+          uint32_t v[2] = {0u, 0u};
+#pragma unroll
+          for (int e = 0; e < CP; ++e) {
+            int ih, iw;
+            const bool ok = tap(h0 + b_r[i][e], 0, g.Hin, ih) & tap(w0 + b_s[i][e], 0, g.Win, iw) & mok & b_ok[i][e];
+            v[e] = ok ? ((const unsigned short *)x)[boff + (ih * g.Win + iw) * g.Cc + b_c[i][e]] : 0u;
+          }
+          breg[i][j] = v[0] | (v[1] << 16);
+        }
+        if (++q == (uint32_t)g.Q) {
+          q = 0;
+          if (++p == (uint32_t)g.P) {
+            p = 0;
+            ++b;
+          }
+        }
+      }
+    }
+  };
+  auto store_one = [&](T *dst, int tasks_per_row_group, int t, const uint32_t *regs, int rows_limit) {
+    const int cp = t % tasks_per_row_group, mg = t / tasks_per_row_group;
+    if (sizeof(T) == 4) {
+      u4 v = {regs[0], regs[1], regs[2], regs[3]};
+      *(u4 *)&dst[cp * LK + mg * VW] = v;
+    } else {
+      u4 lo, hi;
+      lo.x = (regs[0] & 0xffffu) | (regs[1] << 16);
+      lo.y = (regs[2] & 0xffffu) | (regs[3] << 16);
+      lo.z = (regs[4] & 0xffffu) | (regs[5] << 16);
+      lo.w = (regs[6] & 0xffffu) | (regs[7] << 16);
+      hi.x = (regs[0] >> 16) | (regs[1] & 0xffff0000u);
+      hi.y = (regs[2] >> 16) | (regs[3] & 0xffff0000u);
+      hi.z = (regs[4] >> 16) | (regs[5] & 0xffff0000u);
+      hi.w = (regs[6] >> 16) | (regs[7] & 0xffff0000u);
+      *(u4 *)&dst[(cp * 2) * LK + mg * VW] = lo;
+      *(u4 *)&dst[(cp * 2 + 1) * LK + mg * VW] = hi;
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int t = i * kThreads + tid;
+      if (A_TASKS % kThreads == 0 || t < A_TASKS) store_one(As[buf], BM / CP, t, areg[i], BM);
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int t = i * kThreads + tid;
+      if (B_TASKS % kThreads == 0 || t < B_TASKS) store_one(Bs[buf], BN / CP, t, breg[i], BN);
+    }
+  };
+
+  f16v acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+  const int KT = m_end > m_begin ? (m_end - m_begin + BK - 1) / BK : 0;
+  if (KT > 0) {
+    load_tiles(m_begin);
+    store_tiles(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_tiles(m_begin + (kt + 1) * BK);
+    mma_tile<T, TM, TN, LK, VW>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+    if (kt + 1 < KT) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  float *out = io.out + rep * io.out_rs + split * io.split_stride;
+  const int col_l = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int k = k0 + wn * TN * 32 + tn * 32 + col_l;
+    if (k >= g.K) continue;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int n = n0 + wm * TM * 32 + tm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (n < g.N) out[(long long)n * g.K + k] = acc[tm][tn][v];
+      }
+  }
+}
+
+template <typename T, int WM, int WN, int TM, int TN>
+hipError_t run_igemm(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, replicas);
+  if (out_f32)
+    hipLaunchKernelGGL((k_igemm<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+  else
+    hipLaunchKernelGGL((k_igemm<T, WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
+
+template <typename T, int WM, int WN, int TM, int TN>
+hipError_t run_wgrad(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid((g.K + BN - 1) / BN, (g.N + BM - 1) / BM, replicas * io.splits);
+  hipLaunchKernelGGL((k_wgrad<T, WM, WN, TM, TN>), grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
+
+// Output-channel tile of the bf16 kernels by layer width.
+int bf16_ntile(int n) {
+  if (n <= 32) return 32;
+  if (n <= 64) return 64;
+  if (n % 96 == 0 || n <= 96) return 96;
+  return 128;
+}
+
+}  // namespace
+
+hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
+  if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
+  if (dtype == 0) return run_igemm<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
+  switch (bf16_ntile(g.N)) {
+    case 32: return run_igemm<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);
+    case 64: return run_igemm<bf16_t, 4, 1, 1, 2>(st, out_f32, replicas, g, io);
+    case 96: return run_igemm<bf16_t, 4, 1, 1, 3>(st, out_f32, replicas, g, io);
+    default: return run_igemm<bf16_t, 2, 2, 2, 2>(st, out_f32, replicas, g, io);
+  }
+}
+
+hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom &g, const WgradIO &io) {
+  if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || io.splits < 1 || (long long)replicas * io.splits > 65535 ||
+      io.chunk < 32 || (io.chunk & 31))
+    return hipErrorInvalidValue;
+  if (dtype == 0) return run_wgrad<float, 2, 2, 1, 1>(st, replicas, g, io);
+  switch (bf16_ntile(g.N)) {
+    case 32: return run_wgrad<bf16_t, 1, 4, 1, 1>(st, replicas, g, io);
+    case 64: return run_wgrad<bf16_t, 1, 4, 2, 1>(st, replicas, g, io);
+    case 96: return run_wgrad<bf16_t, 1, 4, 3, 1>(st, replicas, g, io);
+    default: return run_wgrad<bf16_t, 2, 2, 2, 2>(st, replicas, g, io);
+  }
+}
+
+int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
+  int bm, bn;
+  if (dtype == 0) {
+    bm = 64, bn = 64;
+  } else {
+    bm = bf16_ntile(g.N);
+    bn = 128;
+  }
+  const long long tiles = (long long)((g.K + bn - 1) / bn) * ((g.N + bm - 1) / bm) * replicas;
+  const int steps = (g.M + 31) / 32;                  // contraction steps of 32 rows available
+  long long want = (1024 + tiles - 1) / tiles;        // aim at >= 1024 workgroups (4 per CU)
+  if (want > steps / 4) want = steps / 4;             // keep >= 4 steps (128 rows) per split
+  if (want < 1) want = 1;
+  const long long cap = 65535 / replicas;
+  if (want > cap) want = cap;
+  int chunk = (int)(((steps + want - 1) / want) * 32);
+  int splits = (g.M + chunk - 1) / chunk;
+  if (chunk_out) *chunk_out = chunk;
+  return splits;
+}

@@ -1,11 +1,487 @@
-// placeholder until the network executor lands
+// Replica-batched network executor.  A network is a static list of ops over tensors that live in
+// the caller's workspace; every op is one (or a few) grouped launches covering all replicas.
+// The backward pass walks the list in reverse with hand-written gradient routing (which tensor
+// receives which gradient, written or accumulated) fixed at plan time.
 #include "net.h"
-struct Net { int dummy; };
-Net *net_create(const parle_config &, const Arch &, const std::vector<Segment> &, int64_t, std::string &err) { return new Net{0}; }
+
+#include "igemm.h"
+#include "nn.h"
+
+namespace {
+
+enum OpType { OP_CONV = 0, OP_POOL = 1, OP_GAP = 2, OP_BNRELU = 3 };
+
+struct Tensor {
+  int H = 0, W = 0, C = 0;
+  bool f32 = false;       // fp32 storage regardless of the activation dtype (logits)
+  bool external = false;  // the caller's image buffer (fp32 mode): no workspace slot
+  int64_t off = -1;       // byte offset in the workspace
+  int64_t goff = -1;      // byte offset of its gradient (activation dtype), -1 = none
+};
+
+struct Op {
+  int type = 0;
+  int in = -1, out = -1;
+  // conv / fc
+  int wseg = -1, bseg = -1;
+  int Hin = 0, Win = 0, Cin = 0, Cout = 0, R = 1, stride = 1, pad = 0, Ho = 0, Wo = 0;
+  bool relu = false;
+  int resid = -1;          // tensor added to the conv output before the ReLU
+  bool need_dx = false;
+  bool mask_in = false;    // the input is a ReLU output: its gradient is masked by (in > 0)
+  bool dx_accumulate = false;
+  int dy = -1;             // tensor whose gradient is this op's output gradient (default: out)
+  int64_t wt_off = -1;     // transposed weights (bytes)
+  // pool
+  bool pool_relu_mask = false;
+  // bn
+  int gseg = -1, betaseg = -1;
+  int64_t saved_off = -1, sums_off = -1, run_off = 0;  // run_off in floats inside a replica's BN row
+  int bn_add = -1;         // tensor whose gradient is added to this op's input gradient
+};
+
+}  // namespace
+
+struct Net {
+  parle_config cfg;
+  Arch arch;
+  std::vector<Segment> segs;
+  int64_t n_pad = 0;
+  int n = 0, B = 0, dtype = 0, esize = 4;
+  std::vector<Tensor> tensors;
+  std::vector<Op> ops;
+  int t_images = -1, t_logits = -1;
+  int64_t ws_bytes = 0;
+  int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0;
+  int64_t bn_floats = 0;
+  int max_bn_c = 0;
+
+  int64_t alloc(int64_t bytes) {
+    const int64_t o = ws_bytes;
+    ws_bytes += (bytes + 255) / 256 * 256;
+    return o;
+  }
+  int add_tensor(int H, int W, int C, bool f32 = false, bool external = false) {
+    Tensor t;
+    t.H = H, t.W = W, t.C = C, t.f32 = f32, t.external = external;
+    if (!external) t.off = alloc((int64_t)n * B * H * W * C * (f32 ? 4 : esize));
+    tensors.push_back(t);
+    return (int)tensors.size() - 1;
+  }
+  void want_grad(int t) {
+    if (tensors[t].goff < 0) tensors[t].goff = alloc((int64_t)n * B * tensors[t].H * tensors[t].W * tensors[t].C * esize);
+  }
+  int64_t rs(int t) const { return (int64_t)B * tensors[t].H * tensors[t].W * tensors[t].C; }
+
+  // conv on tensor `in` seen as [B, Hin, Win, Cin]; returns the op index
+  int add_conv(int in, int Hin, int Win, int Cin, const std::string &name, int Cout, int R, int stride, int pad,
+               bool bias, bool relu, bool out_f32 = false) {
+    Op op;
+    op.type = OP_CONV;
+    op.in = in;
+    op.Hin = Hin, op.Win = Win, op.Cin = Cin, op.Cout = Cout, op.R = R, op.stride = stride, op.pad = pad;
+    op.Ho = (Hin + 2 * pad - R) / stride + 1;
+    op.Wo = (Win + 2 * pad - R) / stride + 1;
+    op.relu = relu;
+    op.wseg = find_segment(segs, name + ".w");
+    op.bseg = bias ? find_segment(segs, name + ".b") : -1;
+    op.out = add_tensor(op.Ho, op.Wo, Cout, out_f32);
+    op.dy = op.out;
+    ops.push_back(op);
+    return (int)ops.size() - 1;
+  }
+  int add_bn(int in, const std::string &name) {
+    Op op;
+    op.type = OP_BNRELU;
+    op.in = in;
+    const Tensor t = tensors[in];  // copy: add_tensor may reallocate the vector
+    op.out = add_tensor(t.H, t.W, t.C);
+    op.gseg = find_segment(segs, name + ".g");
+    op.betaseg = find_segment(segs, name + ".b");
+    op.saved_off = alloc((int64_t)n * 2 * t.C * 4);
+    op.sums_off = alloc((int64_t)n * 2 * t.C * 4);
+    op.run_off = bn_floats;
+    bn_floats += 2 * t.C;
+    if (t.C > max_bn_c) max_bn_c = t.C;
+    ops.push_back(op);
+    return (int)ops.size() - 1;
+  }
+};
+
+namespace {
+
+bool build_plan(Net &N, std::string &err) {
+  const Arch &a = N.arch;
+  const bool bf = N.dtype == 1;
+  // the images: fp32 mode reads the caller's buffer directly, bf16 mode converts into a slot
+  N.t_images = N.add_tensor(a.H, a.W, a.C, false, !bf);
+  const int img = N.t_images;
+  switch (a.model) {
+    case PARLE_MODEL_MLP: {
+      const int d = a.H * a.W * a.C;
+      const int f1 = N.add_conv(img, 1, 1, d, "fc1", a.a0, 1, 1, 0, true, true);
+      const int f2 = N.add_conv(N.ops[f1].out, 1, 1, a.a0, "fc2", a.classes, 1, 1, 0, true, false, true);
+      N.ops[f2].need_dx = true, N.ops[f2].mask_in = true;
+      N.t_logits = N.ops[f2].out;
+      break;
+    }
+    case PARLE_MODEL_LENET: {
+      const int k = a.a2;
+      const int c1 = N.add_conv(img, a.H, a.W, a.C, "conv1", a.a0, k, 1, 0, true, true);
+      Op p1;
+      p1.type = OP_POOL, p1.in = N.ops[c1].out, p1.pool_relu_mask = true;
+      p1.out = N.add_tensor(N.ops[c1].Ho / 2, N.ops[c1].Wo / 2, a.a0);
+      N.ops.push_back(p1);
+      const Tensor tp1 = N.tensors[p1.out];
+      const int c2 = N.add_conv(p1.out, tp1.H, tp1.W, a.a0, "conv2", a.a1, k, 1, 0, true, true);
+      N.ops[c2].need_dx = true;
+      Op p2;
+      p2.type = OP_POOL, p2.in = N.ops[c2].out, p2.pool_relu_mask = true;
+      p2.out = N.add_tensor(N.ops[c2].Ho / 2, N.ops[c2].Wo / 2, a.a1);
+      N.ops.push_back(p2);
+      const Tensor tp2 = N.tensors[p2.out];
+      const int f1 = N.add_conv(p2.out, 1, 1, tp2.H * tp2.W * tp2.C, "fc1", a.a3, 1, 1, 0, true, true);
+      N.ops[f1].need_dx = true;
+      const int f2 = N.add_conv(N.ops[f1].out, 1, 1, a.a3, "fc2", a.classes, 1, 1, 0, true, false, true);
+      N.ops[f2].need_dx = true, N.ops[f2].mask_in = true;
+      N.t_logits = N.ops[f2].out;
+      break;
+    }
+    case PARLE_MODEL_ALLCNN_C: {
+      const int ca = a.a0, cb = a.a1;
+      const int cout[9] = {ca, ca, ca, cb, cb, cb, cb, cb, a.classes};
+      const int ks[9] = {3, 3, 3, 3, 3, 3, 3, 1, 1};
+      const int st[9] = {1, 1, 2, 1, 1, 2, 1, 1, 1};
+      int cur = img, H = a.H, W = a.W, C = a.C;
+      for (int i = 0; i < 9; ++i) {
+        const int c = N.add_conv(cur, H, W, C, "conv" + std::to_string(i + 1), cout[i], ks[i], st[i], ks[i] == 3 ? 1 : 0,
+                                 true, i < 8);
+        if (i > 0) N.ops[c].need_dx = true, N.ops[c].mask_in = true;
+        cur = N.ops[c].out, H = N.ops[c].Ho, W = N.ops[c].Wo, C = cout[i];
+      }
+      Op g;
+      g.type = OP_GAP, g.in = cur;
+      g.out = N.add_tensor(1, 1, C, true);
+      N.ops.push_back(g);
+      N.t_logits = g.out;
+      break;
+    }
+    case PARLE_MODEL_WRN: {
+      const int c0 = N.add_conv(img, a.H, a.W, a.C, "conv1", a.a0, 3, 1, 1, false, false);
+      int h = N.ops[c0].out, H = N.ops[c0].Ho, W = N.ops[c0].Wo;
+      for (const WrnBlock &b : wrn_block_list(a)) {
+        const int bn1 = N.add_bn(h, b.name + ".bn1");
+        const int o = N.ops[bn1].out;
+        int s = -1;
+        if (b.has_sc) {
+          const int sc = N.add_conv(o, H, W, b.cin, b.name + ".sc", b.cout, 1, b.stride, 0, false, false);
+          N.ops[sc].need_dx = true, N.ops[sc].dx_accumulate = true;
+          s = N.ops[sc].out;
+        } else {
+          N.ops[bn1].bn_add = -2;  // resolved below to the block output
+        }
+        const int cv1 = N.add_conv(o, H, W, b.cin, b.name + ".conv1", b.cout, 3, b.stride, 1, false, false);
+        N.ops[cv1].need_dx = true;
+        const int bn2 = N.add_bn(N.ops[cv1].out, b.name + ".bn2");
+        const int cv2 = N.add_conv(N.ops[bn2].out, N.ops[cv1].Ho, N.ops[cv1].Wo, b.cout, b.name + ".conv2", b.cout, 3, 1,
+                                   1, false, false);
+        N.ops[cv2].need_dx = true;
+        N.ops[cv2].resid = b.has_sc ? s : h;
+        const int v = N.ops[cv2].out;
+        if (b.has_sc) {
+          // the shortcut conv's output gradient is the block output's gradient; it runs (in reverse
+          // order) after conv1's backward-data has written the gradient of o, hence accumulates
+          for (Op &op : N.ops)
+            if (op.type == OP_CONV && op.out == s) op.dy = v;
+        } else {
+          N.ops[bn1].bn_add = v;
+        }
+        h = v, H = N.ops[cv1].Ho, W = N.ops[cv1].Wo;
+      }
+      const int bno = N.add_bn(h, "bn_out");
+      Op g;
+      g.type = OP_GAP, g.in = N.ops[bno].out;
+      g.out = N.add_tensor(1, 1, N.tensors[h].C, false);
+      N.ops.push_back(g);
+      const int fc = N.add_conv(g.out, 1, 1, N.tensors[h].C, "fc", a.classes, 1, 1, 0, true, false, true);
+      N.ops[fc].need_dx = true;
+      N.t_logits = N.ops[fc].out;
+      break;
+    }
+    default:
+      err = "model has no network";
+      return false;
+  }
+  // gradients, transposed weights, scratch
+  int64_t wpartial = 0;
+  for (Op &op : N.ops) {
+    if (op.wseg < 0 && op.type == OP_CONV) {
+      err = "internal: weight segment not found";
+      return false;
+    }
+    if (op.stride != 1 && op.stride != 2) {
+      err = "internal: stride must be 1 or 2";
+      return false;
+    }
+    N.want_grad(op.out);
+    if (op.type == OP_CONV) {
+      const int64_t wsize = (int64_t)op.Cout * op.R * op.R * op.Cin;
+      if (op.need_dx) {
+        N.want_grad(op.in);
+        op.wt_off = N.alloc((int64_t)N.n * wsize * N.esize);
+      }
+      ConvGeom g{};
+      g.M = N.B * op.Ho * op.Wo, g.N = op.Cout, g.K = op.R * op.R * op.Cin;
+      int chunk = 0;
+      const int S = wgrad_plan(N.dtype, N.n, g, &chunk);
+      if (S > 1 && (int64_t)N.n * S * wsize * 4 > wpartial) wpartial = (int64_t)N.n * S * wsize * 4;
+      if ((int64_t)N.B * op.Hin * op.Win * op.Cin >= (1LL << 31) || (int64_t)g.M * op.Cout >= (1LL << 31) ||
+          wsize >= (1LL << 31)) {
+        err = "a layer exceeds 2^31 elements per replica";
+        return false;
+      }
+    } else {
+      N.want_grad(op.in);
+    }
+  }
+  N.off_wpartial = N.alloc(wpartial > 0 ? wpartial : 256);
+  int maxc = N.max_bn_c;
+  for (const Op &op : N.ops)
+    if (op.type == OP_CONV && op.bseg >= 0 && op.Cout > maxc) maxc = op.Cout;
+  N.off_colpartial = N.alloc((int64_t)N.n * 1024 * 2 * (maxc > 0 ? maxc : 1) * 8);
+  N.off_rowcopy = N.alloc(bf ? N.n_pad * 2 : 256);  // bf16 copy of one parameter row for parle_eval
+  return true;
+}
+
+struct Run {
+  Net *N;
+  hipStream_t st;
+  int n, B;            // replicas and batch of this launch (eval: 1, count)
+  const float *params;  // fp32 rows
+  const void *params_t; // rows in the activation dtype (== params in fp32 mode)
+  int64_t p_rs;
+  char *ws;
+  const float *images;
+  void *tptr(int t) const {
+    const Tensor &T = N->tensors[t];
+    return T.external ? (void *)images : (void *)(ws + T.off);
+  }
+  void *gptr(int t) const { return ws + N->tensors[t].goff; }
+  int64_t trs(int t) const { return (int64_t)B * N->tensors[t].H * N->tensors[t].W * N->tensors[t].C; }
+  const void *wptr(int seg) const { return (const char *)params_t + N->segs[seg].offset * N->esize; }
+  const float *fptr(int seg) const { return params + N->segs[seg].offset; }
+};
+
+ConvShape shape_of(const Op &op, int B) { return ConvShape{B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad}; }
+ConvGeom fwd_geom(const Op &op, int B) { return conv_fwd_geom(shape_of(op, B)); }
+ConvGeom bwd_geom(const Op &op, int B) { return conv_bwd_geom(shape_of(op, B)); }
+
+#define HIP_TRY(expr)                   \
+  do {                                  \
+    hipError_t _e = (expr);             \
+    if (_e != hipSuccess) return _e;    \
+  } while (0)
+
+hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_eval_row) {
+  Net &N = *r.N;
+  const int vw = 16 / N.esize;
+  for (const Op &op : N.ops) {
+    switch (op.type) {
+      case OP_CONV: {
+        const ConvGeom g = fwd_geom(op, r.B);
+        GemmIO io{};
+        io.in = r.tptr(op.in), io.in_rs = r.trs(op.in);
+        io.w = r.wptr(op.wseg), io.w_rs = r.p_rs;
+        io.out = r.tptr(op.out), io.out_rs = r.trs(op.out), io.ldc = op.Cout;
+        io.bias = op.bseg >= 0 ? r.fptr(op.bseg) : nullptr, io.bias_rs = r.p_rs;
+        io.resid = op.resid >= 0 ? r.tptr(op.resid) : nullptr, io.resid_rs = op.resid >= 0 ? r.trs(op.resid) : 0;
+        io.relu = op.relu;
+        io.vecA = (op.Cin % vw == 0) && aligned_to(io.in, 16);
+        io.vecB = (g.K % vw == 0) && (N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) && aligned_to(io.w, 16);
+        HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, io));
+        break;
+      }
+      case OP_POOL: {
+        const Tensor &ti = N.tensors[op.in];
+        HIP_TRY(launch_maxpool_fwd(r.st, N.dtype, r.n, r.B, ti.H, ti.W, ti.C, r.tptr(op.in), r.trs(op.in),
+                                   r.tptr(op.out), r.trs(op.out)));
+        break;
+      }
+      case OP_GAP: {
+        const Tensor &ti = N.tensors[op.in];
+        HIP_TRY(launch_gap_fwd(r.st, N.dtype, N.tensors[op.out].f32, r.n, r.B, ti.H * ti.W, ti.C, r.tptr(op.in),
+                               r.trs(op.in), r.tptr(op.out), r.trs(op.out)));
+        break;
+      }
+      case OP_BNRELU: {
+        const Tensor &ti = N.tensors[op.in];
+        const int M = r.B * ti.H * ti.W;
+        float *saved = (float *)(r.ws + op.saved_off);
+        if (train) {
+          HIP_TRY(launch_bn_train_fwd(r.st, N.dtype, r.n, M, ti.C, r.tptr(op.in), r.trs(op.in), r.fptr(op.gseg),
+                                      r.fptr(op.betaseg), r.p_rs, (double *)(r.ws + N.off_colpartial), saved,
+                                      bn_stats + op.run_off, N.bn_floats, r.tptr(op.out), r.trs(op.out)));
+        } else {
+          HIP_TRY(launch_bn_eval_fwd(r.st, N.dtype, M, ti.C, r.tptr(op.in), r.fptr(op.gseg), r.fptr(op.betaseg),
+                                     bn_eval_row + op.run_off, saved, r.tptr(op.out)));
+        }
+        break;
+      }
+    }
+  }
+  return hipSuccess;
+}
+
+hipError_t backward(const Run &r, float *grad) {
+  Net &N = *r.N;
+  const int vw = 16 / N.esize;
+  for (int oi = (int)N.ops.size() - 1; oi >= 0; --oi) {
+    const Op &op = N.ops[oi];
+    switch (op.type) {
+      case OP_CONV: {
+        const void *dy = r.gptr(op.dy);
+        const int64_t dy_rs = r.trs(op.dy);
+        const ConvGeom gf = fwd_geom(op, r.B);
+        if (op.bseg >= 0)
+          HIP_TRY(launch_bias_grad(r.st, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + N.off_colpartial),
+                                   grad + N.segs[op.bseg].offset, r.p_rs));
+        {
+          WgradIO io{};
+          io.dy = dy, io.dy_rs = dy_rs;
+          io.x = r.tptr(op.in), io.x_rs = r.trs(op.in);
+          int chunk = 0;
+          const int S = wgrad_plan(N.dtype, r.n, gf, &chunk);
+          io.splits = S, io.chunk = chunk;
+          io.pairA = (op.Cout % 2 == 0) && aligned_to(dy, 4);
+          io.pairB = (op.Cin % 2 == 0) && aligned_to(io.x, 4);
+          const int64_t wsize = N.segs[op.wseg].size;
+          if (S == 1) {
+            io.out = grad + N.segs[op.wseg].offset, io.out_rs = r.p_rs, io.split_stride = 0;
+            HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
+          } else {
+            io.out = (float *)(r.ws + N.off_wpartial), io.out_rs = (int64_t)S * wsize, io.split_stride = wsize;
+            HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
+            HIP_TRY(launch_reduce_partials(r.st, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
+          }
+        }
+        if (op.need_dx) {
+          void *wt = r.ws + op.wt_off;
+          const int64_t wsize = N.segs[op.wseg].size;
+          HIP_TRY(launch_weight_transpose(r.st, N.dtype, r.n, op.Cout, op.R * op.R, op.Cin, r.wptr(op.wseg), r.p_rs, wt,
+                                          wsize));
+          const ConvGeom gb = bwd_geom(op, r.B);
+          GemmIO io{};
+          io.in = dy, io.in_rs = dy_rs;
+          io.w = wt, io.w_rs = wsize;
+          io.out = r.gptr(op.in), io.out_rs = r.trs(op.in), io.ldc = op.Cin;
+          io.mask = op.mask_in ? r.tptr(op.in) : nullptr, io.mask_rs = r.trs(op.in);
+          io.accumulate = op.dx_accumulate;
+          io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
+          io.vecB = (gb.K % vw == 0) && (wsize % vw == 0);
+          HIP_TRY(launch_igemm(r.st, N.dtype, false, r.n, gb, io));
+        }
+        break;
+      }
+      case OP_POOL: {
+        const Tensor &ti = N.tensors[op.in];
+        HIP_TRY(launch_maxpool_bwd(r.st, N.dtype, r.n, r.B, ti.H, ti.W, ti.C, r.tptr(op.in), r.trs(op.in),
+                                   r.gptr(op.out), r.trs(op.out), r.gptr(op.in), r.trs(op.in), op.pool_relu_mask));
+        break;
+      }
+      case OP_GAP: {
+        const Tensor &ti = N.tensors[op.in];
+        HIP_TRY(launch_gap_bwd(r.st, N.dtype, r.n, r.B, ti.H * ti.W, ti.C, r.gptr(op.out), r.trs(op.out), r.gptr(op.in),
+                               r.trs(op.in)));
+        break;
+      }
+      case OP_BNRELU: {
+        const Tensor &ti = N.tensors[op.in];
+        const int M = r.B * ti.H * ti.W;
+        HIP_TRY(launch_bn_bwd(r.st, N.dtype, r.n, M, ti.C, r.tptr(op.in), r.trs(op.in), r.gptr(op.out), r.trs(op.out),
+                              r.fptr(op.gseg), r.fptr(op.betaseg), r.p_rs, (const float *)(r.ws + op.saved_off),
+                              (double *)(r.ws + N.off_colpartial), (float *)(r.ws + op.sums_off),
+                              grad + N.segs[op.gseg].offset, grad + N.segs[op.betaseg].offset,
+                              op.bn_add >= 0 ? r.gptr(op.bn_add) : nullptr, op.bn_add >= 0 ? r.trs(op.bn_add) : 0,
+                              r.gptr(op.in), r.trs(op.in)));
+        break;
+      }
+    }
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+Net *net_create(const parle_config &cfg, const Arch &a, const std::vector<Segment> &segs, int64_t n_pad,
+                std::string &err) {
+  Net *N = new Net();
+  N->cfg = cfg, N->arch = a, N->segs = segs, N->n_pad = n_pad;
+  N->n = cfg.n_replicas, N->B = cfg.batch, N->dtype = cfg.compute_bf16 ? 1 : 0, N->esize = cfg.compute_bf16 ? 2 : 4;
+  if ((int64_t)N->B * a.H * a.W * a.C >= (1LL << 31)) {
+    err = "batch * image size exceeds 2^31 elements";
+    delete N;
+    return nullptr;
+  }
+  if (!build_plan(*N, err)) {
+    delete N;
+    return nullptr;
+  }
+  return N;
+}
+
 void net_destroy(Net *net) { delete net; }
-int64_t net_workspace_bytes(const Net *) { return 0; }
-int64_t net_bn_floats_per_replica(const Net *) { return 0; }
-hipError_t net_train_step(Net *, hipStream_t, const float *, const void *, float *, float *, void *, const float *, const int32_t *, float *) { return hipErrorNotSupported; }
-hipError_t net_eval(Net *, hipStream_t, const float *, const float *, void *, const float *, const int32_t *, int, float *, int32_t *) { return hipErrorNotSupported; }
-hipError_t net_average_bn(Net *, hipStream_t, const float *, float *) { return hipErrorNotSupported; }
-hipError_t net_init_bn(Net *, hipStream_t, float *) { return hipErrorNotSupported; }
+int64_t net_workspace_bytes(const Net *net) { return net->ws_bytes; }
+int64_t net_bn_floats_per_replica(const Net *net) { return net->bn_floats; }
+
+hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const void *params_bf16, float *grad,
+                          float *bn_stats, void *workspace, const float *images, const int32_t *labels,
+                          float *loss_dev) {
+  Net &N = *net;
+  Run r{net, st, N.n, N.B, params, N.dtype ? params_bf16 : (const void *)params, N.n_pad, (char *)workspace, images};
+  if (N.dtype == 1) {
+    const Tensor &ti = N.tensors[N.t_images];
+    HIP_TRY(launch_convert(st, 1, images, r.ws + ti.off, (long long)N.n * N.B * ti.H * ti.W * ti.C));
+  }
+  HIP_TRY(forward(r, true, bn_stats, nullptr));
+  const Tensor &tl = N.tensors[N.t_logits];
+  HIP_TRY(launch_softmax_xent_train(st, N.dtype, N.n, N.B, tl.C, (const float *)r.tptr(N.t_logits), r.trs(N.t_logits),
+                                    labels, loss_dev, r.gptr(N.t_logits), r.trs(N.t_logits)));
+  return backward(r, grad);
+}
+
+hipError_t net_eval(Net *net, hipStream_t st, const float *param_row, const float *bn_row, void *workspace,
+                    const float *images, const int32_t *labels, int count, float *loss_sum_dev, int32_t *n_err_dev) {
+  Net &N = *net;
+  char *ws = (char *)workspace;
+  const void *row_t = param_row;
+  if (N.dtype == 1) {
+    HIP_TRY(launch_convert(st, 1, param_row, ws + N.off_rowcopy, N.n_pad));
+    row_t = ws + N.off_rowcopy;
+  }
+  Run r{net, st, 1, count, param_row, row_t, N.n_pad, ws, images};
+  if (N.dtype == 1) {
+    const Tensor &ti = N.tensors[N.t_images];
+    HIP_TRY(launch_convert(st, 1, images, ws + ti.off, (long long)count * ti.H * ti.W * ti.C));
+  }
+  HIP_TRY(forward(r, false, nullptr, bn_row));
+  const Tensor &tl = N.tensors[N.t_logits];
+  return launch_softmax_xent_eval(st, count, tl.C, (const float *)r.tptr(N.t_logits), labels, loss_sum_dev, n_err_dev);
+}
+
+hipError_t net_average_bn(Net *net, hipStream_t st, const float *bn_stats, float *out_row) {
+  return launch_row_mean(st, net->n, net->bn_floats, bn_stats, net->bn_floats, out_row);
+}
+
+hipError_t net_init_bn(Net *net, hipStream_t st, float *bn_stats) {
+  // running mean 0, running variance 1, per replica and layer
+  for (int rep = 0; rep < net->n; ++rep) {
+    for (const Op &op : net->ops) {
+      if (op.type != OP_BNRELU) continue;
+      const int C = net->tensors[op.in].C;
+      float *row = bn_stats + (int64_t)rep * net->bn_floats + op.run_off;
+      HIP_TRY(launch_fill(st, row, C, 0.f));
+      HIP_TRY(launch_fill(st, row + C, C, 1.f));
+    }
+  }
+  return hipSuccess;
+}

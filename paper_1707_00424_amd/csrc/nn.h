@@ -1,0 +1,58 @@
+// Memory-bound layer kernels of the replica-batched networks (all replicas in one launch).
+// dtype: 0 = fp32 activations, 1 = bf16 activations.  Tensors are [replica][rows][C] channels-last;
+// `rs` arguments are replica strides in elements.
+#pragma once
+#include "common.h"
+
+// Softmax cross-entropy.  logits fp32 [n][B][C]; labels [n][B].
+// train: loss_out[n] = mean loss (may be NULL), dlogits (activation dtype) = (softmax - onehot)/B.
+hipError_t launch_softmax_xent_train(hipStream_t st, int dtype, int n, int B, int C, const float *logits,
+                                     long long logits_rs, const int32_t *labels, float *loss_out, void *dlogits,
+                                     long long dl_rs);
+// eval: one parameter set, `count` samples: loss_sum[0] = sum of losses, n_err[0] = #(argmax != label).
+hipError_t launch_softmax_xent_eval(hipStream_t st, int count, int C, const float *logits, const int32_t *labels,
+                                    float *loss_sum, int32_t *n_err);
+
+// 2x2 max-pool, stride 2, floor.  in [n][B,H,W,C] -> out [n][B,H/2,W/2,C].
+hipError_t launch_maxpool_fwd(hipStream_t st, int dtype, int n, int B, int H, int W, int C, const void *in,
+                              long long in_rs, void *out, long long out_rs);
+// din = dout routed to the first maximum of each window, times (in > 0) when relu_mask.
+hipError_t launch_maxpool_bwd(hipStream_t st, int dtype, int n, int B, int H, int W, int C, const void *in,
+                              long long in_rs, const void *dout, long long dout_rs, void *din, long long din_rs,
+                              int relu_mask);
+
+// Global average pool over HW.  in [n][B,HW,C] -> out [n][B,C] (fp32 when out_f32, else activation dtype).
+hipError_t launch_gap_fwd(hipStream_t st, int dtype, bool out_f32, int n, int B, int HW, int C, const void *in,
+                          long long in_rs, void *out, long long out_rs);
+hipError_t launch_gap_bwd(hipStream_t st, int dtype, int n, int B, int HW, int C, const void *dout, long long dout_rs,
+                          void *din, long long din_rs);
+
+// Column sums of dy [n][M][C] (bias gradients): partial [n][S][C] doubles, then grad[rep*grad_rs + c].
+hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, const void *dy, long long dy_rs,
+                            double *partial, float *grad, long long grad_rs);
+int colreduce_splits(int n, int M);
+// out[rep*out_rs + i] = sum_s partial[(rep*S + s)*len + i], i < len.
+hipError_t launch_reduce_partials(hipStream_t st, int n, int S, long long len, const float *partial, float *out,
+                                  long long out_rs);
+
+// Batch normalisation (per replica, per channel, over M rows), fused with the ReLU that follows it.
+// saved: [n][2][C] fp32 = mean, 1/sqrt(var + eps).  running: [2][C] per replica (mean, var), stride run_rs.
+hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
+                               const float *gamma, const float *beta, long long p_rs, double *partial, float *saved,
+                               float *running, long long run_rs, void *out, long long out_rs);
+hipError_t launch_bn_eval_fwd(hipStream_t st, int dtype, int M, int C, const void *x, const float *gamma,
+                              const float *beta, const float *running_row, float *saved, void *out);
+// dx = BN-ReLU backward of dout (+ add when not NULL); dgamma, dbeta written to grad (fp32, stride p_rs).
+hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
+                         const void *dout, long long dout_rs, const float *gamma, const float *beta, long long p_rs,
+                         const float *saved, double *partial, float *sums, float *dgamma, float *dbeta,
+                         const void *add, long long add_rs, void *dx, long long dx_rs);
+
+// wt[ci][(r, s, co)] = w[co][(r, s, ci)] for every replica (operand of the backward-data GEMM).
+hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, int RS, int Cin, const void *w,
+                                   long long w_rs, void *wt, long long wt_rs);
+// dst (activation dtype) = src fp32, `count` elements.
+hipError_t launch_convert(hipStream_t st, int dtype, const float *src, void *dst, long long count);
+hipError_t launch_fill(hipStream_t st, float *dst, long long count, float value);
+// out[i] = mean over replicas of in[rep*rs + i].
+hipError_t launch_row_mean(hipStream_t st, int n, long long len, const float *in, long long rs, float *out);

@@ -1,0 +1,621 @@
+// Memory-bound layer kernels: loss, pooling, batch normalisation, bias gradients, weight transposes.
+// All reductions use a fixed order (per-thread serial, wavefront shuffle, serial over wavefronts and
+// over row-splits), so results are bit-reproducible from run to run.
+#include "nn.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kBnEps = 1e-5f;
+constexpr float kBnMomentum = 0.1f;
+
+template <typename T>
+__device__ __forceinline__ float ldf(const T *p, long long i);
+template <>
+__device__ __forceinline__ float ldf<float>(const float *p, long long i) {
+  return p[i];
+}
+template <>
+__device__ __forceinline__ float ldf<bf16_t>(const bf16_t *p, long long i) {
+  return bf16_to_f32(p[i]);
+}
+template <typename T>
+__device__ __forceinline__ void stf(T *p, long long i, float v);
+template <>
+__device__ __forceinline__ void stf<float>(float *p, long long i, float v) {
+  p[i] = v;
+}
+template <>
+__device__ __forceinline__ void stf<bf16_t>(bf16_t *p, long long i, float v) {
+  p[i] = f32_to_bf16(v);
+}
+
+inline int blocks_for(long long items, int cap = 65535 * 16) {
+  long long b = (items + kThreads - 1) / kThreads;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (int)b;
+}
+
+// ------------------------------------------------------------------ softmax cross-entropy
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_softmax_train(int B, int C, const float *__restrict__ logits,
+                                                            long long logits_rs, const int32_t *__restrict__ labels,
+                                                            float *__restrict__ loss_out, T *__restrict__ dl,
+                                                            long long dl_rs) {
+  __shared__ float red[kThreads / PARLE_WAVE];
+  const int rep = blockIdx.x;
+  const float *lg = logits + rep * logits_rs;
+  const int32_t *lab = labels + (long long)rep * B;
+  T *d = dl + rep * dl_rs;
+  const float invB = 1.0f / (float)B;
+  float loss = 0.f;
+  for (int b = threadIdx.x; b < B; b += kThreads) {
+    const float *row = lg + (long long)b * C;
+    float mx = row[0];
+    for (int c = 1; c < C; ++c) mx = fmaxf(mx, row[c]);
+    float se = 0.f;
+    for (int c = 0; c < C; ++c) se += expf(row[c] - mx);
+    const float lse = logf(se) + mx;
+    const int y = lab[b];
+    loss += lse - row[y];
+    for (int c = 0; c < C; ++c) {
+      const float p = expf(row[c] - lse);
+      stf<T>(d, (long long)b * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
+    }
+  }
+  loss = wave_sum(loss);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) red[threadIdx.x / PARLE_WAVE] = loss;
+  __syncthreads();
+  if (threadIdx.x == 0 && loss_out) {
+    float s = 0.f;
+    for (int w = 0; w < kThreads / PARLE_WAVE; ++w) s += red[w];
+    loss_out[rep] = s * invB;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_softmax_eval(int count, int C, const float *__restrict__ logits,
+                                                           const int32_t *__restrict__ labels,
+                                                           float *__restrict__ loss_sum, int32_t *__restrict__ n_err) {
+  __shared__ double red[kThreads / PARLE_WAVE];
+  __shared__ int redi[kThreads / PARLE_WAVE];
+  double loss = 0.0;
+  int err = 0;
+  for (int b = threadIdx.x; b < count; b += kThreads) {
+    const float *row = logits + (long long)b * C;
+    float mx = row[0];
+    int arg = 0;
+    for (int c = 1; c < C; ++c)
+      if (row[c] > mx) mx = row[c], arg = c;
+    float se = 0.f;
+    for (int c = 0; c < C; ++c) se += expf(row[c] - mx);
+    const int y = labels[b];
+    loss += (double)(logf(se) + mx - row[y]);
+    err += arg != y;
+  }
+  loss = wave_sum(loss);
+  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) err += __shfl_down(err, off, PARLE_WAVE);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) red[threadIdx.x / PARLE_WAVE] = loss, redi[threadIdx.x / PARLE_WAVE] = err;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    int e = 0;
+    for (int w = 0; w < kThreads / PARLE_WAVE; ++w) s += red[w], e += redi[w];
+    loss_sum[0] = (float)s;
+    n_err[0] = e;
+  }
+}
+
+// ------------------------------------------------------------------ pooling
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_maxpool_fwd(int B, int H, int W, int C, const T *__restrict__ in,
+                                                          long long in_rs, T *__restrict__ out, long long out_rs) {
+  const int Ho = H / 2, Wo = W / 2;
+  const long long total = (long long)B * Ho * Wo * C;
+  const T *x = in + blockIdx.y * in_rs;
+  T *o = out + blockIdx.y * out_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    long long t = i / C;
+    const int wo = t % Wo;
+    t /= Wo;
+    const int ho = t % Ho;
+    const int b = t / Ho;
+    const long long base = (((long long)b * H + 2 * ho) * W + 2 * wo) * C + c;
+    float m = ldf<T>(x, base);
+    m = fmaxf(m, ldf<T>(x, base + C));
+    m = fmaxf(m, ldf<T>(x, base + (long long)W * C));
+    m = fmaxf(m, ldf<T>(x, base + (long long)W * C + C));
+    stf<T>(o, i, m);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_maxpool_bwd(int B, int H, int W, int C, const T *__restrict__ in,
+                                                          long long in_rs, const T *__restrict__ dout,
+                                                          long long dout_rs, T *__restrict__ din, long long din_rs,
+                                                          int relu_mask) {
+  const int Ho = H / 2, Wo = W / 2;
+  const long long total = (long long)B * H * W * C;
+  const T *x = in + blockIdx.y * in_rs;
+  const T *dy = dout + blockIdx.y * dout_rs;
+  T *dx = din + blockIdx.y * din_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    long long t = i / C;
+    const int w = t % W;
+    t /= W;
+    const int h = t % H;
+    const int b = t / H;
+    const int ho = h >> 1, wo = w >> 1;
+    float g = 0.f;
+    if (ho < Ho && wo < Wo) {
+      const long long base = (((long long)b * H + 2 * ho) * W + 2 * wo) * C + c;
+      const float v0 = ldf<T>(x, base), v1 = ldf<T>(x, base + C), v2 = ldf<T>(x, base + (long long)W * C),
+                  v3 = ldf<T>(x, base + (long long)W * C + C);
+      int arg = 0;
+      float m = v0;
+      if (v1 > m) m = v1, arg = 1;
+      if (v2 > m) m = v2, arg = 2;
+      if (v3 > m) m = v3, arg = 3;
+      const int mine = (h & 1) * 2 + (w & 1);
+      if (mine == arg && (!relu_mask || m > 0.f)) g = ldf<T>(dy, (((long long)b * Ho + ho) * Wo + wo) * C + c);
+    }
+    stf<T>(dx, i, g);
+  }
+}
+
+template <typename T, bool OUT_F32>
+__global__ __launch_bounds__(kThreads) void k_gap_fwd(int B, int HW, int C, const T *__restrict__ in, long long in_rs,
+                                                      void *__restrict__ out, long long out_rs) {
+  const long long total = (long long)B * C;
+  const T *x = in + blockIdx.y * in_rs;
+  const float inv = 1.0f / (float)HW;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    const long long b = i / C;
+    float s = 0.f;
+    for (int p = 0; p < HW; ++p) s += ldf<T>(x, (b * HW + p) * C + c);
+    if (OUT_F32)
+      ((float *)out)[blockIdx.y * out_rs + i] = s * inv;
+    else
+      stf<T>((T *)out + blockIdx.y * out_rs, i, s * inv);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_gap_bwd(int B, int HW, int C, const T *__restrict__ dout,
+                                                      long long dout_rs, T *__restrict__ din, long long din_rs) {
+  const long long total = (long long)B * HW * C;
+  const T *dy = dout + blockIdx.y * dout_rs;
+  T *dx = din + blockIdx.y * din_rs;
+  const float inv = 1.0f / (float)HW;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    const long long b = i / ((long long)HW * C);
+    stf<T>(dx, i, ldf<T>(dy, b * C + c) * inv);
+  }
+}
+
+// ------------------------------------------------------------------ column reductions over rows
+// MODE 0: s1 = sum x.  MODE 1: s1 = sum x, s2 = sum x^2.
+// MODE 2: BN-ReLU backward sums: xhat = (x - mean) rstd, pre = xhat gamma + beta, d = pre > 0 ? dy : 0;
+//         s1 = sum d, s2 = sum d * xhat.
+// partial layout: [rep][split][2][C] doubles.  ct = channel lanes (power of two <= 64).
+template <typename T, int MODE>
+__global__ __launch_bounds__(kThreads) void k_colreduce(int M, int C, int chunk, int ct, const T *__restrict__ x,
+                                                        long long x_rs, const T *__restrict__ dy, long long dy_rs,
+                                                        const float *__restrict__ saved, const float *__restrict__ gamma,
+                                                        const float *__restrict__ beta, long long p_rs,
+                                                        double *__restrict__ partial) {
+  __shared__ float red[2][kThreads];
+  const int rep = blockIdx.y, split = blockIdx.x, S = gridDim.x;
+  const int tr = kThreads / ct;
+  const int lc = threadIdx.x % ct, lr = threadIdx.x / ct;
+  const int r0 = split * chunk, r1 = min(M, r0 + chunk);
+  const T *xp = x + rep * x_rs;
+  const T *dp = MODE == 2 ? dy + rep * dy_rs : nullptr;
+  double *out = partial + ((long long)rep * S + split) * 2 * C;
+  for (int cb = 0; cb < C; cb += ct) {
+    const int c = cb + lc;
+    float s1 = 0.f, s2 = 0.f;
+    if (c < C) {
+      float mean = 0.f, rstd = 0.f, gm = 0.f, bt = 0.f;
+      if (MODE == 2) {
+        mean = saved[(long long)rep * 2 * C + c];
+        rstd = saved[(long long)rep * 2 * C + C + c];
+        gm = gamma[rep * p_rs + c];
+        bt = beta[rep * p_rs + c];
+      }
+      for (int r = r0 + lr; r < r1; r += tr) {
+        const float v = ldf<T>(xp, (long long)r * C + c);
+        if (MODE == 0) {
+          s1 += v;
+        } else if (MODE == 1) {
+          s1 += v;
+          s2 += v * v;
+        } else {
+          const float xh = (v - mean) * rstd;
+          const float d = (xh * gm + bt) > 0.f ? ldf<T>(dp, (long long)r * C + c) : 0.f;
+          s1 += d;
+          s2 += d * xh;
+        }
+      }
+    }
+    red[0][threadIdx.x] = s1;
+    red[1][threadIdx.x] = s2;
+    __syncthreads();
+    if (lr == 0 && c < C) {
+      double a1 = 0.0, a2 = 0.0;
+      for (int j = 0; j < tr; ++j) a1 += (double)red[0][j * ct + lc], a2 += (double)red[1][j * ct + lc];
+      out[c] = a1;
+      out[C + c] = a2;
+    }
+    __syncthreads();
+  }
+}
+
+// bias gradient: grad[c] = sum over splits of s1
+__global__ __launch_bounds__(kThreads) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
+                                                            float *__restrict__ grad, long long grad_rs) {
+  const int rep = blockIdx.y;
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  double s = 0.0;
+  for (int sp = 0; sp < S; ++sp) s += partial[((long long)rep * S + sp) * 2 * C + c];
+  grad[rep * grad_rs + c] = (float)s;
+}
+
+__global__ __launch_bounds__(kThreads) void k_bn_stats_finalize(int M, int C, int S, const double *__restrict__ partial,
+                                                                float *__restrict__ saved, float *__restrict__ running,
+                                                                long long run_rs) {
+  const int rep = blockIdx.y;
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int sp = 0; sp < S; ++sp) {
+    s1 += partial[((long long)rep * S + sp) * 2 * C + c];
+    s2 += partial[((long long)rep * S + sp) * 2 * C + C + c];
+  }
+  const double mean = s1 / M;
+  double var = s2 / M - mean * mean;
+  if (var < 0.0) var = 0.0;
+  saved[(long long)rep * 2 * C + c] = (float)mean;
+  saved[(long long)rep * 2 * C + C + c] = (float)(1.0 / sqrt(var + (double)kBnEps));
+  if (running) {
+    float *rm = running + rep * run_rs, *rv = rm + C;
+    const double unbiased = M > 1 ? var * ((double)M / (M - 1)) : var;
+    rm[c] = (1.f - kBnMomentum) * rm[c] + kBnMomentum * (float)mean;
+    rv[c] = (1.f - kBnMomentum) * rv[c] + kBnMomentum * (float)unbiased;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_bn_eval_prepare(int C, const float *__restrict__ running_row,
+                                                              float *__restrict__ saved) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  saved[c] = running_row[c];
+  saved[C + c] = 1.0f / sqrtf(running_row[C + c] + kBnEps);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_bn_apply_relu(int M, int C, const T *__restrict__ x, long long x_rs,
+                                                            const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, long long p_rs,
+                                                            const float *__restrict__ saved, T *__restrict__ out,
+                                                            long long out_rs) {
+  const int rep = blockIdx.y;
+  const long long total = (long long)M * C;
+  const T *xp = x + rep * x_rs;
+  T *op = out + rep * out_rs;
+  const float *mean = saved + (long long)rep * 2 * C, *rstd = mean + C;
+  const float *gm = gamma + rep * p_rs, *bt = beta + rep * p_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    const float v = (ldf<T>(xp, i) - mean[c]) * rstd[c] * gm[c] + bt[c];
+    stf<T>(op, i, v > 0.f ? v : 0.f);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
+                                                              float *__restrict__ sums, float *__restrict__ dgamma,
+                                                              float *__restrict__ dbeta, long long p_rs) {
+  const int rep = blockIdx.y;
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int sp = 0; sp < S; ++sp) {
+    s1 += partial[((long long)rep * S + sp) * 2 * C + c];
+    s2 += partial[((long long)rep * S + sp) * 2 * C + C + c];
+  }
+  sums[(long long)rep * 2 * C + c] = (float)s1;
+  sums[(long long)rep * 2 * C + C + c] = (float)s2;
+  dbeta[rep * p_rs + c] = (float)s1;
+  dgamma[rep * p_rs + c] = (float)s2;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(int M, int C, const T *__restrict__ x, long long x_rs,
+                                                           const T *__restrict__ dout, long long dout_rs,
+                                                           const float *__restrict__ gamma,
+                                                           const float *__restrict__ beta, long long p_rs,
+                                                           const float *__restrict__ saved,
+                                                           const float *__restrict__ sums, const T *__restrict__ add,
+                                                           long long add_rs, T *__restrict__ dx, long long dx_rs) {
+  const int rep = blockIdx.y;
+  const long long total = (long long)M * C;
+  const T *xp = x + rep * x_rs;
+  const T *dp = dout + rep * dout_rs;
+  const T *ap = add ? add + rep * add_rs : nullptr;
+  T *op = dx + rep * dx_rs;
+  const float *mean = saved + (long long)rep * 2 * C, *rstd = mean + C;
+  const float *s1 = sums + (long long)rep * 2 * C, *s2 = s1 + C;
+  const float *gm = gamma + rep * p_rs, *bt = beta + rep * p_rs;
+  const float invM = 1.0f / (float)M;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c = i % C;
+    const float xh = (ldf<T>(xp, i) - mean[c]) * rstd[c];
+    const float d = (xh * gm[c] + bt[c]) > 0.f ? ldf<T>(dp, i) : 0.f;
+    float v = gm[c] * rstd[c] * (d - s1[c] * invM - xh * s2[c] * invM);
+    if (ap) v += ldf<T>(ap, i);
+    stf<T>(op, i, v);
+  }
+}
+
+// ------------------------------------------------------------------ small utilities
+__global__ __launch_bounds__(kThreads) void k_reduce_partials(int S, long long len, const float *__restrict__ partial,
+                                                              float *__restrict__ out, long long out_rs) {
+  const int rep = blockIdx.y;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < len; i += (long long)gridDim.x * kThreads) {
+    float s = 0.f;
+    for (int sp = 0; sp < S; ++sp) s += partial[((long long)rep * S + sp) * len + i];
+    out[rep * out_rs + i] = s;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_weight_transpose(int Cout, int RS, int Cin, const T *__restrict__ w,
+                                                               long long w_rs, T *__restrict__ wt, long long wt_rs) {
+  const long long total = (long long)Cout * RS * Cin;
+  const T *src = w + blockIdx.y * w_rs;
+  T *dst = wt + blockIdx.y * wt_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int co = i % Cout;
+    long long t = i / Cout;
+    const int rs = t % RS;
+    const int ci = t / RS;
+    dst[i] = src[((long long)co * RS + rs) * Cin + ci];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_convert(const float *__restrict__ src, T *__restrict__ dst,
+                                                      long long count) {
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < count; i += (long long)gridDim.x * kThreads)
+    stf<T>(dst, i, src[i]);
+}
+
+__global__ __launch_bounds__(kThreads) void k_fill(float *__restrict__ dst, long long count, float v) {
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < count; i += (long long)gridDim.x * kThreads)
+    dst[i] = v;
+}
+
+__global__ __launch_bounds__(kThreads) void k_row_mean(int n, long long len, const float *__restrict__ in, long long rs,
+                                                       float *__restrict__ out) {
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < len; i += (long long)gridDim.x * kThreads) {
+    float s = 0.f;
+    for (int a = 0; a < n; ++a) s += in[a * rs + i];
+    out[i] = s / (float)n;
+  }
+}
+
+int channel_lanes(int C) {
+  int ct = 1;
+  while (ct < C && ct < 64) ct <<= 1;
+  return ct;
+}
+
+int col_chunk(int M, int S) {
+  int chunk = (M + S - 1) / S;
+  return chunk < 1 ? 1 : chunk;
+}
+
+}  // namespace
+
+#define DISPATCH_T(dtype, CALL_F32, CALL_BF16) \
+  do {                                         \
+    if ((dtype) == 0) {                        \
+      CALL_F32;                                \
+    } else {                                   \
+      CALL_BF16;                               \
+    }                                          \
+  } while (0)
+
+hipError_t launch_softmax_xent_train(hipStream_t st, int dtype, int n, int B, int C, const float *logits,
+                                     long long logits_rs, const int32_t *labels, float *loss_out, void *dlogits,
+                                     long long dl_rs) {
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_softmax_train<float>, dim3(n), dim3(kThreads), 0, st, B, C, logits, logits_rs, labels,
+                                loss_out, (float *)dlogits, dl_rs),
+             hipLaunchKernelGGL(k_softmax_train<bf16_t>, dim3(n), dim3(kThreads), 0, st, B, C, logits, logits_rs,
+                                labels, loss_out, (bf16_t *)dlogits, dl_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_xent_eval(hipStream_t st, int count, int C, const float *logits, const int32_t *labels,
+                                    float *loss_sum, int32_t *n_err) {
+  hipLaunchKernelGGL(k_softmax_eval, dim3(1), dim3(kThreads), 0, st, count, C, logits, labels, loss_sum, n_err);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(hipStream_t st, int dtype, int n, int B, int H, int W, int C, const void *in,
+                              long long in_rs, void *out, long long out_rs) {
+  dim3 grid(blocks_for((long long)B * (H / 2) * (W / 2) * C, 65535), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_maxpool_fwd<float>, grid, dim3(kThreads), 0, st, B, H, W, C, (const float *)in, in_rs,
+                                (float *)out, out_rs),
+             hipLaunchKernelGGL(k_maxpool_fwd<bf16_t>, grid, dim3(kThreads), 0, st, B, H, W, C, (const bf16_t *)in,
+                                in_rs, (bf16_t *)out, out_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(hipStream_t st, int dtype, int n, int B, int H, int W, int C, const void *in,
+                              long long in_rs, const void *dout, long long dout_rs, void *din, long long din_rs,
+                              int relu_mask) {
+  dim3 grid(blocks_for((long long)B * H * W * C, 65535), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_maxpool_bwd<float>, grid, dim3(kThreads), 0, st, B, H, W, C, (const float *)in, in_rs,
+                                (const float *)dout, dout_rs, (float *)din, din_rs, relu_mask),
+             hipLaunchKernelGGL(k_maxpool_bwd<bf16_t>, grid, dim3(kThreads), 0, st, B, H, W, C, (const bf16_t *)in,
+                                in_rs, (const bf16_t *)dout, dout_rs, (bf16_t *)din, din_rs, relu_mask));
+  return hipGetLastError();
+}
+
+hipError_t launch_gap_fwd(hipStream_t st, int dtype, bool out_f32, int n, int B, int HW, int C, const void *in,
+                          long long in_rs, void *out, long long out_rs) {
+  dim3 grid(blocks_for((long long)B * C, 65535), n);
+  if (dtype == 0) {
+    hipLaunchKernelGGL((k_gap_fwd<float, true>), grid, dim3(kThreads), 0, st, B, HW, C, (const float *)in, in_rs, out,
+                       out_rs);
+  } else if (out_f32) {
+    hipLaunchKernelGGL((k_gap_fwd<bf16_t, true>), grid, dim3(kThreads), 0, st, B, HW, C, (const bf16_t *)in, in_rs, out,
+                       out_rs);
+  } else {
+    hipLaunchKernelGGL((k_gap_fwd<bf16_t, false>), grid, dim3(kThreads), 0, st, B, HW, C, (const bf16_t *)in, in_rs,
+                       out, out_rs);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gap_bwd(hipStream_t st, int dtype, int n, int B, int HW, int C, const void *dout, long long dout_rs,
+                          void *din, long long din_rs) {
+  dim3 grid(blocks_for((long long)B * HW * C, 65535), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_gap_bwd<float>, grid, dim3(kThreads), 0, st, B, HW, C, (const float *)dout, dout_rs,
+                                (float *)din, din_rs),
+             hipLaunchKernelGGL(k_gap_bwd<bf16_t>, grid, dim3(kThreads), 0, st, B, HW, C, (const bf16_t *)dout, dout_rs,
+                                (bf16_t *)din, din_rs));
+  return hipGetLastError();
+}
+
+int colreduce_splits(int n, int M) {
+  // enough workgroups to fill the chip, at least 64 rows per split
+  int want = (1024 + n - 1) / n;
+  int maxs = (M + 63) / 64;
+  if (want > maxs) want = maxs;
+  if (want < 1) want = 1;
+  if (want > 1024) want = 1024;
+  return want;
+}
+
+hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, const void *dy, long long dy_rs,
+                            double *partial, float *grad, long long grad_rs) {
+  const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
+  dim3 grid(S, n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL((k_colreduce<float, 0>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)dy,
+                                dy_rs, (const float *)nullptr, 0LL, (const float *)nullptr, (const float *)nullptr,
+                                (const float *)nullptr, 0LL, partial),
+             hipLaunchKernelGGL((k_colreduce<bf16_t, 0>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
+                                (const bf16_t *)dy, dy_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
+                                (const float *)nullptr, (const float *)nullptr, 0LL, partial));
+  hipLaunchKernelGGL(k_bias_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, C, S, partial, grad,
+                     grad_rs);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(hipStream_t st, int n, int S, long long len, const float *partial, float *out,
+                                  long long out_rs) {
+  hipLaunchKernelGGL(k_reduce_partials, dim3(blocks_for(len, 65535), n), dim3(kThreads), 0, st, S, len, partial, out,
+                     out_rs);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
+                               const float *gamma, const float *beta, long long p_rs, double *partial, float *saved,
+                               float *running, long long run_rs, void *out, long long out_rs) {
+  const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
+  dim3 grid(S, n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL((k_colreduce<float, 1>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)x,
+                                x_rs, (const float *)nullptr, 0LL, (const float *)nullptr, (const float *)nullptr,
+                                (const float *)nullptr, 0LL, partial),
+             hipLaunchKernelGGL((k_colreduce<bf16_t, 1>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
+                                (const bf16_t *)x, x_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
+                                (const float *)nullptr, (const float *)nullptr, 0LL, partial));
+  hipLaunchKernelGGL(k_bn_stats_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, M, C, S,
+                     partial, saved, running, run_rs);
+  dim3 agrid(blocks_for((long long)M * C, 4096), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_bn_apply_relu<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs, gamma,
+                                beta, p_rs, saved, (float *)out, out_rs),
+             hipLaunchKernelGGL(k_bn_apply_relu<bf16_t>, agrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)x, x_rs,
+                                gamma, beta, p_rs, saved, (bf16_t *)out, out_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_eval_fwd(hipStream_t st, int dtype, int M, int C, const void *x, const float *gamma,
+                              const float *beta, const float *running_row, float *saved, void *out) {
+  hipLaunchKernelGGL(k_bn_eval_prepare, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, C, running_row,
+                     saved);
+  dim3 agrid(blocks_for((long long)M * C, 4096), 1);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_bn_apply_relu<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, 0LL, gamma,
+                                beta, 0LL, saved, (float *)out, 0LL),
+             hipLaunchKernelGGL(k_bn_apply_relu<bf16_t>, agrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)x, 0LL,
+                                gamma, beta, 0LL, saved, (bf16_t *)out, 0LL));
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
+                         const void *dout, long long dout_rs, const float *gamma, const float *beta, long long p_rs,
+                         const float *saved, double *partial, float *sums, float *dgamma, float *dbeta,
+                         const void *add, long long add_rs, void *dx, long long dx_rs) {
+  const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
+  dim3 grid(S, n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL((k_colreduce<float, 2>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)x,
+                                x_rs, (const float *)dout, dout_rs, saved, gamma, beta, p_rs, partial),
+             hipLaunchKernelGGL((k_colreduce<bf16_t, 2>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
+                                (const bf16_t *)x, x_rs, (const bf16_t *)dout, dout_rs, saved, gamma, beta, p_rs,
+                                partial));
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, C, S, partial,
+                     sums, dgamma, dbeta, p_rs);
+  dim3 agrid(blocks_for((long long)M * C, 4096), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_bn_bwd_apply<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs,
+                                (const float *)dout, dout_rs, gamma, beta, p_rs, saved, sums, (const float *)add, add_rs,
+                                (float *)dx, dx_rs),
+             hipLaunchKernelGGL(k_bn_bwd_apply<bf16_t>, agrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)x, x_rs,
+                                (const bf16_t *)dout, dout_rs, gamma, beta, p_rs, saved, sums, (const bf16_t *)add,
+                                add_rs, (bf16_t *)dx, dx_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, int RS, int Cin, const void *w,
+                                   long long w_rs, void *wt, long long wt_rs) {
+  dim3 grid(blocks_for((long long)Cout * RS * Cin, 65535), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_weight_transpose<float>, grid, dim3(kThreads), 0, st, Cout, RS, Cin, (const float *)w,
+                                w_rs, (float *)wt, wt_rs),
+             hipLaunchKernelGGL(k_weight_transpose<bf16_t>, grid, dim3(kThreads), 0, st, Cout, RS, Cin,
+                                (const bf16_t *)w, w_rs, (bf16_t *)wt, wt_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_convert(hipStream_t st, int dtype, const float *src, void *dst, long long count) {
+  dim3 grid(blocks_for(count, 65535));
+  DISPATCH_T(dtype, hipLaunchKernelGGL(k_convert<float>, grid, dim3(kThreads), 0, st, src, (float *)dst, count),
+             hipLaunchKernelGGL(k_convert<bf16_t>, grid, dim3(kThreads), 0, st, src, (bf16_t *)dst, count));
+  return hipGetLastError();
+}
+
+hipError_t launch_fill(hipStream_t st, float *dst, long long count, float value) {
+  hipLaunchKernelGGL(k_fill, dim3(blocks_for(count, 65535)), dim3(kThreads), 0, st, dst, count, value);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_mean(hipStream_t st, int n, long long len, const float *in, long long rs, float *out) {
+  hipLaunchKernelGGL(k_row_mean, dim3(blocks_for(len, 65535)), dim3(kThreads), 0, st, n, len, in, rs, out);
+  return hipGetLastError();
+}

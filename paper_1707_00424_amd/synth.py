@@ -58,14 +58,18 @@ def flat_grads(seed: int, step: int, n: int, n_params: int, std: float = 1e-2) -
     return out
 
 
-def init_params(layout, seed: int) -> np.ndarray:
+def init_params(layout, seed: int, weight_init: str = "he_normal") -> np.ndarray:
     """Draw one replica's initial parameters, float32 ``[sum of segment sizes]``.
 
     ``layout`` is a sequence of dicts with keys ``name``, ``shape``, ``kind`` and
-    ``fan_in``.  kind ``weight``: N(0, 2/fan_in) (keeps activation scale through
-    ReLU layers); ``bias``: U(-1/sqrt(fan_in), 1/sqrt(fan_in)); ``bn_gamma``:
+    ``fan_in``.  kind ``weight``: N(0, 2/fan_in) for ``weight_init="he_normal"``
+    (keeps the activation scale through ReLU layers; used for the deep
+    convolutional networks) or U(-1/sqrt(fan_in), 1/sqrt(fan_in)) for
+    ``"uniform"`` (the default initialisation of the framework the paper's
+    implementation used; used for the MLP and LeNet, which train stably with it
+    at step size 0.1); ``bias``: U(-1/sqrt(fan_in), 1/sqrt(fan_in)); ``bn_gamma``:
     1 + 0.1 N(0,1); ``bn_beta``: 0.1 N(0,1).  Segments are drawn in order from
-    one generator, so the vector depends only on (layout, seed).
+    one generator, so the vector depends only on (layout, seed, weight_init).
     """
     rng = np.random.default_rng([seed, 5005])
     parts = []
@@ -73,8 +77,13 @@ def init_params(layout, seed: int) -> np.ndarray:
         size = int(np.prod(seg["shape"]))
         kind = seg["kind"]
         fan_in = float(seg["fan_in"])
-        if kind == "weight":
+        if kind == "weight" and weight_init == "uniform":
+            b = 1.0 / np.sqrt(fan_in)
+            v = rng.uniform(-b, b, size)
+        elif kind == "weight" and weight_init == "he_normal":
             v = rng.standard_normal(size) * np.sqrt(2.0 / fan_in)
+        elif kind == "weight":
+            raise ValueError(f"unknown weight_init {weight_init!r}")
         elif kind == "bias":
             b = 1.0 / np.sqrt(fan_in)
             v = rng.uniform(-b, b, size)

@@ -1,0 +1,184 @@
+"""Single-kernel parity of the replica-grouped convolution kernels (forward, backward-data,
+backward-weight) against the oracle's convolution, through the C ABI.
+
+For bf16 the inputs are drawn on the bf16 grid, so both sides see exactly the same numbers and no
+ReLU decision depends on input rounding; what remains is the accumulation order (fp32 on the MFMA
+units vs float64) and the final rounding of bf16 outputs (half an ulp = 2^-9 relative).
+"""
+import numpy as np
+import pytest
+
+from oracle import nets as onets
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1707_00424_amd import binding as pb
+    pb.lib()
+    return torch, pb
+
+
+def to_bf16_grid(a):
+    """Round float32 values to the nearest bf16 (ties to even), returned as float32."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32)
+
+
+def upload(torch, a, dtype):
+    t = torch.as_tensor(np.ascontiguousarray(a, np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if dtype else t.contiguous()
+
+
+def download(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def oracle_conv(x, w, bias, resid, relu, stride, pad, dy=None, mask_relu_input=False):
+    """Forward output and (if dy given) input / weight gradients of one replica, float64."""
+    t = onets.Tape()
+    xv, wv = onets.Var(x.astype(np.float64)), onets.Var(w.astype(np.float64))
+    bv = onets.Var(bias.astype(np.float64)) if bias is not None else None
+    o = onets.conv2d(t, xv, wv, bv, stride, pad)
+    if resid is not None:
+        o = onets.add(t, o, onets.Var(resid.astype(np.float64)))
+    if relu:
+        o = onets.relu(t, o)
+    if dy is None:
+        return o.v, None, None
+    o.g = dy.astype(np.float64)
+    t.backward()
+    return o.v, xv.g, wv.g
+
+
+CASES = [
+    # n, B, H, W, Cin, Cout, k, stride, pad
+    (2, 3, 9, 7, 3, 10, 3, 1, 1),       # scalar gathers, narrow output
+    (2, 5, 8, 8, 8, 16, 3, 1, 1),       # vector gathers
+    (3, 4, 11, 9, 16, 48, 3, 2, 1),     # stride 2, odd extent
+    (2, 2, 12, 12, 24, 96, 3, 1, 1),    # 96-wide tile
+    (2, 2, 8, 8, 40, 100, 3, 2, 1),     # 128-wide tile with a ragged edge
+    (2, 6, 6, 6, 32, 200, 1, 1, 0),     # 1x1, two 128-wide tiles
+    (2, 3, 10, 10, 5, 7, 5, 1, 0),      # 5x5 valid, odd channels
+    (2, 37, 1, 1, 136, 72, 1, 1, 0),    # fully connected
+    (1, 2, 8, 8, 16, 32, 1, 2, 0),      # strided 1x1 (shortcut)
+]
+
+
+def tolerances(dtype, ref):
+    scale = np.abs(ref).max()
+    if dtype == 0:
+        return 0.0, 2e-5 * scale
+    return 2.0 ** -8, 2e-5 * scale
+
+
+def assert_near(name, got, ref, rel, absol):
+    err = np.abs(got - ref)
+    bound = rel * np.abs(ref) + absol
+    bad = err > bound
+    assert not bad.any(), f"{name}: {bad.sum()} of {bad.size} outside tolerance, worst {np.max(err - bound):.3e}"
+
+
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_conv_kernels_match_oracle(gpu, case, dtype):
+    torch, pb = gpu
+    n, B, H, W, Cin, Cout, k, stride, pad = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    q = to_bf16_grid if dtype else (lambda a: np.asarray(a, np.float32))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    x = q(rng.standard_normal((n, B, H, W, Cin)))
+    w = q(rng.standard_normal((n, Cout, k, k, Cin)) / np.sqrt(k * k * Cin))
+    bias = rng.standard_normal((n, Cout)).astype(np.float32)
+    resid = q(rng.standard_normal((n, B, Ho, Wo, Cout)))
+    dy = q(rng.standard_normal((n, B, Ho, Wo, Cout)))
+    mask = q(rng.standard_normal((n, B, H, W, Cin)))
+    prev = q(rng.standard_normal((n, B, H, W, Cin)))
+    desc = pb.parle_conv_desc(dtype, n, B, H, W, Cin, Cout, k, stride, pad)
+    tdt = torch.bfloat16 if dtype else torch.float32
+    dx_, dw_, dres = upload(torch, x, dtype), upload(torch, w, dtype), upload(torch, resid, dtype)
+    dbias, ddy, dmask = upload(torch, bias, 0), upload(torch, dy, dtype), upload(torch, mask, dtype)
+
+    # forward: plain, and with bias + residual + ReLU
+    y1 = torch.zeros((n, B, Ho, Wo, Cout), dtype=tdt, device="cuda")
+    y2 = torch.zeros_like(y1)
+    pb.parle_k_conv_forward(desc, dx_, dw_, None, None, 0, y1)
+    pb.parle_k_conv_forward(desc, dx_, dw_, dbias, dres, 1, y2)
+    # backward data: plain write, then masked accumulate onto an existing gradient
+    wt = torch.zeros(n * Cout * k * k * Cin, dtype=tdt, device="cuda")
+    g1 = torch.zeros((n, B, H, W, Cin), dtype=tdt, device="cuda")
+    g2 = upload(torch, prev, dtype)
+    pb.parle_k_conv_backward_data(desc, ddy, dw_, None, 0, wt, g1)
+    pb.parle_k_conv_backward_data(desc, ddy, dw_, dmask, 1, wt, g2)
+    # backward weight
+    sb = pb.parle_k_conv_scratch_bytes(desc)
+    scratch = torch.zeros(max(sb // 4, 4), dtype=torch.float32, device="cuda")
+    gw = torch.zeros((n, Cout, k, k, Cin), dtype=torch.float32, device="cuda")
+    pb.parle_k_conv_backward_weight(desc, ddy, dx_, scratch, gw)
+    torch.cuda.synchronize()
+
+    for r in range(n):
+        ref1, rdx, rdw = oracle_conv(x[r], w[r], None, None, False, stride, pad, dy[r])
+        ref2, _, _ = oracle_conv(x[r], w[r], bias[r], resid[r], True, stride, pad)
+        assert_near(f"fwd[{r}]", download(y1[r]), ref1, *tolerances(dtype, ref1))
+        assert_near(f"fwd+epilogue[{r}]", download(y2[r]), ref2, *tolerances(dtype, ref2))
+        assert_near(f"dgrad[{r}]", download(g1[r]), rdx, *tolerances(dtype, rdx))
+        ref_acc = prev[r].astype(np.float64) + rdx * (mask[r] > 0)
+        rel, ab = tolerances(dtype, ref_acc)
+        assert_near(f"dgrad masked accumulate[{r}]", download(g2[r]), ref_acc, rel, ab)
+        assert_near(f"wgrad[{r}]", download(gw[r]), rdw, 0.0, 2e-5 * np.abs(rdw).max())
+
+
+@pytest.mark.parametrize("layer", [
+    # full-size layers of the bf16 workloads, batch 128, n = 3 (the launch shapes the bench times)
+    (3, 128, 32, 32, 96, 96, 3, 1, 1),      # All-CNN-C conv2
+    (3, 128, 16, 16, 192, 192, 3, 2, 1),    # All-CNN-C conv6 (stride 2)
+    (3, 128, 32, 32, 16, 64, 3, 1, 1),      # WRN-16-4 group 1
+    (3, 128, 8, 8, 256, 256, 3, 1, 1),      # WRN-16-4 group 3
+])
+def test_full_size_layers_sampled(gpu, layer):
+    """Forward and backward-data are checked on sampled images (rows are independent); the weight
+    gradient on sampled (output channel, input channel) pairs, each summed over all 128 images."""
+    torch, pb = gpu
+    n, B, H, W, Cin, Cout, k, stride, pad = layer
+    dtype = 1
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    bf = torch.bfloat16
+    x = torch.randn((n, B, H, W, Cin), generator=gen, device="cuda").to(bf)
+    w = (torch.randn((n, Cout, k, k, Cin), generator=gen, device="cuda") / np.sqrt(k * k * Cin)).to(bf)
+    dy = torch.randn((n, B, Ho, Wo, Cout), generator=gen, device="cuda").to(bf)
+    desc = pb.parle_conv_desc(dtype, n, B, H, W, Cin, Cout, k, stride, pad)
+    y = torch.zeros((n, B, Ho, Wo, Cout), dtype=bf, device="cuda")
+    dx = torch.zeros((n, B, H, W, Cin), dtype=bf, device="cuda")
+    wt = torch.zeros(n * Cout * k * k * Cin, dtype=bf, device="cuda")
+    gw = torch.zeros((n, Cout, k, k, Cin), dtype=torch.float32, device="cuda")
+    scratch = torch.zeros(max(pb.parle_k_conv_scratch_bytes(desc) // 4, 4), dtype=torch.float32, device="cuda")
+    pb.parle_k_conv_forward(desc, x, w, None, None, 0, y)
+    pb.parle_k_conv_backward_data(desc, dy, w, None, 0, wt, dx)
+    pb.parle_k_conv_backward_weight(desc, dy, x, scratch, gw)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    for r in (0, n - 1):
+        wr = download(w[r])
+        for b in (0, int(rng.integers(1, B - 1)), B - 1):
+            ry, rdx, _ = oracle_conv(download(x[r, b:b + 1]), wr, None, None, False, stride, pad, download(dy[r, b:b + 1]))
+            assert_near("fwd", download(y[r, b:b + 1]), ry, *tolerances(1, ry))
+            assert_near("dgrad", download(dx[r, b:b + 1]), rdx, *tolerances(1, rdx))
+        xr, dyr = download(x[r]), download(dy[r])
+        xp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin))
+        xp[:, pad:pad + H, pad:pad + W] = xr
+        got = download(gw[r])
+        scale = np.abs(got).max()
+        for _ in range(24):
+            co, ci = int(rng.integers(Cout)), int(rng.integers(Cin))
+            for i in range(k):
+                for j in range(k):
+                    win = xp[:, i:i + stride * (Ho - 1) + 1:stride, j:j + stride * (Wo - 1) + 1:stride, ci]
+                    ref = float(np.sum(win * dyr[..., co]))
+                    assert abs(got[co, i, j, ci] - ref) <= 2e-5 * scale + 1e-5 * abs(ref), (co, i, j, ci)
