@@ -71,6 +71,58 @@ def read_traffic():
     return None
 
 
+MODEL_WORKLOADS = {
+    # name: (oracle arch name, library model, n, compute_bf16, weight init)
+    "mlp_n3_fp32": ("mlp", 1, 3, 0, "uniform"),
+    "lenet_n6_fp32": ("lenet", 2, 6, 0, "uniform"),
+    "allcnn_c_n3_bf16": ("allcnn", 3, 3, 1, "he_normal"),
+    "wrn16_4_n3_bf16": ("wrn", 4, 3, 1, "he_normal"),
+}
+MFMA_PEAK_TFLOPS = {0: 157.3, 1: 2500.0}
+
+
+def bench_model(name, torch, pb, blocks=2, warmup=5):
+    """Replica-images/s of the whole step (forward, loss, backward, fused update; outer step every
+    L = 25) on synthetic class-conditional Gaussian images, batch 128 per replica."""
+    from oracle import nets as onets          # only for the flop count of the roofline figure
+    from paper_1707_00424_amd import synth
+    arch_name, model, n, bf16, wi = MODEL_WORKLOADS[name]
+    B, Lm = 128, 25
+    cfg = pb.make_config(model=model, n_replicas=n, batch=B, L=Lm, compute_bf16=bf16, eta_inner=0.01, eta_outer=0.01,
+                         gamma0=0.03, rho0=1.0, fuse_outer=1, scoping_B=390 if model == 4 else 0)
+    lay = pb.parle_query_layout(cfg)
+    x0 = np.tile(synth.init_params(lay, 0, wi), (n, 1))
+    P = pb.Parle(cfg, x0)
+    a = onets.arch(arch_name)
+    X, Y = synth.image_batches(0, 5, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = torch.as_tensor(X).cuda(), torch.as_tensor(Y).cuda()
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    for i in range(warmup):
+        P.parle_inner_step(dX[i % 5], dY[i % 5], loss)
+    P.parle_outer_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for blk in range(blocks):
+        for i in range(Lm):
+            P.parle_inner_step(dX[i % 5], dY[i % 5], loss)
+        P.parle_outer_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    steps = blocks * Lm
+    flops_step = 3 * onets.flops_forward_per_image(a) * n * B     # forward + two backward contractions
+    ips = steps * n * B / dt
+    out = {"replica_images_per_sec": round(ips, 1), "ms_per_inner_step": round(dt / steps * 1e3, 4),
+           "n_replicas": n, "batch_per_replica": B, "dtype": "bf16" if bf16 else "f32",
+           "contraction_tflops": round(flops_step * steps / dt / 1e12, 2),
+           "mfma_peak_tflops": MFMA_PEAK_TFLOPS[bf16],
+           "frac_of_mfma_peak": round(flops_step * steps / dt / 1e12 / MFMA_PEAK_TFLOPS[bf16], 4),
+           "final_loss": [round(float(v), 4) for v in loss.cpu().numpy()]}
+    P.close()
+    del P
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +130,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--fuse-outer", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--models", default="all", help="comma list of model workloads to time as well, or none")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="profiling aid: also run 3 plain device copies of one [n, n_pad] fp32 tensor, "
+                         "the known-size kernel the HBM counters are scaled by")
+    ap.add_argument("--only-models", action="store_true",
+                    help="profiling aid: skip the headline workload and print only the model timings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the Parle step on ONE GPU (all replicas stacked on it); "
@@ -91,6 +149,10 @@ def main():
         sys.exit(1)
     pb.lib()
     torch.cuda.set_device(0)
+    names = list(MODEL_WORKLOADS) if args.models == "all" else [m for m in args.models.split(",") if m and m != "none"]
+    if args.only_models:
+        print(json.dumps({"models": {nm: bench_model(nm, torch, pb) for nm in names}}))
+        return
     n, N = N_REPLICAS, N_PARAMS
     cfg = pb.make_config(model=pb.MODEL_FLAT, n_replicas=n, n_params=N, L=L, eta_inner=0.1, eta_outer=0.1,
                          momentum=0.9, alpha=0.75, gamma0=0.03, rho0=1.0, fuse_outer=args.fuse_outer)
@@ -140,9 +202,18 @@ def main():
                      "avg_launch_ms": round(inner_ms, 4), "algorithmic_bytes_per_launch": inner_bytes,
                      "traffic": read_traffic()},
     }
+    if args.copy_calibration:
+        scratch = torch.empty_like(P.grad)
+        for _ in range(3):
+            scratch.copy_(P.grad)
+        torch.cuda.synchronize()
+        out["config"]["copy_calibration_bytes_read"] = P.grad.numel() * 4
+        del scratch
     P.close()
     del P
     torch.cuda.empty_cache()
+    if names:
+        out["models"] = {nm: bench_model(nm, torch, pb) for nm in names}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

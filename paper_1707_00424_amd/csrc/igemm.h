@@ -90,5 +90,11 @@ inline ConvGeom conv_bwd_geom(const ConvShape &c) {
 // dtype: 0 = fp32 (v_mfma_f32_32x32x2_f32), 1 = bf16 (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
 hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom &g, const WgradIO &io);
+// Vector fast paths (igemm_fast.hip); launch_igemm / launch_wgrad pick them when applicable.
+bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
+hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
+void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
+hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Rows of M per split so that the launch has enough workgroups; returns the split count.
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out);

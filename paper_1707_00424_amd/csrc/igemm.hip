@@ -12,95 +12,11 @@
 //                  elements inside a step is irrelevant as long as A and B agree, which they do
 //                  because both are read from LDS with the same offsets);
 //   D (32x32 fp32, 16 registers v): column l % 32, row 8*(v/4) + 4*(l/32) + v%4.
-#include "igemm.h"
+#include "igemm_dev.h"
 
 namespace {
 
-typedef float f16v __attribute__((ext_vector_type(16)));
-typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
-typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-
-constexpr int kThreads = 256;
-
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
-  return (uint32_t)(((uint64_t)n * f.magic) >> f.shift);
-}
-
-template <typename T>
-__device__ __forceinline__ float to_f32(T v);
-template <>
-__device__ __forceinline__ float to_f32<float>(float v) {
-  return v;
-}
-template <>
-__device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) {
-  return bf16_to_f32(v);
-}
-template <typename T>
-__device__ __forceinline__ T from_f32(float v);
-template <>
-__device__ __forceinline__ float from_f32<float>(float v) {
-  return v;
-}
-template <>
-__device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) {
-  return f32_to_bf16(v);
-}
-
-// One contraction sub-step on a 32x32 accumulator from two 16-byte fragments.
-template <typename T>
-__device__ __forceinline__ void mma(const u4 &a, const u4 &b, f16v &acc);
-template <>
-__device__ __forceinline__ void mma<float>(const u4 &a, const u4 &b, f16v &acc) {
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-}
-template <>
-__device__ __forceinline__ void mma<bf16_t>(const u4 &a, const u4 &b, f16v &acc) {
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), acc, 0, 0, 0);
-}
-
-template <typename T, int VW>
-__device__ __forceinline__ u4 pack_vec(const T *tmp) {
-  u4 r;
-  if (sizeof(T) == 4) {
-    const uint32_t *p = (const uint32_t *)tmp;
-    r.x = p[0], r.y = p[1], r.z = p[2], r.w = p[3];
-  } else {
-    const unsigned short *p = (const unsigned short *)tmp;
-    r.x = p[0] | ((uint32_t)p[1] << 16);
-    r.y = p[2] | ((uint32_t)p[3] << 16);
-    r.z = p[4] | ((uint32_t)p[5] << 16);
-    r.w = p[6] | ((uint32_t)p[7] << 16);
-  }
-  return r;
-}
-
-__device__ __forceinline__ bool tap(int t, int dshift, int lim, int &idx) {
-  const int dm = (1 << dshift) - 1;
-  idx = t >> dshift;
-  return t >= 0 && (t & dm) == 0 && idx < lim;
-}
-
-// Shared MFMA inner step: every wavefront multiplies its TM x TN fragments for both halves of BK.
-template <typename T, int TM, int TN, int LK, int VW>
-__device__ __forceinline__ void mma_tile(const T *As, const T *Bs, int arow0, int brow0, int lane, f16v (&acc)[TM][TN]) {
-  const int r = lane & 31, h = lane >> 5;
-#pragma unroll
-  for (int sub = 0; sub < 2; ++sub) {
-    u4 af[TM], bf[TN];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&As[(arow0 + tm * 32 + r) * LK + sub * 2 * VW + h * VW];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&Bs[(brow0 + tn * 32 + r) * LK + sub * 2 * VW + h * VW];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) mma<T>(af[tm], bf[tn], acc[tm][tn]);
-  }
-}
+using namespace igemm_dev;
 
 // ---------------------------------------------------------------------------------------------
 // forward / backward-data: out[m, n] = epilogue( sum_k gather(m, k) * w[n, k] )
@@ -237,39 +153,7 @@ __global__ __launch_bounds__(kThreads) void k_igemm(const ConvGeom g, const Gemm
     __syncthreads();
   }
 
-  // epilogue
-  const int col_l = lane & 31, h = lane >> 5;
-  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
-  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
-  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    const int n = n0 + wn * TN * 32 + tn * 32 + col_l;
-    if (n >= g.N) continue;
-    const float bv = bias ? bias[n] : 0.f;
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int m = m0 + wm * TM * 32 + tm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-        if (m >= g.M) continue;
-        const long long o = (long long)m * io.ldc + n;
-        float val = acc[tm][tn][v] + bv;
-        if (resid) val += to_f32<T>(resid[o]);
-        if (io.relu) val = val > 0.f ? val : 0.f;
-        if (mask) val = to_f32<T>(mask[o]) > 0.f ? val : 0.f;
-        if (OUT_F32) {
-          float *out = (float *)io.out + rep * io.out_rs;
-          if (io.accumulate) val += out[o];
-          out[o] = val;
-        } else {
-          T *out = (T *)io.out + rep * io.out_rs;
-          if (io.accumulate) val += to_f32<T>(out[o]);
-          out[o] = from_f32<T>(val);
-        }
-      }
-    }
-  }
+  store_tile<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -486,6 +370,7 @@ int bf16_ntile(int n) {
 
 hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
+  if (igemm_fast_applicable(dtype, g, io)) return launch_igemm_fast(st, dtype, out_f32, replicas, g, io);
   if (dtype == 0) return run_igemm<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
   switch (bf16_ntile(g.N)) {
     case 32: return run_igemm<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);
@@ -499,6 +384,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || io.splits < 1 || (long long)replicas * io.splits > 65535 ||
       io.chunk < 32 || (io.chunk & 31))
     return hipErrorInvalidValue;
+  if (wgrad_fast_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad_fast(st, replicas, g, io);
   if (dtype == 0) return run_wgrad<float, 2, 2, 1, 1>(st, replicas, g, io);
   switch (bf16_ntile(g.N)) {
     case 32: return run_wgrad<bf16_t, 1, 4, 1, 1>(st, replicas, g, io);
@@ -510,7 +396,9 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   int bm, bn;
-  if (dtype == 0) {
+  if (wgrad_fast_applicable(dtype, g)) {
+    wgrad_fast_tile(g, &bm, &bn);
+  } else if (dtype == 0) {
     bm = 64, bn = 64;
   } else {
     bm = bf16_ntile(g.N);

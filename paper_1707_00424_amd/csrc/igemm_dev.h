@@ -1,0 +1,132 @@
+// Device-side helpers shared by the implicit-GEMM kernels (MFMA wrappers, LDS fragment reads).
+#pragma once
+#include "igemm.h"
+
+namespace igemm_dev {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
+  return (uint32_t)(((uint64_t)n * f.magic) >> f.shift);
+}
+
+template <typename T>
+__device__ __forceinline__ float to_f32(T v);
+template <>
+__device__ __forceinline__ float to_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) {
+  return bf16_to_f32(v);
+}
+template <typename T>
+__device__ __forceinline__ T from_f32(float v);
+template <>
+__device__ __forceinline__ float from_f32<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) {
+  return f32_to_bf16(v);
+}
+
+// One contraction sub-step on a 32x32 accumulator from two 16-byte fragments.
+template <typename T>
+__device__ __forceinline__ void mma(const u4 &a, const u4 &b, f16v &acc);
+template <>
+__device__ __forceinline__ void mma<float>(const u4 &a, const u4 &b, f16v &acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mma<bf16_t>(const u4 &a, const u4 &b, f16v &acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), acc, 0, 0, 0);
+}
+
+template <typename T, int VW>
+__device__ __forceinline__ u4 pack_vec(const T *tmp) {
+  u4 r;
+  if (sizeof(T) == 4) {
+    const uint32_t *p = (const uint32_t *)tmp;
+    r.x = p[0], r.y = p[1], r.z = p[2], r.w = p[3];
+  } else {
+    const unsigned short *p = (const unsigned short *)tmp;
+    r.x = p[0] | ((uint32_t)p[1] << 16);
+    r.y = p[2] | ((uint32_t)p[3] << 16);
+    r.z = p[4] | ((uint32_t)p[5] << 16);
+    r.w = p[6] | ((uint32_t)p[7] << 16);
+  }
+  return r;
+}
+
+__device__ __forceinline__ bool tap(int t, int dshift, int lim, int &idx) {
+  const int dm = (1 << dshift) - 1;
+  idx = t >> dshift;
+  return t >= 0 && (t & dm) == 0 && idx < lim;
+}
+
+// Shared MFMA inner step: every wavefront multiplies its TM x TN fragments for both halves of BK.
+template <typename T, int TM, int TN, int LK, int VW>
+__device__ __forceinline__ void mma_tile(const T *As, const T *Bs, int arow0, int brow0, int lane, f16v (&acc)[TM][TN]) {
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    u4 af[TM], bf[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&As[(arow0 + tm * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&Bs[(brow0 + tn * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma<T>(af[tm], bf[tn], acc[tm][tn]);
+  }
+}
+
+
+// Writes a wavefront's TM x TN accumulator tiles: bias, residual, ReLU, mask, accumulate, convert.
+template <typename T, int TM, int TN, bool OUT_F32>
+__device__ __forceinline__ void store_tile(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
+                                           f16v (&acc)[TM][TN]) {
+  const int col_l = lane & 31, h = lane >> 5;
+  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
+  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
+  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int n = ncol0 + tn * 32 + col_l;
+    if (n >= g.N) continue;
+    const float bv = bias ? bias[n] : 0.f;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int m = mrow0 + tm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (m >= g.M) continue;
+        const long long o = (long long)m * io.ldc + n;
+        float val = acc[tm][tn][v] + bv;
+        if (resid) val += to_f32<T>(resid[o]);
+        if (io.relu) val = val > 0.f ? val : 0.f;
+        if (mask) val = to_f32<T>(mask[o]) > 0.f ? val : 0.f;
+        if (OUT_F32) {
+          float *out = (float *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += out[o];
+          out[o] = val;
+        } else {
+          T *out = (T *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += to_f32<T>(out[o]);
+          out[o] = from_f32<T>(val);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace igemm_dev

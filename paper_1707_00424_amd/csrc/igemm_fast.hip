@@ -1,0 +1,352 @@
+// Vector fast paths of the implicit-GEMM kernels (channel counts that are multiples of the 16-byte
+// vector width): the same tiling and MFMA layout as igemm.hip, with
+//   * forward / backward-data: per-row validity of every tap precomputed as two bit masks (rows of the
+//     window, columns of the window) and a linear tap offset, so a contraction step costs a few
+//     integer instructions per 16-byte load instead of two range/parity tests and a multiply chain;
+//     wavefront tiles up to 64x128 so that LDS fragment reads per MFMA drop below one;
+//   * backward-weight (bf16): both operands are staged in LDS exactly as they lie in memory
+//     ([pixel][channel], 16-byte loads and stores) and the MFMA fragments, which need the pixel index
+//     contiguous, are fetched with the LDS transpose read (ds_read_b64_tr_b16).  Lane l of a 16-lane
+//     group addresses row k0 + l/4, columns c0 + 4*(l%4) .. +3 and receives T[k0+e][c0+l], e = 0..3
+//     (layout confirmed with an in-bounds probe on the device).
+#include "igemm_dev.h"
+
+namespace {
+
+using namespace igemm_dev;
+typedef short s4v __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// forward / backward-data, vector path
+// ---------------------------------------------------------------------------------------------
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32>
+__global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const GemmIO io) {
+  constexpr int VW = 16 / sizeof(T);
+  constexpr int BK = 4 * VW;
+  constexpr int LK = BK + VW;
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  static_assert(BM % 64 == 0, "row tile must be a multiple of 64");
+  constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
+  __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
+  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int rep = blockIdx.z;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const T *__restrict__ in = (const T *)io.in + rep * io.in_rs;
+  const T *__restrict__ w = (const T *)io.w + rep * io.w_rs;
+  const int lrow = tid >> 2, lkv = tid & 3;
+  const int PQ = g.P * g.Q;
+
+  int a_base[A_IT];
+  uint32_t a_hmask[A_IT], a_wmask[A_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) {
+    const int m = m0 + i * 64 + lrow;
+    const bool ok = m < g.M;
+    const uint32_t mm = ok ? m : 0;
+    const int b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
+    const int p = fdiv(rem, g.dQ), q = rem - p * g.Q;
+    const int bh = p * g.sp + g.off, bw = q * g.sp + g.off;
+    uint32_t hm = 0, wmk = 0;
+    for (int r = 0; r < g.R; ++r) {
+      int idx;
+      hm |= (uint32_t)(ok && tap(bh + r * g.sr, g.dshift, g.Hin, idx)) << r;
+    }
+    for (int s = 0; s < g.S; ++s) {
+      int idx;
+      wmk |= (uint32_t)tap(bw + s * g.sr, g.dshift, g.Win, idx) << s;
+    }
+    a_hmask[i] = hm, a_wmask[i] = wmk;
+    a_base[i] = (b * g.Hin + (bh >> g.dshift)) * g.Win * g.Cc + (bw >> g.dshift) * g.Cc;
+  }
+  int b_row[B_IT];
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) {
+    const int row = i * 64 + lrow, nrow = n0 + row;
+    b_row[i] = (row < BN && nrow < g.N) ? nrow * g.K : -1;
+  }
+  int kk = lkv * VW, kr, ks, kc;
+  {
+    const uint32_t rs = fdiv(kk, g.dCc);
+    kc = kk - rs * g.Cc;
+    kr = fdiv(rs, g.dS);
+    ks = rs - kr * g.S;
+  }
+
+  u4 areg[A_IT], breg[B_IT];
+  const u4 zero4 = {0u, 0u, 0u, 0u};
+
+  auto load_tiles = [&]() {
+    const int toff = g.sr * (((kr >> g.dshift) * g.Win + (ks >> g.dshift)) * g.Cc) + kc;
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const bool ok = ((a_hmask[i] >> kr) & (a_wmask[i] >> ks) & 1u) != 0;
+      areg[i] = ok ? *(const u4 *)(in + a_base[i] + toff) : zero4;
+    }
+    const bool kok = kk < g.K;
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) breg[i] = (kok && b_row[i] >= 0) ? *(const u4 *)(w + b_row[i] + kk) : zero4;
+  };
+  auto advance_k = [&]() {
+    kk += BK;
+    kc += BK;
+    while (kc >= g.Cc) {
+      kc -= g.Cc;
+      if (++ks == g.S) {
+        ks = 0;
+        ++kr;
+      }
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) *(u4 *)&As[buf][(i * 64 + lrow) * LK + lkv * VW] = areg[i];
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = i * 64 + lrow;
+      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf][row * LK + lkv * VW] = breg[i];
+    }
+  };
+
+  f16v acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+  const int KT = (g.K + BK - 1) / BK;
+  load_tiles();
+  store_tiles(0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) {
+      advance_k();
+      load_tiles();
+    }
+    mma_tile<T, TM, TN, LK, VW>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+    if (kt + 1 < KT) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+  store_tile<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// backward-weight, bf16, LDS transpose reads.  out[n, k] = sum_m dy[m, n] * gather(m, k).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ u4 lds_tr_frag(const bf16_t *tile, int ld, int krow, int col) {
+  // 8 contraction values (rows krow .. krow+7 as seen by this lane's 16-lane group) of column `col + l%16`
+  const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v *)(tile + krow * ld + col));
+  const s4v hi =
+      __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s4v *)(tile + (krow + 4) * ld + col));
+  u4 r;
+  r.x = (uint32_t)(unsigned short)lo.x | ((uint32_t)(unsigned short)lo.y << 16);
+  r.y = (uint32_t)(unsigned short)lo.z | ((uint32_t)(unsigned short)lo.w << 16);
+  r.z = (uint32_t)(unsigned short)hi.x | ((uint32_t)(unsigned short)hi.y << 16);
+  r.w = (uint32_t)(unsigned short)hi.z | ((uint32_t)(unsigned short)hi.w << 16);
+  return r;
+}
+
+template <int WAVES_M, int WAVES_N, int TM, int TN>
+__global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const WgradIO io) {
+  constexpr int BKM = 32;  // pixels per contraction step
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  constexpr int LDA = BM + 16, LDB = BN + 16;  // row strides = 32 (mod 128) bytes: conflict-free transpose reads
+  constexpr int AV = BM / 8, BV = BN / 8;      // 16-byte vectors per pixel row
+  static_assert(kThreads % BV == 0, "a thread must own one column vector of the gathered operand");
+  constexpr int A_IT = (BKM * AV + kThreads - 1) / kThreads;
+  constexpr int B_ROWS = kThreads / BV, B_IT = BKM / B_ROWS;
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BKM * LDA];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BKM * LDB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int rep = blockIdx.z / io.splits, split = blockIdx.z % io.splits;
+  const int n0 = blockIdx.y * BM, k0 = blockIdx.x * BN;
+  const bf16_t *__restrict__ dy = (const bf16_t *)io.dy + rep * io.dy_rs;
+  const bf16_t *__restrict__ x = (const bf16_t *)io.x + rep * io.x_rs;
+  const int m_begin = split * io.chunk, m_end = min(g.M, m_begin + io.chunk);
+  const int PQ = g.P * g.Q;
+
+  // gathered operand: this thread's fixed column vector (tap r, s and first channel)
+  const int bcv = tid % BV, brow0 = tid / BV;
+  const int kcol = k0 + bcv * 8;
+  const bool bcol_ok = kcol < g.K;
+  int b_r, b_s, b_c;
+  {
+    const uint32_t kk = bcol_ok ? kcol : 0;
+    const uint32_t rs = fdiv(kk, g.dCc);
+    b_c = kk - rs * g.Cc;
+    b_r = fdiv(rs, g.dS);
+    b_s = rs - b_r * g.S;
+  }
+  const int b_tapoff = ((b_r - (-g.off)) * g.Win + (b_s - (-g.off))) * g.Cc + b_c;  // (r - pad, s - pad)
+
+  u4 areg[A_IT], breg[B_IT];
+  const u4 zero4 = {0u, 0u, 0u, 0u};
+
+  auto load_tiles = [&](int mbase) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int v = i * kThreads + tid;
+      const int row = v / AV, cv = v % AV;
+      const int m = mbase + row, n = n0 + cv * 8;
+      const bool ok = (BKM * AV % kThreads == 0 || v < BKM * AV) && m < m_end && n < g.N;
+      areg[i] = ok ? *(const u4 *)(dy + (long long)m * g.N + n) : zero4;
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int m = mbase + i * B_ROWS + brow0;
+      const bool mok = m < m_end;
+      const uint32_t mm = mok ? m : 0;
+      const int b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
+      const int p = fdiv(rem, g.dQ), q = rem - p * g.Q;
+      const int ih = p * g.sp + g.off + b_r, iw = q * g.sp + g.off + b_s;
+      const bool ok = mok && bcol_ok && ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win;
+      const int base = ((b * g.Hin + p * g.sp) * g.Win + q * g.sp) * g.Cc;
+      breg[i] = ok ? *(const u4 *)(x + base + b_tapoff) : zero4;
+    }
+  };
+  auto store_tiles = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int v = i * kThreads + tid;
+      if (BKM * AV % kThreads == 0 || v < BKM * AV) *(u4 *)&As[buf][(v / AV) * LDA + (v % AV) * 8] = areg[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) *(u4 *)&Bs[buf][(i * B_ROWS + brow0) * LDB + bcv * 8] = breg[i];
+  };
+
+  f16v acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+  // fragment addressing: 16-lane group gq covers columns 16*(gq%2) .. +15 and contraction half gq/2
+  const int gq = lane >> 4, j = lane & 15;
+  const int frag_k = 8 * (gq >> 1) + (j >> 2), frag_c = 16 * (gq & 1) + 4 * (j & 3);
+
+  const int KT = m_end > m_begin ? (m_end - m_begin + BKM - 1) / BKM : 0;
+  if (KT > 0) {
+    load_tiles(m_begin);
+    store_tiles(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_tiles(m_begin + (kt + 1) * BKM);
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      u4 af[TM], bf[TN];
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+        af[tm] = lds_tr_frag(As[buf], LDA, sub * 16 + frag_k, wm * TM * 32 + tm * 32 + frag_c);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+        bf[tn] = lds_tr_frag(Bs[buf], LDB, sub * 16 + frag_k, wn * TN * 32 + tn * 32 + frag_c);
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) mma<bf16_t>(af[tm], bf[tn], acc[tm][tn]);
+    }
+    if (kt + 1 < KT) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  float *out = io.out + rep * io.out_rs + split * io.split_stride;
+  const int col_l = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int k = k0 + wn * TN * 32 + tn * 32 + col_l;
+    if (k >= g.K) continue;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int n = n0 + wm * TM * 32 + tm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (n < g.N) out[(long long)n * g.K + k] = acc[tm][tn][v];
+      }
+  }
+}
+
+template <typename T, int WM, int WN, int TM, int TN>
+hipError_t run_v(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, replicas);
+  if (out_f32)
+    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+  else
+    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
+
+template <int WM, int WN, int TM, int TN>
+hipError_t run_tr(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid((g.K + BN - 1) / BN, (g.N + BM - 1) / BM, replicas * io.splits);
+  hipLaunchKernelGGL((k_wgrad_tr<WM, WN, TM, TN>), grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
+
+// tall (256-row) tiles only when they still leave enough workgroups to fill the chip
+bool tall_ok(const ConvGeom &g, int bn, int replicas) {
+  const long long blocks = (long long)((g.M + 255) / 256) * ((g.N + bn - 1) / bn) * replicas;
+  return blocks >= 512;
+}
+
+}  // namespace
+
+bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
+  const int vw = dtype ? 8 : 4;
+  return io.vecA && io.vecB && g.Cc % vw == 0 && g.K % vw == 0 && g.R <= 16 && g.S <= 16;
+}
+
+hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g,
+                             const GemmIO &io) {
+  if (dtype == 0) return run_v<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
+  const int n = g.N;
+  if (n <= 32) return run_v<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);
+  if (n <= 64)
+    return tall_ok(g, 64, replicas) ? run_v<bf16_t, 4, 1, 2, 2>(st, out_f32, replicas, g, io)
+                                    : run_v<bf16_t, 4, 1, 1, 2>(st, out_f32, replicas, g, io);
+  if (n <= 96)
+    return tall_ok(g, 96, replicas) ? run_v<bf16_t, 4, 1, 2, 3>(st, out_f32, replicas, g, io)
+                                    : run_v<bf16_t, 4, 1, 1, 3>(st, out_f32, replicas, g, io);
+  if (n <= 128) return run_v<bf16_t, 2, 2, 2, 2>(st, out_f32, replicas, g, io);
+  if (n <= 192 || n % 192 == 0) return run_v<bf16_t, 2, 2, 2, 3>(st, out_f32, replicas, g, io);
+  return run_v<bf16_t, 2, 2, 2, 4>(st, out_f32, replicas, g, io);
+}
+
+bool wgrad_fast_applicable(int dtype, const ConvGeom &g) {
+  return dtype == 1 && g.Cc % 8 == 0 && g.N % 8 == 0 && g.N >= 32 && g.dshift == 0 && g.sr == 1;
+}
+
+void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn) {
+  const int n = g.N;
+  if (n <= 32) *bm = 32, *bn = 128;
+  else if (n <= 64) *bm = 64, *bn = 256;
+  else if (n <= 96) *bm = 96, *bn = 256;
+  else if (n <= 128) *bm = 128, *bn = 128;
+  else if (n <= 192 || n % 192 == 0) *bm = 192, *bn = 128;
+  else *bm = 256, *bn = 128;
+}
+
+hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
+  int bm, bn;
+  wgrad_fast_tile(g, &bm, &bn);
+  switch (bm) {
+    case 32: return run_tr<1, 4, 1, 1>(st, replicas, g, io);
+    case 64: return run_tr<1, 4, 2, 2>(st, replicas, g, io);
+    case 96: return run_tr<1, 4, 3, 2>(st, replicas, g, io);
+    case 128: return run_tr<2, 2, 2, 2>(st, replicas, g, io);
+    case 192: return run_tr<2, 2, 3, 2>(st, replicas, g, io);
+    default: return run_tr<2, 2, 4, 2>(st, replicas, g, io);
+  }
+}

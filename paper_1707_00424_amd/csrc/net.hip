@@ -52,7 +52,7 @@ struct Net {
   std::vector<Op> ops;
   int t_images = -1, t_logits = -1;
   int64_t ws_bytes = 0;
-  int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0;
+  int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0, wpartial_bytes = 0;
   int64_t bn_floats = 0;
   int max_bn_c = 0;
 
@@ -230,8 +230,8 @@ bool build_plan(Net &N, std::string &err) {
         N.want_grad(op.in);
         op.wt_off = N.alloc((int64_t)N.n * wsize * N.esize);
       }
-      ConvGeom g{};
-      g.M = N.B * op.Ho * op.Wo, g.N = op.Cout, g.K = op.R * op.R * op.Cin;
+      // the complete forward geometry: the split plan depends on which kernel variant will run
+      const ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
       int chunk = 0;
       const int S = wgrad_plan(N.dtype, N.n, g, &chunk);
       if (S > 1 && (int64_t)N.n * S * wsize * 4 > wpartial) wpartial = (int64_t)N.n * S * wsize * 4;
@@ -244,7 +244,8 @@ bool build_plan(Net &N, std::string &err) {
       N.want_grad(op.in);
     }
   }
-  N.off_wpartial = N.alloc(wpartial > 0 ? wpartial : 256);
+  N.wpartial_bytes = wpartial > 0 ? wpartial : 256;
+  N.off_wpartial = N.alloc(N.wpartial_bytes);
   int maxc = N.max_bn_c;
   for (const Op &op : N.ops)
     if (op.type == OP_CONV && op.bseg >= 0 && op.Cout > maxc) maxc = op.Cout;
@@ -359,6 +360,8 @@ hipError_t backward(const Run &r, float *grad) {
             io.out = grad + N.segs[op.wseg].offset, io.out_rs = r.p_rs, io.split_stride = 0;
             HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
           } else {
+            // never launch with more partials than the plan reserved room for
+            if ((int64_t)r.n * S * wsize * 4 > N.wpartial_bytes) return hipErrorInvalidValue;
             io.out = (float *)(r.ws + N.off_wpartial), io.out_rs = (int64_t)S * wsize, io.split_stride = wsize;
             HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
             HIP_TRY(launch_reduce_partials(r.st, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));

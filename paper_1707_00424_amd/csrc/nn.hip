@@ -255,28 +255,37 @@ __global__ __launch_bounds__(kThreads) void k_colreduce(int M, int C, int chunk,
   }
 }
 
-// bias gradient: grad[c] = sum over splits of s1
-__global__ __launch_bounds__(kThreads) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
-                                                            float *__restrict__ grad, long long grad_rs) {
-  const int rep = blockIdx.y;
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= C) return;
-  double s = 0.0;
-  for (int sp = 0; sp < S; ++sp) s += partial[((long long)rep * S + sp) * 2 * C + c];
-  grad[rep * grad_rs + c] = (float)s;
+// Sum over the row-splits of one channel's two partial sums: one wavefront per (channel, replica),
+// lane l takes splits l, l+64, ... in order, then a fixed shuffle tree (deterministic).
+__device__ __forceinline__ void sum_splits(const double *__restrict__ partial, int rep, int S, int C, int c, double &s1,
+                                           double &s2) {
+  s1 = 0.0, s2 = 0.0;
+  for (int sp = threadIdx.x; sp < S; sp += PARLE_WAVE) {
+    const double *p = partial + ((long long)rep * S + sp) * 2 * C;
+    s1 += p[c];
+    s2 += p[C + c];
+  }
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
 }
 
-__global__ __launch_bounds__(kThreads) void k_bn_stats_finalize(int M, int C, int S, const double *__restrict__ partial,
-                                                                float *__restrict__ saved, float *__restrict__ running,
-                                                                long long run_rs) {
-  const int rep = blockIdx.y;
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int sp = 0; sp < S; ++sp) {
-    s1 += partial[((long long)rep * S + sp) * 2 * C + c];
-    s2 += partial[((long long)rep * S + sp) * 2 * C + C + c];
-  }
+// bias gradient: grad[c] = sum over splits of s1
+__global__ __launch_bounds__(PARLE_WAVE) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
+                                                              float *__restrict__ grad, long long grad_rs) {
+  const int rep = blockIdx.y, c = blockIdx.x;
+  double s1, s2;
+  sum_splits(partial, rep, S, C, c, s1, s2);
+  if (threadIdx.x == 0) grad[rep * grad_rs + c] = (float)s1;
+}
+
+__global__ __launch_bounds__(PARLE_WAVE) void k_bn_stats_finalize(int M, int C, int S,
+                                                                  const double *__restrict__ partial,
+                                                                  float *__restrict__ saved, float *__restrict__ running,
+                                                                  long long run_rs) {
+  const int rep = blockIdx.y, c = blockIdx.x;
+  double s1, s2;
+  sum_splits(partial, rep, S, C, c, s1, s2);
+  if (threadIdx.x != 0) return;
   const double mean = s1 / M;
   double var = s2 / M - mean * mean;
   if (var < 0.0) var = 0.0;
@@ -317,17 +326,13 @@ __global__ __launch_bounds__(kThreads) void k_bn_apply_relu(int M, int C, const 
   }
 }
 
-__global__ __launch_bounds__(kThreads) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
-                                                              float *__restrict__ sums, float *__restrict__ dgamma,
-                                                              float *__restrict__ dbeta, long long p_rs) {
-  const int rep = blockIdx.y;
-  const int c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= C) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int sp = 0; sp < S; ++sp) {
-    s1 += partial[((long long)rep * S + sp) * 2 * C + c];
-    s2 += partial[((long long)rep * S + sp) * 2 * C + C + c];
-  }
+__global__ __launch_bounds__(PARLE_WAVE) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
+                                                                float *__restrict__ sums, float *__restrict__ dgamma,
+                                                                float *__restrict__ dbeta, long long p_rs) {
+  const int rep = blockIdx.y, c = blockIdx.x;
+  double s1, s2;
+  sum_splits(partial, rep, S, C, c, s1, s2);
+  if (threadIdx.x != 0) return;
   sums[(long long)rep * 2 * C + c] = (float)s1;
   sums[(long long)rep * 2 * C + C + c] = (float)s2;
   dbeta[rep * p_rs + c] = (float)s1;
@@ -519,8 +524,7 @@ hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, cons
              hipLaunchKernelGGL((k_colreduce<bf16_t, 0>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
                                 (const bf16_t *)dy, dy_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
                                 (const float *)nullptr, (const float *)nullptr, 0LL, partial));
-  hipLaunchKernelGGL(k_bias_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, C, S, partial, grad,
-                     grad_rs);
+  hipLaunchKernelGGL(k_bias_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, grad, grad_rs);
   return hipGetLastError();
 }
 
@@ -543,8 +547,8 @@ hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, c
              hipLaunchKernelGGL((k_colreduce<bf16_t, 1>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
                                 (const bf16_t *)x, x_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
                                 (const float *)nullptr, (const float *)nullptr, 0LL, partial));
-  hipLaunchKernelGGL(k_bn_stats_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, M, C, S,
-                     partial, saved, running, run_rs);
+  hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, M, C, S, partial, saved, running,
+                     run_rs);
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_bn_apply_relu<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs, gamma,
@@ -579,8 +583,7 @@ hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const v
              hipLaunchKernelGGL((k_colreduce<bf16_t, 2>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
                                 (const bf16_t *)x, x_rs, (const bf16_t *)dout, dout_rs, saved, gamma, beta, p_rs,
                                 partial));
-  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads, n), dim3(kThreads), 0, st, C, S, partial,
-                     sums, dgamma, dbeta, p_rs);
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, sums, dgamma, dbeta, p_rs);
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_bn_bwd_apply<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs,
