@@ -41,6 +41,7 @@ parle_status parle_k_conv_forward(void *hip_stream, const parle_conv_desc *desc,
   io.relu = relu;
   io.vecA = (c.Cin % vw == 0) && (io.in_rs % vw == 0);
   io.vecB = (g.K % vw == 0);
+  io.in_bytes = io.in_rs * es;
   return launch_igemm((hipStream_t)hip_stream, desc->dtype, false, desc->n, g, io) == hipSuccess ? PARLE_OK : PARLE_EHIP;
 }
 
@@ -67,6 +68,7 @@ parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc 
   io.accumulate = accumulate;
   io.vecA = (c.Cout % vw == 0) && (io.in_rs % vw == 0);
   io.vecB = (g.K % vw == 0) && (wsize % vw == 0);
+  io.in_bytes = io.in_rs * es;
   return launch_igemm(st, desc->dtype, false, desc->n, g, io) == hipSuccess ? PARLE_OK : PARLE_EHIP;
 }
 

@@ -48,6 +48,7 @@ struct GemmIO {
   long long mask_rs;
   int relu, accumulate;
   int vecA, vecB;     // 16-byte loads allowed for the gathered operand / the weight matrix
+  long long in_bytes; // bytes of one replica's gathered tensor (range of the buffer loads)
 };
 
 struct WgradIO {

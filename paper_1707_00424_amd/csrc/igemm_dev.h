@@ -91,6 +91,100 @@ __device__ __forceinline__ void mma_tile(const T *As, const T *Bs, int arow0, in
 }
 
 
+// Same inner step with the MFMA operands swapped: every 32x32 accumulator then holds the TRANSPOSED
+// tile (lane l: row m = l % 32; registers v: columns 8*(v/4) + 4*(l/32) + v%4), i.e. each lane owns
+// groups of four consecutive output channels of one pixel and can store them as one vector.
+template <typename T, int TM, int TN, int LK, int VW>
+__device__ __forceinline__ void mma_tile_t(const T *As, const T *Bs, int arow0, int brow0, int lane, f16v (&acc)[TM][TN]) {
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int sub = 0; sub < 2; ++sub) {
+    u4 af[TM], bf[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&As[(arow0 + tm * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&Bs[(brow0 + tn * 32 + r) * LK + sub * 2 * VW + h * VW];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma<T>(bf[tn], af[tm], acc[tm][tn]);
+  }
+}
+
+template <typename T>
+struct Vec4;  // four consecutive elements of an activation tensor
+template <>
+struct Vec4<float> {
+  typedef f4 type;
+  static __device__ __forceinline__ f4 to_f32(f4 v) { return v; }
+  static __device__ __forceinline__ f4 from_f32(f4 v) { return v; }
+};
+template <>
+struct Vec4<bf16_t> {
+  typedef us4 type;
+  static __device__ __forceinline__ f4 to_f32(us4 v) {
+    f4 r = {bf16_to_f32(v.x), bf16_to_f32(v.y), bf16_to_f32(v.z), bf16_to_f32(v.w)};
+    return r;
+  }
+  static __device__ __forceinline__ us4 from_f32(f4 v) {
+    us4 r = {f32_to_bf16(v.x), f32_to_bf16(v.y), f32_to_bf16(v.z), f32_to_bf16(v.w)};
+    return r;
+  }
+};
+
+// Epilogue for transposed accumulator tiles (see mma_tile_t).  Requires N % 4 == 0 and ldc % 4 == 0.
+template <typename T, int TM, int TN, bool OUT_F32>
+__device__ __forceinline__ void store_tile_t(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
+                                             f16v (&acc)[TM][TN]) {
+  typedef typename Vec4<T>::type TV;
+  const int row_l = lane & 31, h = lane >> 5;
+  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
+  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
+  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
+  const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 15) == 0;  // segment offsets need not be 16-byte aligned
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int m = mrow0 + tm * 32 + row_l;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const int n = ncol0 + tn * 32 + 8 * vg + 4 * h;
+        if (n >= g.N) continue;
+        const long long o = (long long)m * io.ldc + n;
+        f4 val = {acc[tm][tn][4 * vg], acc[tm][tn][4 * vg + 1], acc[tm][tn][4 * vg + 2], acc[tm][tn][4 * vg + 3]};
+        if (bias) {
+          if (bias_vec) {
+            val += *(const f4 *)(bias + n);
+          } else {
+            val.x += bias[n], val.y += bias[n + 1], val.z += bias[n + 2], val.w += bias[n + 3];
+          }
+        }
+        if (resid) val += Vec4<T>::to_f32(*(const TV *)(resid + o));
+        if (io.relu) {
+          val.x = val.x > 0.f ? val.x : 0.f, val.y = val.y > 0.f ? val.y : 0.f;
+          val.z = val.z > 0.f ? val.z : 0.f, val.w = val.w > 0.f ? val.w : 0.f;
+        }
+        if (mask) {
+          const f4 mk = Vec4<T>::to_f32(*(const TV *)(mask + o));
+          val.x = mk.x > 0.f ? val.x : 0.f, val.y = mk.y > 0.f ? val.y : 0.f;
+          val.z = mk.z > 0.f ? val.z : 0.f, val.w = mk.w > 0.f ? val.w : 0.f;
+        }
+        if (OUT_F32) {
+          float *out = (float *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += *(const f4 *)(out + o);
+          *(f4 *)(out + o) = val;
+        } else {
+          T *out = (T *)io.out + rep * io.out_rs;
+          if (io.accumulate) val += Vec4<T>::to_f32(*(const TV *)(out + o));
+          *(TV *)(out + o) = Vec4<T>::from_f32(val);
+        }
+      }
+    }
+  }
+}
+
 // Writes a wavefront's TM x TN accumulator tiles: bias, residual, ReLU, mask, accumulate, convert.
 template <typename T, int TM, int TN, bool OUT_F32>
 __device__ __forceinline__ void store_tile(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,

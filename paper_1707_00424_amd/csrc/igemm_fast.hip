@@ -75,32 +75,37 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
     ks = rs - kr * g.S;
   }
 
-  u4 areg[A_IT], breg[B_IT];
   const u4 zero4 = {0u, 0u, 0u, 0u};
 
-  auto load_tiles = [&]() {
+  // Loads of steps past the end are fully masked (tap row index beyond the window, kk >= K), so
+  // the pipeline below may always run two steps ahead without touching memory out of range.
+  auto load_tiles = [&](u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
     const int toff = g.sr * (((kr >> g.dshift) * g.Win + (ks >> g.dshift)) * g.Cc) + kc;
+    const int krs = kr < 31 ? kr : 31;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
-      const bool ok = ((a_hmask[i] >> kr) & (a_wmask[i] >> ks) & 1u) != 0;
+      const bool ok = ((a_hmask[i] >> krs) & (a_wmask[i] >> ks) & 1u) != 0;
       areg[i] = ok ? *(const u4 *)(in + a_base[i] + toff) : zero4;
     }
     const bool kok = kk < g.K;
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) breg[i] = (kok && b_row[i] >= 0) ? *(const u4 *)(w + b_row[i] + kk) : zero4;
   };
+  // branch-free: Cc >= VW, so one step of BK = 4*VW crosses at most four tap boundaries
   auto advance_k = [&]() {
     kk += BK;
     kc += BK;
-    while (kc >= g.Cc) {
-      kc -= g.Cc;
-      if (++ks == g.S) {
-        ks = 0;
-        ++kr;
-      }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const bool wrap = kc >= g.Cc;
+      kc -= wrap ? g.Cc : 0;
+      ks += wrap ? 1 : 0;
+      const bool wrap_s = ks == g.S;
+      ks = wrap_s ? 0 : ks;
+      kr += wrap_s ? 1 : 0;
     }
   };
-  auto store_tiles = [&](int buf) {
+  auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const u4 (&breg)[B_IT]) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) *(u4 *)&As[buf][(i * 64 + lrow) * LK + lkv * VW] = areg[i];
 #pragma unroll
@@ -118,21 +123,161 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
+  // Software pipeline, two steps deep: global loads of step t+2 are issued before the MFMAs of
+  // step t, the registers of step t+1 go to the other LDS buffer after them, one barrier per step.
+  // Two register sets, so the loop is unrolled by two; the body has no data-dependent branches.
   const int KT = (g.K + BK - 1) / BK;
-  load_tiles();
-  store_tiles(0);
+  u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
+  load_tiles(a0, b0);
+  advance_k();
+  load_tiles(a1, b1);
+  store_tiles(0, a0, b0);
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) {
-      advance_k();
-      load_tiles();
-    }
-    mma_tile<T, TM, TN, LK, VW>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
-    if (kt + 1 < KT) store_tiles(buf ^ 1);
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    advance_k();
+    load_tiles(a0, b0);
+    mma_tile<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
+    store_tiles(1, a1, b1);
+    __syncthreads();
+    advance_k();
+    load_tiles(a1, b1);
+    mma_tile<T, TM, TN, LK, VW>(As[1], Bs[1], wm * TM * 32, wn * TN * 32, lane, acc);
+    store_tiles(0, a0, b0);
     __syncthreads();
   }
+  if (kt < KT) mma_tile<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
   store_tile<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// forward / backward-data, uniform-tap path: the channel count is a multiple of the contraction
+// step (Cc % BK == 0), so a whole step lies inside one window tap and the tap bookkeeping is
+// wavefront-uniform (scalar registers).  Operands are fetched with raw buffer loads: a lane whose
+// tap falls outside the image, or whose row is beyond the tensor, gets an offset past the buffer's
+// range and the hardware returns zeros -- no branch, no select.  Accumulator tiles are kept
+// transposed so the epilogue writes four consecutive channels per lane.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t kOob = 0x80000000u;  // beyond any per-replica tensor (each is < 2 GiB)
+
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32>
+__global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const GemmIO io) {
+  constexpr int VW = 16 / sizeof(T);
+  constexpr int BK = 4 * VW;
+  constexpr int LK = BK + VW;
+  constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+  static_assert(BM % 64 == 0, "row tile must be a multiple of 64");
+  constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
+  __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
+  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int rep = blockIdx.z;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int lrow = tid >> 2, lkv = tid & 3;
+  const int PQ = g.P * g.Q;
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((const T *)io.in + rep * io.in_rs), 0, (int)(io.in_bytes), 0x00020000);
+  const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((const T *)io.w + rep * io.w_rs), 0, (int)((long long)g.N * g.K * sizeof(T)), 0x00020000);
+
+  // per row: byte offset of its window origin (+ this lane's vector inside a step) and one validity
+  // bit per tap
+  uint32_t a_off[A_IT], a_taps[A_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) {
+    const int m = m0 + i * 64 + lrow;
+    const bool ok = m < g.M;
+    const uint32_t mm = ok ? m : 0;
+    const int b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
+    const int p = fdiv(rem, g.dQ), q = rem - p * g.Q;
+    const int bh = p * g.sp + g.off, bw = q * g.sp + g.off;
+    uint32_t taps = 0;
+    for (int r = 0; r < g.R; ++r) {
+      int idx;
+      const bool hv = ok && tap(bh + r * g.sr, g.dshift, g.Hin, idx);
+      for (int s2 = 0; s2 < g.S; ++s2) taps |= (uint32_t)(hv && tap(bw + s2 * g.sr, g.dshift, g.Win, idx)) << (r * g.S + s2);
+    }
+    a_taps[i] = taps;
+    a_off[i] = (uint32_t)(((b * g.Hin + (bh >> g.dshift)) * g.Win * g.Cc + (bw >> g.dshift) * g.Cc + lkv * VW) * (int)sizeof(T));
+  }
+  uint32_t b_off[B_IT];
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) {
+    const int row = i * 64 + lrow, nrow = n0 + row;
+    b_off[i] = (row < BN && nrow < g.N) ? (uint32_t)((nrow * g.K + lkv * VW) * (int)sizeof(T)) : kOob;
+  }
+  // wavefront-uniform contraction state: tap (kr, ks), first channel kc of the step, step index
+  int kr = 0, ks = 0, kc = 0, kt_load = 0;
+
+  auto load_tiles = [&](u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
+    const int tapi = kr * g.S + ks;
+    const uint32_t toff = (uint32_t)((g.sr * (((kr >> g.dshift) * g.Win + (ks >> g.dshift)) * g.Cc) + kc) * (int)sizeof(T));
+    const bool live = kt_load * BK < g.K;  // steps past the end load nothing
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const bool ok = live && ((a_taps[i] >> tapi) & 1u);
+      areg[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, ok ? a_off[i] + toff : kOob, 0, 0);
+    }
+    const uint32_t kb = (uint32_t)(kt_load * BK * (int)sizeof(T));
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i)
+      breg[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (live && b_off[i] != kOob) ? b_off[i] + kb : kOob, 0, 0);
+  };
+  auto advance_k = [&]() {
+    ++kt_load;
+    kc += BK;
+    if (kc >= g.Cc) {
+      kc = 0;
+      if (++ks == g.S) {
+        ks = 0;
+        ++kr;
+      }
+    }
+  };
+  auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const u4 (&breg)[B_IT]) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) *(u4 *)&As[buf][(i * 64 + lrow) * LK + lkv * VW] = areg[i];
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = i * 64 + lrow;
+      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf][row * LK + lkv * VW] = breg[i];
+    }
+  };
+
+  f16v acc[TM][TN];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
+
+  // two-step-deep software pipeline, unrolled by two (see k_igemm_v)
+  const int KT = g.K / BK;
+  u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
+  load_tiles(a0, b0);
+  advance_k();
+  load_tiles(a1, b1);
+  store_tiles(0, a0, b0);
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    advance_k();
+    load_tiles(a0, b0);
+    mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
+    store_tiles(1, a1, b1);
+    __syncthreads();
+    advance_k();
+    load_tiles(a1, b1);
+    mma_tile_t<T, TM, TN, LK, VW>(As[1], Bs[1], wm * TM * 32, wn * TN * 32, lane, acc);
+    store_tiles(0, a0, b0);
+    __syncthreads();
+  }
+  if (kt < KT) mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
+  store_tile_t<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -186,10 +331,10 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
   }
   const int b_tapoff = ((b_r - (-g.off)) * g.Win + (b_s - (-g.off))) * g.Cc + b_c;  // (r - pad, s - pad)
 
-  u4 areg[A_IT], breg[B_IT];
   const u4 zero4 = {0u, 0u, 0u, 0u};
 
-  auto load_tiles = [&](int mbase) {
+  // rows at or beyond m_end are masked, so the pipeline may load two steps ahead unconditionally
+  auto load_tiles = [&](int mbase, u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const int v = i * kThreads + tid;
@@ -211,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
       breg[i] = ok ? *(const u4 *)(x + base + b_tapoff) : zero4;
     }
   };
-  auto store_tiles = [&](int buf) {
+  auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const u4 (&breg)[B_IT]) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const int v = i * kThreads + tid;
@@ -233,32 +378,39 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
   const int gq = lane >> 4, j = lane & 15;
   const int frag_k = 8 * (gq >> 1) + (j >> 2), frag_c = 16 * (gq & 1) + 4 * (j & 3);
 
-  const int KT = m_end > m_begin ? (m_end - m_begin + BKM - 1) / BKM : 0;
-  if (KT > 0) {
-    load_tiles(m_begin);
-    store_tiles(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_tiles(m_begin + (kt + 1) * BKM);
+  auto mma_step = [&](const bf16_t *at, const bf16_t *bt) {
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       u4 af[TM], bf[TN];
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-        af[tm] = lds_tr_frag(As[buf], LDA, sub * 16 + frag_k, wm * TM * 32 + tm * 32 + frag_c);
+      for (int tm = 0; tm < TM; ++tm) af[tm] = lds_tr_frag(at, LDA, sub * 16 + frag_k, wm * TM * 32 + tm * 32 + frag_c);
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-        bf[tn] = lds_tr_frag(Bs[buf], LDB, sub * 16 + frag_k, wn * TN * 32 + tn * 32 + frag_c);
+      for (int tn = 0; tn < TN; ++tn) bf[tn] = lds_tr_frag(bt, LDB, sub * 16 + frag_k, wn * TN * 32 + tn * 32 + frag_c);
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) mma<bf16_t>(af[tm], bf[tn], acc[tm][tn]);
     }
-    if (kt + 1 < KT) store_tiles(buf ^ 1);
+  };
+  // two-step-deep software pipeline, unrolled by two (see k_igemm_v); an empty split writes zeros
+  const int KT = m_end > m_begin ? (m_end - m_begin + BKM - 1) / BKM : 0;
+  u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
+  load_tiles(m_begin, a0, b0);
+  load_tiles(m_begin + BKM, a1, b1);
+  store_tiles(0, a0, b0);
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 1 < KT; kt += 2) {
+    load_tiles(m_begin + (kt + 2) * BKM, a0, b0);
+    mma_step(As[0], Bs[0]);
+    store_tiles(1, a1, b1);
+    __syncthreads();
+    load_tiles(m_begin + (kt + 3) * BKM, a1, b1);
+    mma_step(As[1], Bs[1]);
+    store_tiles(0, a0, b0);
     __syncthreads();
   }
+  if (kt < KT) mma_step(As[0], Bs[0]);
 
   float *out = io.out + rep * io.out_rs + split * io.split_stride;
   const int col_l = lane & 31, h = lane >> 5;
@@ -287,6 +439,17 @@ hipError_t run_v(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, 
   return hipGetLastError();
 }
 
+template <typename T, int WM, int WN, int TM, int TN>
+hipError_t run_u(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, replicas);
+  if (out_f32)
+    hipLaunchKernelGGL((k_igemm_u<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+  else
+    hipLaunchKernelGGL((k_igemm_u<T, WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
+
 template <int WM, int WN, int TM, int TN>
 hipError_t run_tr(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
@@ -308,8 +471,29 @@ bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
   return io.vecA && io.vecB && g.Cc % vw == 0 && g.K % vw == 0 && g.R <= 16 && g.S <= 16;
 }
 
+// Uniform-tap kernel: a whole contraction step inside one tap, vector epilogue, 32-bit byte offsets.
+bool uniform_ok(int dtype, const ConvGeom &g, const GemmIO &io) {
+  const int bk = dtype ? 32 : 16;
+  return g.Cc % bk == 0 && g.R * g.S <= 32 && g.N % 4 == 0 && io.ldc % 4 == 0 && io.in_bytes > 0 &&
+         io.in_bytes < (1LL << 31) && (long long)g.N * g.K * (dtype ? 2 : 4) < (1LL << 31);
+}
+
 hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g,
                              const GemmIO &io) {
+  if (uniform_ok(dtype, g, io)) {
+    if (dtype == 0) return run_u<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
+    const int n = g.N;
+    if (n <= 32) return run_u<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);
+    if (n <= 64)
+      return tall_ok(g, 64, replicas) ? run_u<bf16_t, 4, 1, 2, 2>(st, out_f32, replicas, g, io)
+                                      : run_u<bf16_t, 4, 1, 1, 2>(st, out_f32, replicas, g, io);
+    if (n <= 96)
+      return tall_ok(g, 96, replicas) ? run_u<bf16_t, 4, 1, 2, 3>(st, out_f32, replicas, g, io)
+                                      : run_u<bf16_t, 4, 1, 1, 3>(st, out_f32, replicas, g, io);
+    if (n <= 128) return run_u<bf16_t, 2, 2, 2, 2>(st, out_f32, replicas, g, io);
+    if (n <= 192 || n % 192 == 0) return run_u<bf16_t, 2, 2, 2, 3>(st, out_f32, replicas, g, io);
+    return run_u<bf16_t, 2, 2, 2, 4>(st, out_f32, replicas, g, io);
+  }
   if (dtype == 0) return run_v<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
   const int n = g.N;
   if (n <= 32) return run_v<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);

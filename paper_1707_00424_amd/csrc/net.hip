@@ -299,6 +299,7 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         io.relu = op.relu;
         io.vecA = (op.Cin % vw == 0) && aligned_to(io.in, 16);
         io.vecB = (g.K % vw == 0) && (N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) && aligned_to(io.w, 16);
+        io.in_bytes = io.in_rs * N.esize;
         HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, io));
         break;
       }
@@ -381,6 +382,7 @@ hipError_t backward(const Run &r, float *grad) {
           io.accumulate = op.dx_accumulate;
           io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
           io.vecB = (gb.K % vw == 0) && (wsize % vw == 0);
+          io.in_bytes = io.in_rs * N.esize;
           HIP_TRY(launch_igemm(r.st, N.dtype, false, r.n, gb, io));
         }
         break;
