@@ -12,6 +12,8 @@
 //                  elements inside a step is irrelevant as long as A and B agree, which they do
 //                  because both are read from LDS with the same offsets);
 //   D (32x32 fp32, 16 registers v): column l % 32, row 8*(v/4) + 4*(l/32) + v%4.
+#include <stdlib.h>
+
 #include "igemm_dev.h"
 
 namespace {
@@ -406,7 +408,12 @@ int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   }
   const long long tiles = (long long)((g.K + bn - 1) / bn) * ((g.N + bm - 1) / bm) * replicas;
   const int steps = (g.M + 31) / 32;                  // contraction steps of 32 rows available
-  long long want = (1024 + tiles - 1) / tiles;        // aim at >= 1024 workgroups (4 per CU)
+  static const int target = [] {
+    const char *e = getenv("PARLE_WGRAD_BLOCKS");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 384;
+  }();
+  long long want = (target + tiles - 1) / tiles;      // aim at `target` workgroups (default 1.5 per CU: more splits cost more partial-sum traffic than they hide latency)
   if (want > steps / 4) want = steps / 4;             // keep >= 4 steps (128 rows) per split
   if (want < 1) want = 1;
   const long long cap = 65535 / replicas;

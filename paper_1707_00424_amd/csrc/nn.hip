@@ -255,6 +255,89 @@ __global__ __launch_bounds__(kThreads) void k_colreduce(int M, int C, int chunk,
   }
 }
 
+// Same reductions with 16-byte loads: a thread owns VW = 16/sizeof(T) consecutive channels of the
+// rows r0 + lr, r0 + lr + tr, ...; row-lanes are then summed through LDS in a fixed order.
+// Requires C % VW == 0 and C / VW <= 256.
+template <typename T, int MODE>
+__global__ __launch_bounds__(kThreads) void k_colreduce_vec(int M, int C, int chunk, const T *__restrict__ x,
+                                                            long long x_rs, const T *__restrict__ dy, long long dy_rs,
+                                                            const float *__restrict__ saved,
+                                                            const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, long long p_rs,
+                                                            double *__restrict__ partial) {
+  constexpr int VW = 16 / sizeof(T);
+  typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+  __shared__ float red[2 * VW][kThreads];
+  const int rep = blockIdx.y, split = blockIdx.x, S = gridDim.x;
+  const int CV = C / VW, tr = kThreads / CV;
+  const int lc = threadIdx.x % CV, lr = threadIdx.x / CV;
+  const bool active = lr < tr;
+  const int r0 = split * chunk, r1 = min(M, r0 + chunk);
+  const T *xp = x + rep * x_rs;
+  const T *dp = MODE == 2 ? dy + rep * dy_rs : nullptr;
+  float s1[VW], s2[VW], mean[VW], rstd[VW], gm[VW], bt[VW];
+#pragma unroll
+  for (int e = 0; e < VW; ++e) {
+    s1[e] = 0.f, s2[e] = 0.f;
+    if (MODE == 2 && active) {
+      const int c = lc * VW + e;
+      mean[e] = saved[(long long)rep * 2 * C + c];
+      rstd[e] = saved[(long long)rep * 2 * C + C + c];
+      gm[e] = gamma[rep * p_rs + c];
+      bt[e] = beta[rep * p_rs + c];
+    }
+  }
+  auto unpack = [](const u4v &v, float (&f)[VW]) {
+    if (sizeof(T) == 4) {
+      f[0] = __uint_as_float(v.x), f[1] = __uint_as_float(v.y), f[2] = __uint_as_float(v.z), f[3] = __uint_as_float(v.w);
+    } else {
+      const unsigned int w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        f[(2 * e) % VW] = __uint_as_float(w[e] << 16);
+        f[(2 * e + 1) % VW] = __uint_as_float(w[e] & 0xffff0000u);
+      }
+    }
+  };
+  if (active) {
+    for (int r = r0 + lr; r < r1; r += tr) {
+      float xv[VW];
+      unpack(*(const u4v *)(xp + (long long)r * C + lc * VW), xv);
+      if (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < VW; ++e) s1[e] += xv[e];
+      } else if (MODE == 1) {
+#pragma unroll
+        for (int e = 0; e < VW; ++e) s1[e] += xv[e], s2[e] += xv[e] * xv[e];
+      } else {
+        float dv[VW];
+        unpack(*(const u4v *)(dp + (long long)r * C + lc * VW), dv);
+#pragma unroll
+        for (int e = 0; e < VW; ++e) {
+          const float xh = (xv[e] - mean[e]) * rstd[e];
+          const float d = (xh * gm[e] + bt[e]) > 0.f ? dv[e] : 0.f;
+          s1[e] += d;
+          s2[e] += d * xh;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VW; ++e) {
+    red[e][threadIdx.x] = s1[e];
+    red[VW + e][threadIdx.x] = s2[e];
+  }
+  __syncthreads();
+  double *out = partial + ((long long)rep * S + split) * 2 * C;
+  for (int o = threadIdx.x; o < 2 * C; o += kThreads) {
+    const int k = o / C, c = o % C;
+    const int slot = k * VW + c % VW, col = c / VW;
+    double a = 0.0;
+    for (int j = 0; j < tr; ++j) a += (double)red[slot][j * CV + col];
+    out[o] = a;
+  }
+}
+
 // Sum over the row-splits of one channel's two partial sums: one wavefront per (channel, replica),
 // lane l takes splits l, l+64, ... in order, then a fixed shuffle tree (deterministic).
 __device__ __forceinline__ void sum_splits(const double *__restrict__ partial, int rep, int S, int C, int c, double &s1,
@@ -414,6 +497,21 @@ __global__ __launch_bounds__(kThreads) void k_row_mean(int n, long long len, con
   }
 }
 
+template <typename T, int MODE>
+void run_colreduce(hipStream_t st, dim3 grid, int M, int C, int chunk, int ct, const void *x, long long x_rs,
+                   const void *dy, long long dy_rs, const float *saved, const float *gamma, const float *beta,
+                   long long p_rs, double *partial) {
+  constexpr int VW = 16 / sizeof(T);
+  const bool vec = C % VW == 0 && C / VW <= kThreads && x_rs % VW == 0 && dy_rs % VW == 0 &&
+                   (reinterpret_cast<uintptr_t>(x) & 15) == 0 && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
+  if (vec)
+    hipLaunchKernelGGL((k_colreduce_vec<T, MODE>), grid, dim3(kThreads), 0, st, M, C, chunk, (const T *)x, x_rs,
+                       (const T *)dy, dy_rs, saved, gamma, beta, p_rs, partial);
+  else
+    hipLaunchKernelGGL((k_colreduce<T, MODE>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const T *)x, x_rs,
+                       (const T *)dy, dy_rs, saved, gamma, beta, p_rs, partial);
+}
+
 int channel_lanes(int C) {
   int ct = 1;
   while (ct < C && ct < 64) ct <<= 1;
@@ -518,12 +616,10 @@ hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, cons
   const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
   dim3 grid(S, n);
   DISPATCH_T(dtype,
-             hipLaunchKernelGGL((k_colreduce<float, 0>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)dy,
-                                dy_rs, (const float *)nullptr, 0LL, (const float *)nullptr, (const float *)nullptr,
-                                (const float *)nullptr, 0LL, partial),
-             hipLaunchKernelGGL((k_colreduce<bf16_t, 0>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
-                                (const bf16_t *)dy, dy_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
-                                (const float *)nullptr, (const float *)nullptr, 0LL, partial));
+             (run_colreduce<float, 0>(st, grid, M, C, chunk, ct, dy, dy_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
+                                      partial)),
+             (run_colreduce<bf16_t, 0>(st, grid, M, C, chunk, ct, dy, dy_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
+                                       partial)));
   hipLaunchKernelGGL(k_bias_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, grad, grad_rs);
   return hipGetLastError();
 }
@@ -541,12 +637,10 @@ hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, c
   const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
   dim3 grid(S, n);
   DISPATCH_T(dtype,
-             hipLaunchKernelGGL((k_colreduce<float, 1>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)x,
-                                x_rs, (const float *)nullptr, 0LL, (const float *)nullptr, (const float *)nullptr,
-                                (const float *)nullptr, 0LL, partial),
-             hipLaunchKernelGGL((k_colreduce<bf16_t, 1>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
-                                (const bf16_t *)x, x_rs, (const bf16_t *)nullptr, 0LL, (const float *)nullptr,
-                                (const float *)nullptr, (const float *)nullptr, 0LL, partial));
+             (run_colreduce<float, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
+                                      partial)),
+             (run_colreduce<bf16_t, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
+                                       partial)));
   hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, M, C, S, partial, saved, running,
                      run_rs);
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
@@ -578,11 +672,10 @@ hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const v
   const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
   dim3 grid(S, n);
   DISPATCH_T(dtype,
-             hipLaunchKernelGGL((k_colreduce<float, 2>), grid, dim3(kThreads), 0, st, M, C, chunk, ct, (const float *)x,
-                                x_rs, (const float *)dout, dout_rs, saved, gamma, beta, p_rs, partial),
-             hipLaunchKernelGGL((k_colreduce<bf16_t, 2>), grid, dim3(kThreads), 0, st, M, C, chunk, ct,
-                                (const bf16_t *)x, x_rs, (const bf16_t *)dout, dout_rs, saved, gamma, beta, p_rs,
-                                partial));
+             (run_colreduce<float, 2>(st, grid, M, C, chunk, ct, x, x_rs, dout, dout_rs, saved, gamma, beta, p_rs,
+                                      partial)),
+             (run_colreduce<bf16_t, 2>(st, grid, M, C, chunk, ct, x, x_rs, dout, dout_rs, saved, gamma, beta, p_rs,
+                                       partial)));
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, sums, dgamma, dbeta, p_rs);
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
   DISPATCH_T(dtype,
