@@ -409,6 +409,102 @@ __global__ __launch_bounds__(kThreads) void k_bn_apply_relu(int M, int C, const 
   }
 }
 
+// 16-byte vector forms of the two BN element-wise passes (C a multiple of the vector width).
+typedef unsigned int u4e __attribute__((ext_vector_type(4)));
+template <typename T>
+__device__ __forceinline__ void unpack16(const u4e &v, float *f) {
+  if (sizeof(T) == 4) {
+    f[0] = __uint_as_float(v.x), f[1] = __uint_as_float(v.y), f[2] = __uint_as_float(v.z), f[3] = __uint_as_float(v.w);
+  } else {
+    const unsigned int w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[(2 * e) % (16 / sizeof(T))] = __uint_as_float(w[e] << 16);
+      f[(2 * e + 1) % (16 / sizeof(T))] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+}
+template <typename T>
+__device__ __forceinline__ u4e pack16(const float *f) {
+  u4e v;
+  if (sizeof(T) == 4) {
+    v.x = __float_as_uint(f[0]), v.y = __float_as_uint(f[1]), v.z = __float_as_uint(f[2]), v.w = __float_as_uint(f[3]);
+  } else {
+    constexpr int W = 16 / sizeof(T);
+    v.x = f32_to_bf16(f[0]) | ((unsigned int)f32_to_bf16(f[1]) << 16);
+    v.y = f32_to_bf16(f[2]) | ((unsigned int)f32_to_bf16(f[3]) << 16);
+    v.z = f32_to_bf16(f[4 % W]) | ((unsigned int)f32_to_bf16(f[5 % W]) << 16);
+    v.w = f32_to_bf16(f[6 % W]) | ((unsigned int)f32_to_bf16(f[7 % W]) << 16);
+  }
+  return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_bn_apply_relu_vec(int M, int C, const T *__restrict__ x, long long x_rs,
+                                                                const float *__restrict__ gamma,
+                                                                const float *__restrict__ beta, long long p_rs,
+                                                                const float *__restrict__ saved, T *__restrict__ out,
+                                                                long long out_rs) {
+  constexpr int VW = 16 / sizeof(T);
+  const int rep = blockIdx.y;
+  const int CV = C / VW;
+  const long long total = (long long)M * CV;
+  const T *xp = x + rep * x_rs;
+  T *op = out + rep * out_rs;
+  const float *mean = saved + (long long)rep * 2 * C, *rstd = mean + C;
+  const float *gm = gamma + rep * p_rs, *bt = beta + rep * p_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c0 = (int)(i % CV) * VW;
+    float xv[VW], ov[VW];
+    unpack16<T>(*(const u4e *)(xp + i * VW), xv);
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+      const float v = (xv[e] - mean[c0 + e]) * rstd[c0 + e] * gm[c0 + e] + bt[c0 + e];
+      ov[e] = v > 0.f ? v : 0.f;
+    }
+    *(u4e *)(op + i * VW) = pack16<T>(ov);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_bn_bwd_apply_vec(int M, int C, const T *__restrict__ x, long long x_rs,
+                                                               const T *__restrict__ dout, long long dout_rs,
+                                                               const float *__restrict__ gamma,
+                                                               const float *__restrict__ beta, long long p_rs,
+                                                               const float *__restrict__ saved,
+                                                               const float *__restrict__ sums, const T *__restrict__ add,
+                                                               long long add_rs, T *__restrict__ dx, long long dx_rs) {
+  constexpr int VW = 16 / sizeof(T);
+  const int rep = blockIdx.y;
+  const int CV = C / VW;
+  const long long total = (long long)M * CV;
+  const T *xp = x + rep * x_rs;
+  const T *dp = dout + rep * dout_rs;
+  const T *ap = add ? add + rep * add_rs : nullptr;
+  T *op = dx + rep * dx_rs;
+  const float *mean = saved + (long long)rep * 2 * C, *rstd = mean + C;
+  const float *s1 = sums + (long long)rep * 2 * C, *s2 = s1 + C;
+  const float *gm = gamma + rep * p_rs, *bt = beta + rep * p_rs;
+  const float invM = 1.0f / (float)M;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int c0 = (int)(i % CV) * VW;
+    float xv[VW], dv[VW], av[VW], ov[VW];
+    unpack16<T>(*(const u4e *)(xp + i * VW), xv);
+    unpack16<T>(*(const u4e *)(dp + i * VW), dv);
+    if (ap) unpack16<T>(*(const u4e *)(ap + i * VW), av);
+#pragma unroll
+    for (int e = 0; e < VW; ++e) {
+      const int c = c0 + e;
+      const float xh = (xv[e] - mean[c]) * rstd[c];
+      const float d = (xh * gm[c] + bt[c]) > 0.f ? dv[e] : 0.f;
+      float v = gm[c] * rstd[c] * (d - s1[c] * invM - xh * s2[c] * invM);
+      if (ap) v += av[e];
+      ov[e] = v;
+    }
+    *(u4e *)(op + i * VW) = pack16<T>(ov);
+  }
+}
+
 __global__ __launch_bounds__(PARLE_WAVE) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
                                                                 float *__restrict__ sums, float *__restrict__ dgamma,
                                                                 float *__restrict__ dbeta, long long p_rs) {
@@ -643,6 +739,16 @@ hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, c
                                        partial)));
   hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, M, C, S, partial, saved, running,
                      run_rs);
+  const int vw = dtype ? 8 : 4;
+  if (C % vw == 0 && x_rs % vw == 0 && out_rs % vw == 0 && aligned_to(x, 16) && aligned_to(out, 16)) {
+    dim3 vgrid(blocks_for((long long)M * (C / vw), 8192), n);
+    DISPATCH_T(dtype,
+               hipLaunchKernelGGL(k_bn_apply_relu_vec<float>, vgrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs,
+                                  gamma, beta, p_rs, saved, (float *)out, out_rs),
+               hipLaunchKernelGGL(k_bn_apply_relu_vec<bf16_t>, vgrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)x,
+                                  x_rs, gamma, beta, p_rs, saved, (bf16_t *)out, out_rs));
+    return hipGetLastError();
+  }
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_bn_apply_relu<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs, gamma,
@@ -677,6 +783,19 @@ hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const v
              (run_colreduce<bf16_t, 2>(st, grid, M, C, chunk, ct, x, x_rs, dout, dout_rs, saved, gamma, beta, p_rs,
                                        partial)));
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, sums, dgamma, dbeta, p_rs);
+  const int vw = dtype ? 8 : 4;
+  if (C % vw == 0 && x_rs % vw == 0 && dout_rs % vw == 0 && dx_rs % vw == 0 && add_rs % vw == 0 && aligned_to(x, 16) &&
+      aligned_to(dout, 16) && aligned_to(dx, 16) && aligned_to(add, 16)) {
+    dim3 vgrid(blocks_for((long long)M * (C / vw), 8192), n);
+    DISPATCH_T(dtype,
+               hipLaunchKernelGGL(k_bn_bwd_apply_vec<float>, vgrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs,
+                                  (const float *)dout, dout_rs, gamma, beta, p_rs, saved, sums, (const float *)add,
+                                  add_rs, (float *)dx, dx_rs),
+               hipLaunchKernelGGL(k_bn_bwd_apply_vec<bf16_t>, vgrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)x, x_rs,
+                                  (const bf16_t *)dout, dout_rs, gamma, beta, p_rs, saved, sums, (const bf16_t *)add,
+                                  add_rs, (bf16_t *)dx, dx_rs));
+    return hipGetLastError();
+  }
   dim3 agrid(blocks_for((long long)M * C, 4096), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_bn_bwd_apply<float>, agrid, dim3(kThreads), 0, st, M, C, (const float *)x, x_rs,

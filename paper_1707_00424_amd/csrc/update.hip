@@ -13,11 +13,13 @@ struct Tuning {
   int inner_unroll;   // float4 per thread per trip
   int blocks_per_cu;  // 0 = one trip per thread (grid covers the tensor)
   int nontemporal;
+  int contiguous;     // 1: a block's U vectors per thread are adjacent 4 KiB chunks; 0: a grid stride apart
 };
 
 const Tuning &tuning() {
   static Tuning t = [] {
-    Tuning v{2, 0, 1};
+    Tuning v{4, 0, 1, 1};
+    if (const char *s = getenv("PARLE_UPD_CONTIG")) v.contiguous = atoi(s);
     if (const char *s = getenv("PARLE_UPD_UNROLL")) v.inner_unroll = atoi(s);
     if (const char *s = getenv("PARLE_UPD_BLOCKS_PER_CU")) v.blocks_per_cu = atoi(s);
     if (const char *s = getenv("PARLE_UPD_NT")) v.nontemporal = atoi(s);
@@ -54,10 +56,15 @@ template <int U, bool NT, bool BF>
 __global__ __launch_bounds__(kThreads) void k_inner_update(const f4 *__restrict__ G, const f4 *__restrict__ X,
                                                            f4 *__restrict__ Y, f4 *__restrict__ VY,
                                                            f4 *__restrict__ Z, us4 *__restrict__ Y16, int64_t n4,
-                                                           float eta, float mu, float alpha, float wd, float g) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
+                                                           float eta, float mu, float alpha, float wd, float g,
+                                                           int contiguous) {
+  // contiguous: block b owns vectors [b*U*256, (b+1)*U*256); else vector u of a thread is a grid stride away
+  const int64_t stride = contiguous ? kThreads : (int64_t)gridDim.x * kThreads;
+  const int64_t first = contiguous ? (int64_t)blockIdx.x * kThreads * U + threadIdx.x
+                                   : (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int64_t trip = (int64_t)gridDim.x * kThreads * U;
   const float one_m_alpha = 1.0f - alpha;
-  for (int64_t q0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; q0 < n4; q0 += stride * U) {
+  for (int64_t q0 = first; q0 < n4; q0 += trip) {
     f4 gr[U], x[U], y[U], v[U], z[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -287,7 +294,7 @@ parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, co
 #define LAUNCH_INNER(U, NT, BF)                                                                                   \
   hipLaunchKernelGGL((k_inner_update<U, NT, BF>), dim3(grid_for(n4, U)), dim3(kThreads), 0, st, (const f4 *)grad, \
                      (const f4 *)x, (f4 *)y, (f4 *)vy, (f4 *)z, (us4 *)y_bf16, n4, eta_inner, momentum, alpha,    \
-                     weight_decay, g)
+                     weight_decay, g, t.contiguous)
 #define PICK_INNER(U)                   \
   do {                                  \
     if (t.nontemporal) {                \
@@ -304,8 +311,9 @@ parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, co
   } while (0)
   switch (t.inner_unroll) {
     case 1: PICK_INNER(1); break;
-    case 4: PICK_INNER(4); break;
-    default: PICK_INNER(2); break;
+    case 2: PICK_INNER(2); break;
+    case 8: PICK_INNER(8); break;
+    default: PICK_INNER(4); break;
   }
 #undef PICK_INNER
 #undef LAUNCH_INNER
