@@ -38,7 +38,7 @@ def algorithmic_bytes(n, n_elem, inner_steps, outer_steps, fused):
     return inner + mean + outer
 
 
-def cpu_baseline(sample_elems=4_000_000, inner=4):
+def cpu_baseline(sample_elems=N_PARAMS, inner=12):
     """The oracle as it stands (float32 mode), on a column sample of the same workload."""
     from oracle import parle as oparle
     from paper_1707_00424_amd import synth
