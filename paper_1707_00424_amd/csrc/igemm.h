@@ -94,6 +94,9 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 // Vector fast paths (igemm_fast.hip); launch_igemm / launch_wgrad pick them when applicable.
 bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
 hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+// Stride-1 'same' convolutions with the input patch staged once in LDS (igemm_halo.hip).
+bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
+hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);
 bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
 void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
 hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);

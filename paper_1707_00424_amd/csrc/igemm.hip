@@ -372,6 +372,7 @@ int bf16_ntile(int n) {
 
 hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
+  if (conv_halo_applicable(dtype, g, io, out_f32)) return launch_conv_halo(st, replicas, g, io);
   if (igemm_fast_applicable(dtype, g, io)) return launch_igemm_fast(st, dtype, out_f32, replicas, g, io);
   if (dtype == 0) return run_igemm<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
   switch (bf16_ntile(g.N)) {

@@ -67,6 +67,10 @@ CASES = [
     (2, 3, 10, 10, 5, 7, 5, 1, 0),      # 5x5 valid, odd channels
     (2, 37, 1, 1, 136, 72, 1, 1, 0),    # fully connected
     (1, 2, 8, 8, 16, 32, 1, 2, 0),      # strided 1x1 (shortcut)
+    (2, 3, 16, 16, 32, 40, 3, 1, 1),    # stride-1 "same" conv, one image per 256-pixel tile (LDS patch path)
+    (2, 5, 8, 8, 64, 96, 3, 1, 1),      # four images per tile, last tile ragged
+    (1, 2, 32, 32, 32, 20, 3, 1, 1),    # four tiles per image, narrow output
+    (2, 2, 16, 16, 64, 64, 3, 1, 1),    # both directions on the patch path
 ]
 
 
