@@ -13,12 +13,23 @@ typedef unsigned short bf16_t;  // raw bfloat16 bits
 
 #define PARLE_WAVE 64
 
-// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.  gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32, two values per instruction).
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned short f32_to_bf16(float f) {
-  unsigned int u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
+  const __bf16 r = (__bf16)f;
+  return __builtin_bit_cast(unsigned short, r);
+}
+// (lo, hi) -> lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ unsigned int f32x2_to_bf16x2(float lo, float hi) {
+  const f2 v = {lo, hi};
+  const bf16x2_hw r = __builtin_convertvector(v, bf16x2_hw);
+  return __builtin_bit_cast(unsigned int, r);
+}
+__device__ __forceinline__ us4 f32x4_to_bf16x4(f4 v) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  const u2 r = {f32x2_to_bf16x2(v.x, v.y), f32x2_to_bf16x2(v.z, v.w)};
+  return __builtin_bit_cast(us4, r);
 }
 __device__ __forceinline__ float bf16_to_f32(unsigned short h) { return __uint_as_float(((unsigned int)h) << 16); }
 

@@ -30,6 +30,11 @@ struct ConvGeom {
   int sp, off, sr, dshift;
   int M, N, K;  // per replica: rows, output columns, contraction length (K = R*S*Cc)
   FastDiv dPQ, dQ, dCc, dS;
+  // Row order inside an image.  0: natural (p, q).  Otherwise log2 P and log2 Q (both >= 1): the rows
+  // of an image are grouped by the parity class (p % 2, q % 2), class-major, so that the rows of a
+  // tile share the taps that a stride-2 backward-data gather can reach.  Only kernels that say so
+  // honour it; the launchers set it, not the callers.
+  int plp, plq;
 };
 
 struct GemmIO {

@@ -412,9 +412,10 @@ int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   static const int target = [] {
     const char *e = getenv("PARLE_WGRAD_BLOCKS");
     const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 384;
+    return v > 0 ? v : 512;
   }();
-  long long want = (target + tiles - 1) / tiles;      // aim at `target` workgroups (default 1.5 per CU: more splits cost more partial-sum traffic than they hide latency)
+  // at most `target` workgroups: two per compute unit, never a few stragglers in a third round
+  long long want = target / tiles;
   if (want > steps / 4) want = steps / 4;             // keep >= 4 steps (128 rows) per split
   if (want < 1) want = 1;
   const long long cap = 65535 / replicas;

@@ -72,6 +72,16 @@ __device__ __forceinline__ bool tap(int t, int dshift, int lim, int &idx) {
   return t >= 0 && (t & dm) == 0 && idx < lim;
 }
 
+// Row index of a tile -> pixel index (b*P + p)*Q + q, for geometries with parity-class row order.
+__device__ __forceinline__ uint32_t row_pixel(const ConvGeom &g, uint32_t m) {
+  if (g.plq == 0) return m;
+  const int lpq = g.plp + g.plq;
+  const uint32_t b = m >> lpq, mi = m & ((1u << lpq) - 1u);
+  const uint32_t cls = mi >> (lpq - 2), rem = mi & ((1u << (lpq - 2)) - 1u);
+  const uint32_t ph = rem >> (g.plq - 1), qh = rem & ((1u << (g.plq - 1)) - 1u);
+  return (b << lpq) | ((2u * ph + (cls >> 1)) << g.plq) | (2u * qh + (cls & 1u));
+}
+
 // Shared MFMA inner step: every wavefront multiplies its TM x TN fragments for both halves of BK.
 template <typename T, int TM, int TN, int LK, int VW>
 __device__ __forceinline__ void mma_tile(const T *As, const T *Bs, int arow0, int brow0, int lane, f16v (&acc)[TM][TN]) {
@@ -127,8 +137,7 @@ struct Vec4<bf16_t> {
     return r;
   }
   static __device__ __forceinline__ us4 from_f32(f4 v) {
-    us4 r = {f32_to_bf16(v.x), f32_to_bf16(v.y), f32_to_bf16(v.z), f32_to_bf16(v.w)};
-    return r;
+    return f32x4_to_bf16x4(v);
   }
 };
 
@@ -146,13 +155,14 @@ __device__ __forceinline__ void store_tile_t(const ConvGeom &g, const GemmIO &io
   for (int tm = 0; tm < TM; ++tm) {
     const int m = mrow0 + tm * 32 + row_l;
     if (m >= g.M) continue;
+    const uint32_t pix = row_pixel(g, (uint32_t)m);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
         const int n = ncol0 + tn * 32 + 8 * vg + 4 * h;
         if (n >= g.N) continue;
-        const long long o = (long long)m * io.ldc + n;
+        const long long o = (long long)pix * io.ldc + n;
         f4 val = {acc[tm][tn][4 * vg], acc[tm][tn][4 * vg + 1], acc[tm][tn][4 * vg + 2], acc[tm][tn][4 * vg + 3]};
         if (bias) {
           if (bias_vec) {
@@ -180,6 +190,76 @@ __device__ __forceinline__ void store_tile_t(const ConvGeom &g, const GemmIO &io
           if (io.accumulate) val += Vec4<T>::to_f32(*(const TV *)(out + o));
           *(TV *)(out + o) = Vec4<T>::from_f32(val);
         }
+      }
+    }
+  }
+}
+
+// Epilogue for transposed accumulator tiles, staged through LDS so that global memory sees whole
+// rows: each wavefront parks 32 rows x (TN*32) columns of fp32 sums in its own LDS strip, then walks
+// the strip in row-major order, four consecutive channels per lane and consecutive lanes on
+// consecutive channels -- reads of the residual / mask / old output and the final store all hit
+// contiguous runs of a row (the whole row when the tile spans it) instead of 16 bytes per row.
+// Requires N % 4 == 0 and ldc % 4 == 0.  `stage` is this wavefront's strip of kStageFloats<TN>
+// floats; the caller has made sure (barrier) that no wavefront still reads LDS that it aliases.
+// Every wavefront of the workgroup must call this (it contains workgroup barriers).
+template <int TN>
+constexpr int kStageFloats = 32 * (TN * 32 + 4);
+
+template <typename T, int TM, int TN, bool OUT_F32>
+__device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
+                                               f16v (&acc)[TM][TN], float *stage) {
+  typedef typename Vec4<T>::type TV;
+  constexpr int CW = TN * 32, LD = CW + 4, CPR = CW / 4;
+  const int row_l = lane & 31, h = lane >> 5;
+  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
+  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
+  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
+  const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 15) == 0;  // segment offsets need not be 16-byte aligned
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    if (tm) __syncthreads();  // the strip has been read out
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const f4 val = {acc[tm][tn][4 * vg], acc[tm][tn][4 * vg + 1], acc[tm][tn][4 * vg + 2], acc[tm][tn][4 * vg + 3]};
+        *(f4 *)&stage[row_l * LD + tn * 32 + 8 * vg + 4 * h] = val;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < CPR / 2; ++it) {
+      const int c = it * 64 + lane;
+      const int row = c / CPR, ch = (c - row * CPR) * 4;
+      const int m = mrow0 + tm * 32 + row, n = ncol0 + ch;
+      if (m >= g.M || n >= g.N) continue;
+      const long long o = (long long)row_pixel(g, (uint32_t)m) * io.ldc + n;
+      f4 val = *(const f4 *)&stage[row * LD + ch];
+      if (bias) {
+        if (bias_vec) {
+          val += *(const f4 *)(bias + n);
+        } else {
+          val.x += bias[n], val.y += bias[n + 1], val.z += bias[n + 2], val.w += bias[n + 3];
+        }
+      }
+      if (resid) val += Vec4<T>::to_f32(*(const TV *)(resid + o));
+      if (io.relu) {
+        val.x = val.x > 0.f ? val.x : 0.f, val.y = val.y > 0.f ? val.y : 0.f;
+        val.z = val.z > 0.f ? val.z : 0.f, val.w = val.w > 0.f ? val.w : 0.f;
+      }
+      if (mask) {
+        const f4 mk = Vec4<T>::to_f32(*(const TV *)(mask + o));
+        val.x = mk.x > 0.f ? val.x : 0.f, val.y = mk.y > 0.f ? val.y : 0.f;
+        val.z = mk.z > 0.f ? val.z : 0.f, val.w = mk.w > 0.f ? val.w : 0.f;
+      }
+      if (OUT_F32) {
+        float *out = (float *)io.out + rep * io.out_rs;
+        if (io.accumulate) val += *(const f4 *)(out + o);
+        *(f4 *)(out + o) = val;
+      } else {
+        T *out = (T *)io.out + rep * io.out_rs;
+        if (io.accumulate) val += Vec4<T>::to_f32(*(const TV *)(out + o));
+        *(TV *)(out + o) = Vec4<T>::from_f32(val);
       }
     }
   }

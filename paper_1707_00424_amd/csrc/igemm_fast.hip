@@ -169,8 +169,12 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   static_assert(BM % 64 == 0, "row tile must be a multiple of 64");
   constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
-  __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
-  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+  // operand tiles (double-buffered); the epilogue reuses the same LDS as its staging strips
+  constexpr int kPipeBytes = 2 * (BM + BN) * LK * (int)sizeof(T);
+  constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
+  __shared__ __attribute__((aligned(16))) char smem[kPipeBytes > kStageBytes ? kPipeBytes : kStageBytes];
+  T(*As)[BM * LK] = reinterpret_cast<T(*)[BM * LK]>(smem);
+  T(*Bs)[BN * LK] = reinterpret_cast<T(*)[BN * LK]>(smem + 2 * BM * LK * sizeof(T));
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -185,22 +189,26 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
 
   // per row: byte offset of its window origin (+ this lane's vector inside a step) and one validity
   // bit per tap
-  uint32_t a_off[A_IT], a_taps[A_IT];
+  __shared__ uint32_t taps_any;
+  if (tid == 0) taps_any = 0;
+  __syncthreads();
+  uint32_t a_off[A_IT], a_taps[A_IT], my_taps = 0;
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
     const int m = m0 + i * 64 + lrow;
     const bool ok = m < g.M;
-    const uint32_t mm = ok ? m : 0;
+    const uint32_t mm = ok ? row_pixel(g, (uint32_t)m) : 0;
     const int b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
     const int p = fdiv(rem, g.dQ), q = rem - p * g.Q;
     const int bh = p * g.sp + g.off, bw = q * g.sp + g.off;
-    uint32_t taps = 0;
-    for (int r = 0; r < g.R; ++r) {
-      int idx;
-      const bool hv = ok && tap(bh + r * g.sr, g.dshift, g.Hin, idx);
-      for (int s2 = 0; s2 < g.S; ++s2) taps |= (uint32_t)(hv && tap(bw + s2 * g.sr, g.dshift, g.Win, idx)) << (r * g.S + s2);
-    }
+    // window columns the row can reach, then one copy of that mask per reachable window row
+    uint32_t wmask = 0, taps = 0;
+    int idx;
+    for (int s2 = 0; s2 < g.S; ++s2) wmask |= (uint32_t)tap(bw + s2 * g.sr, g.dshift, g.Win, idx) << s2;
+    for (int r = 0; r < g.R; ++r) taps |= tap(bh + r * g.sr, g.dshift, g.Hin, idx) ? wmask << (r * g.S) : 0u;
+    taps = ok ? taps : 0u;
     a_taps[i] = taps;
+    my_taps |= taps;
     a_off[i] = (uint32_t)(((b * g.Hin + (bh >> g.dshift)) * g.Win * g.Cc + (bw >> g.dshift) * g.Cc + lkv * VW) * (int)sizeof(T));
   }
   uint32_t b_off[B_IT];
@@ -209,19 +217,25 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
     const int row = i * 64 + lrow, nrow = n0 + row;
     b_off[i] = (row < BN && nrow < g.N) ? (uint32_t)((nrow * g.K + lkv * VW) * (int)sizeof(T)) : kOob;
   }
-  // wavefront-uniform contraction state: tap (kr, ks), first channel kc of the step, step index
-  int kr = 0, ks = 0, kc = 0, kt_load = 0;
+  // taps that no row of this tile can reach are skipped altogether (stride-2 backward-data with
+  // parity-class row order: a tile reaches 1, 2 or 4 of 9 taps)
+  if (my_taps) atomicOr(&taps_any, my_taps);
+  __syncthreads();
+  const uint32_t tile_taps = __builtin_amdgcn_readfirstlane(taps_any);
+  const int KT = __builtin_popcount(tile_taps) * (g.Cc / BK);
+  // wavefront-uniform contraction state: tap index, first channel kc of the step, steps loaded
+  int tapi = tile_taps ? __builtin_ctz(tile_taps) : 0, kc = 0, kt_load = 0;
 
   auto load_tiles = [&](u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
-    const int tapi = kr * g.S + ks;
+    const int kr = (int)fdiv((uint32_t)tapi, g.dS), ks = tapi - kr * g.S;
     const uint32_t toff = (uint32_t)((g.sr * (((kr >> g.dshift) * g.Win + (ks >> g.dshift)) * g.Cc) + kc) * (int)sizeof(T));
-    const bool live = kt_load * BK < g.K;  // steps past the end load nothing
+    const bool live = kt_load < KT;  // steps past the end load nothing
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const bool ok = live && ((a_taps[i] >> tapi) & 1u);
       areg[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, ok ? a_off[i] + toff : kOob, 0, 0);
     }
-    const uint32_t kb = (uint32_t)(kt_load * BK * (int)sizeof(T));
+    const uint32_t kb = (uint32_t)((tapi * g.Cc + kc) * (int)sizeof(T));
 #pragma unroll
     for (int i = 0; i < B_IT; ++i)
       breg[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (live && b_off[i] != kOob) ? b_off[i] + kb : kOob, 0, 0);
@@ -231,10 +245,8 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
     kc += BK;
     if (kc >= g.Cc) {
       kc = 0;
-      if (++ks == g.S) {
-        ks = 0;
-        ++kr;
-      }
+      const uint32_t rest = tile_taps & ~((2u << tapi) - 1u);
+      tapi = rest ? __builtin_ctz(rest) : 0;
     }
   };
   auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const u4 (&breg)[B_IT]) {
@@ -256,7 +268,6 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
   // two-step-deep software pipeline, unrolled by two (see k_igemm_v)
-  const int KT = g.K / BK;
   u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
   load_tiles(a0, b0);
   advance_k();
@@ -277,7 +288,9 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
     __syncthreads();
   }
   if (kt < KT) mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
-  store_tile_t<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc);
+  __syncthreads();  // operand tiles are dead: their LDS becomes the staging strips
+  store_tile_lds<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc,
+                                     reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -475,12 +488,21 @@ bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
 bool uniform_ok(int dtype, const ConvGeom &g, const GemmIO &io) {
   const int bk = dtype ? 32 : 16;
   return g.Cc % bk == 0 && g.R * g.S <= 32 && g.N % 4 == 0 && io.ldc % 4 == 0 && io.in_bytes > 0 &&
-         io.in_bytes < (1LL << 31) && (long long)g.N * g.K * (dtype ? 2 : 4) < (1LL << 31);
+         io.in_bytes < (1LL << 31) && (long long)g.M * io.ldc * 4 < (1LL << 31) && (long long)g.N * g.K * (dtype ? 2 : 4) < (1LL << 31);
 }
 
-hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g,
+hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g_in,
                              const GemmIO &io) {
+  ConvGeom g = g_in;
+  g.plp = g.plq = 0;
   if (uniform_ok(dtype, g, io)) {
+    // stride-2 backward data on power-of-two images: rows grouped by parity class
+    auto log2_exact = [](int v) {
+      int l = 0;
+      while ((1 << l) < v) ++l;
+      return (1 << l) == v ? l : 0;
+    };
+    if (g.dshift == 1 && log2_exact(g.P) >= 1 && log2_exact(g.Q) >= 1) g.plp = log2_exact(g.P), g.plq = log2_exact(g.Q);
     if (dtype == 0) return run_u<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
     const int n = g.N;
     if (n <= 32) return run_u<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);

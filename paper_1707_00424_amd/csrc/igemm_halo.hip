@@ -36,8 +36,12 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
   constexpr int TM = 2, BM = 256, BN = TN * 32;  // four wavefronts stacked along the pixel axis
   constexpr int B_IT = (BN + 63) / 64;
   constexpr int H_IT = (kHaloSlots * 4 + kThreads - 1) / kThreads;
-  __shared__ __attribute__((aligned(16))) T Hs[kHaloSlots * LK];
-  __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
+  // patch + double-buffered weight tiles; the epilogue reuses the same LDS as its staging strips
+  constexpr int kPipeBytes = (kHaloSlots + 2 * BN) * LK * (int)sizeof(T);
+  constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
+  __shared__ __attribute__((aligned(16))) char smem[kPipeBytes > kStageBytes ? kPipeBytes : kStageBytes];
+  T *Hs = reinterpret_cast<T *>(smem);
+  T(*Bs)[BN * LK] = reinterpret_cast<T(*)[BN * LK]>(smem + kHaloSlots * LK * sizeof(T));
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
@@ -184,7 +188,9 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
     __syncthreads();
   }
   if (kt < KT) mma_step(0);
-  store_tile_t<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc);
+  __syncthreads();  // patch and weight tiles are dead: their LDS becomes the staging strips
+  store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
+                                   reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
 }
 
 template <int TN>
@@ -220,7 +226,7 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32) {
   HaloGeom hg;
   return dtype == 1 && !out_f32 && io.vecA && io.vecB && g.R * g.S > 1 && g.Cc % 32 == 0 && g.N % 4 == 0 &&
-         io.ldc % 4 == 0 && io.in_bytes > 0 && io.in_bytes < (1LL << 31) && (long long)g.N * g.K * 2 < (1LL << 31) &&
+         io.ldc % 4 == 0 && io.in_bytes > 0 && io.in_bytes < (1LL << 31) && (long long)g.M * io.ldc * 4 < (1LL << 31) && (long long)g.N * g.K * 2 < (1LL << 31) &&
          g.M >= 256 && make_halo_geom(g, hg);
 }
 

@@ -431,10 +431,10 @@ __device__ __forceinline__ u4e pack16(const float *f) {
     v.x = __float_as_uint(f[0]), v.y = __float_as_uint(f[1]), v.z = __float_as_uint(f[2]), v.w = __float_as_uint(f[3]);
   } else {
     constexpr int W = 16 / sizeof(T);
-    v.x = f32_to_bf16(f[0]) | ((unsigned int)f32_to_bf16(f[1]) << 16);
-    v.y = f32_to_bf16(f[2]) | ((unsigned int)f32_to_bf16(f[3]) << 16);
-    v.z = f32_to_bf16(f[4 % W]) | ((unsigned int)f32_to_bf16(f[5 % W]) << 16);
-    v.w = f32_to_bf16(f[6 % W]) | ((unsigned int)f32_to_bf16(f[7 % W]) << 16);
+    v.x = f32x2_to_bf16x2(f[0], f[1]);
+    v.y = f32x2_to_bf16x2(f[2], f[3]);
+    v.z = f32x2_to_bf16x2(f[4 % W], f[5 % W]);
+    v.w = f32x2_to_bf16x2(f[6 % W], f[7 % W]);
   }
   return v;
 }

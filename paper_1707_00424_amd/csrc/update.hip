@@ -41,12 +41,7 @@ __device__ __forceinline__ void st4(f4 *p, f4 v) {
     *p = v;
 }
 __device__ __forceinline__ us4 to_bf16x4(f4 v) {
-  us4 o;
-  o.x = f32_to_bf16(v.x);
-  o.y = f32_to_bf16(v.y);
-  o.z = f32_to_bf16(v.z);
-  o.w = f32_to_bf16(v.w);
-  return o;
+  return f32x4_to_bf16x4(v);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -71,6 +71,9 @@ CASES = [
     (2, 5, 8, 8, 64, 96, 3, 1, 1),      # four images per tile, last tile ragged
     (1, 2, 32, 32, 32, 20, 3, 1, 1),    # four tiles per image, narrow output
     (2, 2, 16, 16, 64, 64, 3, 1, 1),    # both directions on the patch path
+    (2, 4, 16, 16, 32, 64, 3, 2, 1),    # stride 2, power-of-two image: backward-data rows grouped by parity class
+    (1, 3, 8, 8, 32, 32, 3, 2, 1),      # same, tiles spanning several classes and images
+    (2, 3, 16, 8, 16, 32, 1, 2, 0),     # strided 1x1: three of four parity classes reach no tap
 ]
 
 
