@@ -45,3 +45,40 @@ class ParleNet:
         loss, nerr = nets.evaluate(self.a, flat, images, labels, bn_state=bn, dtype=self.dtype)
         sp = float(sum(np.sum((self.st.x[i] - self.st.x_ref) ** 2) for i in range(self.cfg.n_replicas)))
         return loss, nerr, sp
+
+
+class ElasticNet:
+    """Elastic-SGD (Section 2.2) on a network: gradient of the mini-batch loss at every replica x^a,
+    then one coupled step of the replicas and the reference; :func:`scope` is rule (9) on rho."""
+
+    def __init__(self, a, cfg: parle.ParleConfig, x0, dtype=np.float64):
+        from . import elastic
+        self._el = elastic
+        self.a, self.cfg, self.dtype = a, cfg, dtype
+        self.st = elastic.init_state(x0, cfg, dtype=dtype)
+        self.bn = [nets.new_bn_state(a, dtype) for _ in range(cfg.n_replicas)]
+
+    def step(self, images, labels):
+        n = self.cfg.n_replicas
+        losses = np.zeros(n)
+        G = np.zeros_like(self.st.xa)
+        for a_i in range(n):
+            losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.xa[a_i], images[a_i], labels[a_i],
+                                                     bn_state=self.bn[a_i], dtype=self.dtype)
+        self._el.step(self.st, G, self.cfg)
+        self.last_grad = G
+        return losses
+
+    def scope(self):
+        self._el.scope(self.st, self.cfg)
+
+    def eval(self, which, images, labels):
+        if which < 0:
+            flat = self.st.x
+            bn = {k: [np.mean([b[k][0] for b in self.bn], axis=0), np.mean([b[k][1] for b in self.bn], axis=0)]
+                  for k in self.bn[0]}
+        else:
+            flat, bn = self.st.xa[which], self.bn[which]
+        loss, nerr = nets.evaluate(self.a, flat, images, labels, bn_state=bn, dtype=self.dtype)
+        sp = float(sum(np.sum((self.st.xa[i] - self.st.x) ** 2) for i in range(self.cfg.n_replicas)))
+        return loss, nerr, sp
