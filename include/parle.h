@@ -7,7 +7,8 @@
  *   - the fused inner update: (8a) with Nesterov momentum and the running average (8b),
  *   - the replica mean: (8d) with eta'' = rho/n (Section 3.1),
  *   - the fused outer update: (8c) with Nesterov momentum and the reset y^a <- x^a,
- *   - the scoping rule (9) on the host.
+ *   - the scoping rule (9) on the host,
+ *   - as a variant, Elastic-SGD (Section 2.2) with scoping on rho (algorithm = 1).
  * Equation, section and remark numbers refer to "Parle: parallelizing stochastic gradient
  * descent" (arXiv 1707.00424).
  *
@@ -33,6 +34,16 @@ extern "C" {
 #endif
 
 typedef struct parle_ctx parle_ctx; /* opaque, host memory, owned by the library */
+
+typedef enum {
+  PARLE_ALG_PARLE = 0,   /* updates (8a)-(8d): proximal inner loop, elastic outer step every L steps.
+                            n = 1 with rho0 = 0 is Entropy-SGD (Section 2.1, updates (6a)-(6c)). */
+  PARLE_ALG_ELASTIC = 1  /* Elastic-SGD, Section 2.2: every step moves all replicas with the elastic
+                            force r*(x^a - x) and the reference towards the replica mean.  State: the
+                            replicas x^a live in buffers.y (and its bf16 copy), their momentum in
+                            buffers.vy, the reference in buffers.x_ref; x is only read by parle_init,
+                            z and vx are not touched.  parle_outer_step applies rule (9) to r alone. */
+} parle_algorithm;
 
 typedef enum {
   PARLE_OK = 0,
@@ -99,6 +110,9 @@ typedef struct {
                             reference, which is then refreshed from the replicas before the move */
   int32_t reset_flags;   /* at the outer step: bit 0 z^a <- x^a, bit 1 momentum of y^a <- 0 */
   int32_t fuse_outer;    /* 0 = replica-mean kernel then outer-update kernel; 1 = one kernel */
+  int32_t algorithm;     /* parle_algorithm */
+  int32_t graph_block;   /* 1 = parle_inner_block replays a captured HIP graph (see there); 0 = it enqueues
+                            the steps one by one */
 } parle_config;
 
 typedef struct {
@@ -159,6 +173,26 @@ parle_status parle_init(const parle_config *cfg, const parle_buffers *buf, void 
  * FLAT: images_dev and labels_dev must be NULL; only the update runs on the caller's grad.
  */
 parle_status parle_inner_step(parle_ctx *ctx, const float *images_dev, const int32_t *labels_dev, float *loss_dev);
+/*
+ * With algorithm = PARLE_ALG_ELASTIC the same call is one Elastic-SGD step (Section 2.2): forward,
+ * loss, backward at the replicas, then for every replica and the reference, all from the old values,
+ *   d = grad + weight_decay*x^a + r*(x^a - x);  v <- mu*v + d;  x^a <- x^a - eta_inner*(d + mu*v)
+ *   x <- x - eta_outer*(x - (1/n) sum_a x^a)
+ */
+
+/*
+ * `steps` consecutive inner steps, equal in effect to calling parle_inner_step on
+ * images_dev + s*n*batch*H*W*C, labels_dev + s*n*batch, loss_dev + s*n for s = 0 .. steps-1
+ * (the latency-bound small networks spend their time in launches, Section 4.1's LeNet being the case
+ * in the paper).  With graph_block = 1 the second call with the same four arguments records the
+ * launches into a HIP graph and later calls with those arguments replay it; other arguments run
+ * step by step and replace the remembered ones.  The graph runs on a stream of the library's own,
+ * ordered after and before the init stream with events, so the caller sees the usual stream order.
+ * The coupling multipliers are read from device memory inside the graph: scoping needs no re-capture.
+ * Not for FLAT (the caller writes the gradient between steps).  1 <= steps <= 4096.
+ */
+parle_status parle_inner_block(parle_ctx *ctx, const float *images_dev, const int32_t *labels_dev, int32_t steps,
+                               float *loss_dev);
 
 /*
  * The outer step, meant to follow every L inner steps (any count >= 1 is accepted, else ESTATE):
@@ -166,12 +200,13 @@ parle_status parle_inner_step(parle_ctx *ctx, const float *images_dev, const int
  *   d = c_z*(x^a - z^a) + r*(x^a - x_ref);  vx <- mu*vx + d;  x^a <- x^a - eta_outer*(d + mu*vx)   (8c)
  *   y^a <- x^a (and z^a, vy per reset_flags), bf16 copy refreshed
  *   g <- min(g / (1 - 1/(2B)), gamma_max), r likewise                         rule (9)
+ * With algorithm = PARLE_ALG_ELASTIC no kernel runs: only r advances by rule (9).
  */
 parle_status parle_outer_step(parle_ctx *ctx);
 
 /*
  * Forward only, at the reference (which = -1; BN uses running statistics averaged over the
- * replicas) or at replica `which`'s x^a.  images_dev [count, H, W, C], labels_dev [count],
+ * replicas) or at replica `which`'s x^a (buffers.x; buffers.y for Elastic-SGD).  images_dev [count, H, W, C], labels_dev [count],
  * 1 <= count <= n*batch.  Writes to HOST: mean loss, number of misclassified samples, and (if
  * not NULL) spread = sum_a ||x^a - x_ref||^2.  Blocks until the stream is idle.
  * FLAT: images/labels must be NULL, count 0; only spread is produced.
@@ -199,6 +234,14 @@ void parle_destroy(parle_ctx *ctx);
 parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, const float *x,
                                   float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
                                   float alpha, float weight_decay, float g);
+
+/* Elastic-SGD (Section 2.2), both updates in one launch, all from the old values:
+ *   d = grad + weight_decay*xa + r*(xa - x_ref);  v <- momentum*v + d;  xa <- xa - eta*(d + momentum*v)
+ *   x_ref <- x_ref - eta_ref*(x_ref - mean_a xa)
+ * xa, v, grad: [n, n_pad]; x_ref: [n_pad]; xa_bf16 may be NULL. */
+parle_status parle_k_elastic_step(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, float *xa, float *v,
+                                  float *x_ref, void *xa_bf16, float eta, float eta_ref, float momentum,
+                                  float weight_decay, float r);
 
 /* (8d) with eta'' = rho/n: x_ref[i] = (sum_{a=0..n-1} x[a][i]) / n, summed in replica order. */
 parle_status parle_k_replica_mean(void *hip_stream, int32_t n, int64_t n_pad, const float *x, float *x_ref);

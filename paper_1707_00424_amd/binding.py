@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libparle.so")
 PARLE_OK, PARLE_EINVAL, PARLE_ENOMEM, PARLE_EALIGN, PARLE_ESIZE, PARLE_EHIP, PARLE_ESTATE, PARLE_ENONFINITE = (
     0, -1, -2, -3, -4, -5, -6, -7)
 MODEL_FLAT, MODEL_MLP, MODEL_LENET, MODEL_ALLCNN_C, MODEL_WRN = 0, 1, 2, 3, 4
+ALG_PARLE, ALG_ELASTIC = 0, 1
 SEG_KINDS = {0: "weight", 1: "bias", 2: "bn_gamma", 3: "bn_beta"}
 
 
@@ -29,7 +30,7 @@ class parle_config(C.Structure):
                 ("gamma0", C.c_float), ("rho0", C.c_float), ("gamma_max", C.c_float), ("rho_max", C.c_float),
                 ("scoping_B", C.c_int64),
                 ("xa_mode", C.c_int32), ("xref_mode", C.c_int32), ("reset_flags", C.c_int32),
-                ("fuse_outer", C.c_int32)]
+                ("fuse_outer", C.c_int32), ("algorithm", C.c_int32), ("graph_block", C.c_int32)]
 
 
 class parle_sizes(C.Structure):
@@ -60,6 +61,7 @@ _SIGNATURES = {
     "parle_query_layout": [C.POINTER(parle_config), C.c_int32, C.POINTER(parle_segment)],
     "parle_init": [C.POINTER(parle_config), C.POINTER(parle_buffers), C.c_void_p, C.POINTER(C.c_void_p)],
     "parle_inner_step": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_inner_block": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
     "parle_outer_step": [C.c_void_p],
     "parle_eval": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_float),
                    C.POINTER(C.c_int32), C.POINTER(C.c_float)],
@@ -68,6 +70,8 @@ _SIGNATURES = {
     "parle_set_state": [C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_float],
     "parle_k_inner_update": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float, C.c_float],
+    "parle_k_elastic_step": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float, C.c_float],
     "parle_k_replica_mean": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
     "parle_k_outer_update": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float,
@@ -120,11 +124,11 @@ def _check(status, ctx=None):
 def make_config(model=MODEL_FLAT, n_replicas=1, batch=0, L=25, compute_bf16=0, in_h=0, in_w=0, in_c=0, n_classes=0,
                 arch=(0, 0, 0, 0), n_params=0, eta_inner=0.1, eta_outer=0.1, momentum=0.9, alpha=0.75,
                 weight_decay=0.0, gamma0=0.01, rho0=1.0, gamma_max=1.0, rho_max=10.0, scoping_B=0, xa_mode=0,
-                xref_mode=0, reset_flags=3, fuse_outer=0) -> parle_config:
+                xref_mode=0, reset_flags=3, fuse_outer=0, algorithm=ALG_PARLE, graph_block=0) -> parle_config:
     a = list(arch) + [0] * (4 - len(arch))
     return parle_config(model, n_replicas, batch, L, compute_bf16, in_h, in_w, in_c, n_classes, (C.c_int32 * 4)(*a),
                         n_params, eta_inner, eta_outer, momentum, alpha, weight_decay, gamma0, rho0, gamma_max,
-                        rho_max, scoping_B, xa_mode, xref_mode, reset_flags, fuse_outer)
+                        rho_max, scoping_B, xa_mode, xref_mode, reset_flags, fuse_outer, algorithm, graph_block)
 
 
 def parle_query_sizes(cfg: parle_config) -> parle_sizes:
@@ -160,6 +164,12 @@ def parle_k_inner_update(grad, x, y, vy, z, y_bf16, eta_inner, momentum, alpha, 
     n, n_pad = x.shape
     _check(lib().parle_k_inner_update(_stream_handle(stream), n, n_pad, _ptr(grad), _ptr(x), _ptr(y), _ptr(vy),
                                       _ptr(z), _ptr(y_bf16), eta_inner, momentum, alpha, weight_decay, g))
+
+
+def parle_k_elastic_step(grad, xa, v, x_ref, xa_bf16, eta, eta_ref, momentum, weight_decay, r, stream=None):
+    n, n_pad = xa.shape
+    _check(lib().parle_k_elastic_step(_stream_handle(stream), n, n_pad, _ptr(grad), _ptr(xa), _ptr(v), _ptr(x_ref),
+                                      _ptr(xa_bf16), eta, eta_ref, momentum, weight_decay, r))
 
 
 def parle_k_replica_mean(x, x_ref, stream=None):
@@ -241,6 +251,11 @@ class Parle:
 
     def parle_inner_step(self, images=None, labels=None, loss=None):
         _check(lib().parle_inner_step(self.ctx, _ptr(images), _ptr(labels), _ptr(loss)), self.ctx)
+
+    def parle_inner_block(self, images, labels, loss=None):
+        """images ``[steps, n, B, H, W, C]``, labels ``[steps, n, B]``, loss ``[steps, n]`` or None."""
+        _check(lib().parle_inner_block(self.ctx, _ptr(images), _ptr(labels), int(images.shape[0]), _ptr(loss)),
+               self.ctx)
 
     def parle_outer_step(self):
         _check(lib().parle_outer_step(self.ctx), self.ctx)

@@ -19,6 +19,13 @@ struct parle_ctx {
   int64_t k = 0, outer_done = 0, inner_since_outer = 0;
   double g = 0.0, r = 0.0;  // multipliers 1/gamma, 1/rho of rule (9), kept in double on the host
   std::string err;
+  // graph replay of an inner block: the library's own stream, the events that tie it to the caller's
+  // stream, the instantiated graph and the arguments it was recorded for
+  hipStream_t gstream = nullptr;
+  hipEvent_t ev_in = nullptr, ev_out = nullptr;
+  hipGraphExec_t gexec = nullptr;
+  const void *gk_images = nullptr, *gk_labels = nullptr, *gk_loss = nullptr;
+  int32_t gk_steps = 0;
 };
 
 namespace {
@@ -26,6 +33,7 @@ namespace {
 constexpr int64_t kRowAlign = 1024;      // elements: every replica row starts 4 KiB aligned
 constexpr int64_t kHeaderBytes = 65536;  // front of the workspace: spread partials and result scalars
 constexpr int64_t kScalarOff = 32768;
+constexpr int64_t kCouplingOff = kScalarOff + 64;  // {g, r} for launches that read them from memory
 
 thread_local std::string g_init_err;
 
@@ -72,6 +80,14 @@ parle_status check_config(const parle_config *cfg, Arch &arch, std::string &msg)
   if (cfg->scoping_B < 0 || (cfg->xa_mode | 1) != 1 || (cfg->xref_mode | 1) != 1 || (cfg->fuse_outer | 1) != 1 ||
       (cfg->compute_bf16 | 1) != 1 || (cfg->reset_flags & ~3)) {
     msg = "scoping_B, xa_mode, xref_mode, fuse_outer, compute_bf16 or reset_flags out of range";
+    return PARLE_EINVAL;
+  }
+  if ((cfg->algorithm | 1) != 1 || (cfg->graph_block | 1) != 1) {
+    msg = "algorithm or graph_block out of range";
+    return PARLE_EINVAL;
+  }
+  if (cfg->graph_block && cfg->model == PARLE_MODEL_FLAT) {
+    msg = "graph_block needs a network model";
     return PARLE_EINVAL;
   }
   if (cfg->xref_mode == 1 && cfg->fuse_outer == 0) {
@@ -121,6 +137,49 @@ parle_status hip_fail(parle_ctx *ctx, hipError_t e, const char *what) {
 }
 
 void *net_ws(parle_ctx *ctx) { return (char *)ctx->buf.workspace + kHeaderBytes; }
+
+float *coupling_dev(parle_ctx *ctx) {
+  return ctx->cfg.graph_block ? (float *)((char *)ctx->buf.workspace + kCouplingOff) : nullptr;
+}
+
+// g, r changed on the host: refresh the copy that captured launches read
+parle_status push_coupling(parle_ctx *ctx) {
+  if (!ctx->cfg.graph_block) return PARLE_OK;
+  return parle_internal_set_coupling(ctx->stream, coupling_dev(ctx), (float)ctx->g, (float)ctx->r);
+}
+
+// the replicas that the network is evaluated at and that the spread is measured on
+const float *replica_rows(const parle_ctx *ctx) {
+  return ctx->cfg.algorithm == PARLE_ALG_ELASTIC ? ctx->buf.y : ctx->buf.x;
+}
+
+// One inner step on stream `st`, no bookkeeping: gradient at the replicas, then the fused update.
+parle_status enqueue_inner(parle_ctx *ctx, hipStream_t st, const float *images_dev, const int32_t *labels_dev,
+                           float *loss_dev) {
+  const parle_config &c = ctx->cfg;
+  if (c.model != PARLE_MODEL_FLAT) {
+    hipError_t e = net_train_step(ctx->net, st, ctx->buf.y, ctx->buf.y_bf16, ctx->buf.grad, (float *)ctx->buf.bn_stats,
+                                  net_ws(ctx), images_dev, labels_dev, loss_dev);
+    if (e != hipSuccess) return hip_fail(ctx, e, "forward/backward");
+  }
+  void *shadow = c.compute_bf16 ? ctx->buf.y_bf16 : nullptr;
+  parle_status s;
+  if (c.algorithm == PARLE_ALG_ELASTIC)
+    s = parle_internal_elastic_step(st, c.n_replicas, ctx->sizes.n_pad, ctx->buf.grad, ctx->buf.y, ctx->buf.vy,
+                                    ctx->buf.x_ref, shadow, c.eta_inner, c.eta_outer, c.momentum, c.weight_decay,
+                                    (float)ctx->r, coupling_dev(ctx));
+  else
+    s = parle_internal_inner_update(st, c.n_replicas, ctx->sizes.n_pad, ctx->buf.grad, ctx->buf.x, ctx->buf.y,
+                                    ctx->buf.vy, ctx->buf.z, shadow, c.eta_inner, c.momentum, c.alpha, c.weight_decay,
+                                    (float)ctx->g, coupling_dev(ctx));
+  if (s) return fail(ctx, s, "update launch failed");
+  return PARLE_OK;
+}
+
+void drop_graph(parle_ctx *ctx) {
+  if (ctx->gexec) hipGraphExecDestroy(ctx->gexec);
+  ctx->gexec = nullptr;
+}
 
 }  // namespace
 
@@ -207,6 +266,7 @@ parle_status parle_init(const parle_config *cfg, const parle_buffers *buf, void 
     if ((e = net_init_bn(ctx->net, st, (float *)buf->bn_stats)) != hipSuccess)
       return bail(PARLE_EHIP, std::string("bn init: ") + hipGetErrorString(e));
   }
+  if (push_coupling(ctx)) return bail(PARLE_EHIP, "coupling upload launch failed");
   *out = ctx;
   return PARLE_OK;
 }
@@ -221,16 +281,74 @@ parle_status parle_inner_step(parle_ctx *ctx, const float *images_dev, const int
     if (!images_dev || !labels_dev) return fail(ctx, PARLE_EINVAL, "images and labels are required");
     if (!aligned_to(images_dev, 16) || !aligned_to(labels_dev, 4) || !aligned_to(loss_dev, 4))
       return fail(ctx, PARLE_EALIGN, "images must be 16-byte aligned, labels and loss 4-byte aligned");
-    hipError_t e = net_train_step(ctx->net, ctx->stream, ctx->buf.y, ctx->buf.y_bf16, ctx->buf.grad,
-                                  (float *)ctx->buf.bn_stats, net_ws(ctx), images_dev, labels_dev, loss_dev);
-    if (e != hipSuccess) return hip_fail(ctx, e, "forward/backward");
   }
-  parle_status s = parle_k_inner_update(ctx->stream, c.n_replicas, ctx->sizes.n_pad, ctx->buf.grad, ctx->buf.x,
-                                        ctx->buf.y, ctx->buf.vy, ctx->buf.z, c.compute_bf16 ? ctx->buf.y_bf16 : nullptr,
-                                        c.eta_inner, c.momentum, c.alpha, c.weight_decay, (float)ctx->g);
-  if (s) return fail(ctx, s, "inner update launch failed");
+  if (parle_status s = enqueue_inner(ctx, ctx->stream, images_dev, labels_dev, loss_dev)) return s;
   ctx->k += 1;
   ctx->inner_since_outer += 1;
+  return PARLE_OK;
+}
+
+parle_status parle_inner_block(parle_ctx *ctx, const float *images_dev, const int32_t *labels_dev, int32_t steps,
+                               float *loss_dev) {
+  if (!ctx) return PARLE_EINVAL;
+  const parle_config &c = ctx->cfg;
+  if (c.model == PARLE_MODEL_FLAT) return fail(ctx, PARLE_EINVAL, "a block of inner steps needs a network model");
+  if (!images_dev || !labels_dev) return fail(ctx, PARLE_EINVAL, "images and labels are required");
+  if (steps < 1 || steps > 4096) return fail(ctx, PARLE_EINVAL, "steps must be in [1, 4096]");
+  const int64_t img_stride = (int64_t)c.n_replicas * c.batch * ctx->sizes.image_elems;
+  const int64_t lab_stride = (int64_t)c.n_replicas * c.batch;
+  if (!aligned_to(images_dev, 16) || (img_stride & 3) || !aligned_to(labels_dev, 4) || !aligned_to(loss_dev, 4))
+    return fail(ctx, PARLE_EALIGN, "every step's images must be 16-byte aligned, labels and loss 4-byte aligned");
+  auto run_steps = [&](hipStream_t st) -> parle_status {
+    for (int32_t s = 0; s < steps; ++s)
+      if (parle_status rc = enqueue_inner(ctx, st, images_dev + s * img_stride, labels_dev + s * lab_stride,
+                                          loss_dev ? loss_dev + (int64_t)s * c.n_replicas : nullptr))
+        return rc;
+    return PARLE_OK;
+  };
+  const bool same = ctx->gk_images == images_dev && ctx->gk_labels == labels_dev && ctx->gk_loss == loss_dev &&
+                    ctx->gk_steps == steps;
+  if (!c.graph_block || !same) {
+    // step by step; with graph_block the arguments are remembered and recorded when they come again
+    if (parle_status rc = run_steps(ctx->stream)) return rc;
+    if (c.graph_block) {
+      drop_graph(ctx);
+      ctx->gk_images = images_dev, ctx->gk_labels = labels_dev, ctx->gk_loss = loss_dev, ctx->gk_steps = steps;
+    }
+  } else {
+    hipError_t e;
+    if (!ctx->gstream) {
+      if ((e = hipStreamCreateWithFlags(&ctx->gstream, hipStreamNonBlocking)) != hipSuccess ||
+          (e = hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming)) != hipSuccess ||
+          (e = hipEventCreateWithFlags(&ctx->ev_out, hipEventDisableTiming)) != hipSuccess)
+        return hip_fail(ctx, e, "graph stream setup");
+    }
+    if (!ctx->gexec) {
+      if ((e = hipStreamBeginCapture(ctx->gstream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
+        return hip_fail(ctx, e, "begin capture");
+      const parle_status rc = run_steps(ctx->gstream);
+      hipGraph_t graph = nullptr;
+      e = hipStreamEndCapture(ctx->gstream, &graph);  // always closes the capture, also after a failed launch
+      if (rc || e != hipSuccess) {
+        if (graph) hipGraphDestroy(graph);
+        return rc ? rc : hip_fail(ctx, e, "end capture");
+      }
+      e = hipGraphInstantiate(&ctx->gexec, graph, nullptr, nullptr, 0);
+      hipGraphDestroy(graph);
+      if (e != hipSuccess) {
+        ctx->gexec = nullptr;
+        return hip_fail(ctx, e, "graph instantiate");
+      }
+    }
+    if ((e = hipEventRecord(ctx->ev_in, ctx->stream)) != hipSuccess ||
+        (e = hipStreamWaitEvent(ctx->gstream, ctx->ev_in, 0)) != hipSuccess ||
+        (e = hipGraphLaunch(ctx->gexec, ctx->gstream)) != hipSuccess ||
+        (e = hipEventRecord(ctx->ev_out, ctx->gstream)) != hipSuccess ||
+        (e = hipStreamWaitEvent(ctx->stream, ctx->ev_out, 0)) != hipSuccess)
+      return hip_fail(ctx, e, "graph launch");
+  }
+  ctx->k += steps;
+  ctx->inner_since_outer += steps;
   return PARLE_OK;
 }
 
@@ -238,6 +356,16 @@ parle_status parle_outer_step(parle_ctx *ctx) {
   if (!ctx) return PARLE_EINVAL;
   if (ctx->inner_since_outer < 1) return fail(ctx, PARLE_ESTATE, "outer step needs an inner step since the last one");
   const parle_config &c = ctx->cfg;
+  if (c.algorithm == PARLE_ALG_ELASTIC) {  // Section 2.2 has no outer update: only rho is scoped, by rule (9)
+    ctx->outer_done += 1;
+    ctx->inner_since_outer = 0;
+    if (c.scoping_B > 0) {
+      const double q = 1.0 - 1.0 / (2.0 * (double)c.scoping_B);
+      ctx->r = fmin(ctx->r / q, (double)c.rho_max);
+      if (push_coupling(ctx)) return fail(ctx, PARLE_EHIP, "coupling upload launch failed");
+    }
+    return PARLE_OK;
+  }
   const float cz = c.xa_mode == 0 ? (float)ctx->g : 1.0f;
   parle_status s = PARLE_OK;
   if (!c.fuse_outer) s = parle_k_replica_mean(ctx->stream, c.n_replicas, ctx->sizes.n_pad, ctx->buf.x, ctx->buf.x_ref);
@@ -252,6 +380,7 @@ parle_status parle_outer_step(parle_ctx *ctx) {
     const double q = 1.0 - 1.0 / (2.0 * (double)c.scoping_B);
     ctx->g = fmin(ctx->g / q, (double)c.gamma_max);
     ctx->r = fmin(ctx->r / q, (double)c.rho_max);
+    if (push_coupling(ctx)) return fail(ctx, PARLE_EHIP, "coupling upload launch failed");
   }
   return PARLE_OK;
 }
@@ -276,7 +405,7 @@ parle_status parle_eval(parle_ctx *ctx, int32_t which, const float *images_dev, 
     if (count < 1 || (int64_t)count > (int64_t)c.n_replicas * c.batch)
       return fail(ctx, PARLE_EINVAL, "count must be in [1, n_replicas*batch]");
     if (!aligned_to(images_dev, 16)) return fail(ctx, PARLE_EALIGN, "images must be 16-byte aligned");
-    const float *row = which < 0 ? ctx->buf.x_ref : ctx->buf.x + (int64_t)which * ctx->sizes.n_pad;
+    const float *row = which < 0 ? ctx->buf.x_ref : replica_rows(ctx) + (int64_t)which * ctx->sizes.n_pad;
     const float *bn_row = nullptr;
     if (ctx->sizes.bn_bytes) {
       const int64_t per = net_bn_floats_per_replica(ctx->net);
@@ -294,7 +423,7 @@ parle_status parle_eval(parle_ctx *ctx, int32_t which, const float *images_dev, 
     if (e != hipSuccess) return hip_fail(ctx, e, "eval forward");
   }
   if (spread_host) {
-    parle_status s = parle_k_spread(ctx->stream, c.n_replicas, ctx->sizes.n_pad, ctx->buf.x, ctx->buf.x_ref,
+    parle_status s = parle_k_spread(ctx->stream, c.n_replicas, ctx->sizes.n_pad, replica_rows(ctx), ctx->buf.x_ref,
                                     (double *)hdr, d_spread);
     if (s) return fail(ctx, s, "spread launch failed");
   }
@@ -331,6 +460,7 @@ parle_status parle_set_state(parle_ctx *ctx, int64_t k, int64_t outer_done, floa
   // a resumed run may go straight to an outer step only if the block it interrupts had begun
   ctx->inner_since_outer = ctx->cfg.L > 0 ? k - outer_done * (int64_t)ctx->cfg.L : 0;
   if (ctx->inner_since_outer < 0) ctx->inner_since_outer = 0;
+  if (push_coupling(ctx)) return fail(ctx, PARLE_EHIP, "coupling upload launch failed");
   return PARLE_OK;
 }
 
@@ -338,6 +468,10 @@ const char *parle_last_error(const parle_ctx *ctx) { return ctx ? ctx->err.c_str
 
 void parle_destroy(parle_ctx *ctx) {
   if (!ctx) return;
+  drop_graph(ctx);
+  if (ctx->ev_in) hipEventDestroy(ctx->ev_in);
+  if (ctx->ev_out) hipEventDestroy(ctx->ev_out);
+  if (ctx->gstream) hipStreamDestroy(ctx->gstream);
   net_destroy(ctx->net);
   delete ctx;
 }

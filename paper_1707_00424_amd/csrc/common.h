@@ -48,3 +48,14 @@ static inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_
 
 // fp32 -> bf16 (round to nearest even) copy of `count` elements (count % 4 == 0), enqueued on `st`.
 parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst, int64_t count);
+
+// Launchers behind the C ABI that also take `coupling_dev`: two floats {g, r} in device memory that
+// override the by-value multipliers (a captured launch cannot change its arguments).  NULL = use the
+// arguments.
+parle_status parle_internal_set_coupling(hipStream_t st, float *coupling_dev, float g, float r);
+parle_status parle_internal_inner_update(hipStream_t st, int32_t n, int64_t n_pad, const float *grad, const float *x,
+                                         float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
+                                         float alpha, float weight_decay, float g, const float *coupling_dev);
+parle_status parle_internal_elastic_step(hipStream_t st, int32_t n, int64_t n_pad, const float *grad, float *xa,
+                                         float *v, float *x_ref, void *xa_bf16, float eta, float eta_ref,
+                                         float momentum, float weight_decay, float r, const float *coupling_dev);

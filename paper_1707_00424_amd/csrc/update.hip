@@ -51,8 +51,10 @@ template <int U, bool NT, bool BF>
 __global__ __launch_bounds__(kThreads) void k_inner_update(const f4 *__restrict__ G, const f4 *__restrict__ X,
                                                            f4 *__restrict__ Y, f4 *__restrict__ VY,
                                                            f4 *__restrict__ Z, us4 *__restrict__ Y16, int64_t n4,
-                                                           float eta, float mu, float alpha, float wd, float g,
-                                                           int contiguous) {
+                                                           float eta, float mu, float alpha, float wd, float g_arg,
+                                                           const float *__restrict__ coupling, int contiguous) {
+  // a captured launch cannot change its arguments: it reads the proximal multiplier from memory
+  const float g = coupling ? coupling[0] : g_arg;
   // contiguous: block b owns vectors [b*U*256, (b+1)*U*256); else vector u of a thread is a grid stride away
   const int64_t stride = contiguous ? kThreads : (int64_t)gridDim.x * kThreads;
   const int64_t first = contiguous ? (int64_t)blockIdx.x * kThreads * U + threadIdx.x
@@ -181,6 +183,46 @@ __global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4
 }
 
 // ---------------------------------------------------------------------------------------------
+// Elastic-SGD (Section 2.2), both coupled updates in one pass over a column:
+//   x^a <- x^a - eta [ grad + wd x^a + r (x^a - x) ]   (Nesterov momentum on the replicas)
+//   x   <- x - eta_ref ( x - mean_a x^a )               (mean of the replicas before the move)
+// ---------------------------------------------------------------------------------------------
+template <int N, bool BF>
+__global__ __launch_bounds__(kThreads) void k_elastic_step(const f4 *__restrict__ G, f4 *__restrict__ XA,
+                                                           f4 *__restrict__ V, f4 *__restrict__ XR,
+                                                           us4 *__restrict__ X16, int n_rt, int64_t np4, float eta,
+                                                           float eta_ref, float mu, float wd, float r_arg,
+                                                           const float *__restrict__ coupling) {
+  const float r = coupling ? coupling[1] : r_arg;
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  const int n = N > 0 ? N : n_rt;
+  const float fn = (float)n;
+  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+    const f4 xr = XR[q];
+    f4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int a = 0; a < n; ++a) {
+      const int64_t o = (int64_t)a * np4 + q;
+      const f4 x = ld4<true>(XA + o);
+      const f4 gr = ld4<true>(G + o);
+      const f4 v = ld4<true>(V + o);
+      s = a ? s + x : x;
+      const f4 d = gr + wd * x + r * (x - xr);
+      const f4 vn = mu * v + d;
+      const f4 xn = x - eta * (d + mu * vn);
+      st4<true>(V + o, vn);
+      st4<true>(XA + o, xn);
+      if (BF) __builtin_nontemporal_store(to_bf16x4(xn), X16 + o);
+    }
+    XR[q] = xr - eta_ref * (xr - s / fn);
+  }
+}
+
+__global__ void k_set_coupling(float *dst, float g, float r) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) dst[0] = g, dst[1] = r;
+}
+
+// ---------------------------------------------------------------------------------------------
 // sum_a ||x^a - x_ref||^2: per-thread fp32 partial over a few elements, fp64 from the wavefront
 // reduction on; per-block partials are summed by one block in a fixed order (deterministic).
 // ---------------------------------------------------------------------------------------------
@@ -273,11 +315,15 @@ parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst,
   return launched();
 }
 
-extern "C" {
+parle_status parle_internal_set_coupling(hipStream_t st, float *coupling_dev, float g, float r) {
+  if (!coupling_dev) return PARLE_EINVAL;
+  hipLaunchKernelGGL(k_set_coupling, dim3(1), dim3(64), 0, st, coupling_dev, g, r);
+  return launched();
+}
 
-parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, const float *x,
-                                  float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
-                                  float alpha, float weight_decay, float g) {
+parle_status parle_internal_inner_update(hipStream_t st, int32_t n, int64_t n_pad, const float *grad, const float *x,
+                                         float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
+                                         float alpha, float weight_decay, float g, const float *coupling_dev) {
   if (parle_status s = check_flat_args(n, n_pad)) return s;
   if (!grad || !x || !y || !vy || !z) return PARLE_EINVAL;
   if (!aligned_to(grad, 16) || !aligned_to(x, 16) || !aligned_to(y, 16) || !aligned_to(vy, 16) || !aligned_to(z, 16) ||
@@ -285,11 +331,10 @@ parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, co
     return PARLE_EALIGN;
   const int64_t n4 = (int64_t)n * n_pad / 4;
   const Tuning &t = tuning();
-  hipStream_t st = (hipStream_t)hip_stream;
 #define LAUNCH_INNER(U, NT, BF)                                                                                   \
   hipLaunchKernelGGL((k_inner_update<U, NT, BF>), dim3(grid_for(n4, U)), dim3(kThreads), 0, st, (const f4 *)grad, \
                      (const f4 *)x, (f4 *)y, (f4 *)vy, (f4 *)z, (us4 *)y_bf16, n4, eta_inner, momentum, alpha,    \
-                     weight_decay, g, t.contiguous)
+                     weight_decay, g, coupling_dev, t.contiguous)
 #define PICK_INNER(U)                   \
   do {                                  \
     if (t.nontemporal) {                \
@@ -313,6 +358,57 @@ parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, co
 #undef PICK_INNER
 #undef LAUNCH_INNER
   return launched();
+}
+
+parle_status parle_internal_elastic_step(hipStream_t st, int32_t n, int64_t n_pad, const float *grad, float *xa,
+                                         float *v, float *x_ref, void *xa_bf16, float eta, float eta_ref,
+                                         float momentum, float weight_decay, float r, const float *coupling_dev) {
+  if (parle_status s = check_flat_args(n, n_pad)) return s;
+  if (!grad || !xa || !v || !x_ref) return PARLE_EINVAL;
+  if (!aligned_to(grad, 16) || !aligned_to(xa, 16) || !aligned_to(v, 16) || !aligned_to(x_ref, 16) ||
+      !aligned_to(xa_bf16, 8))
+    return PARLE_EALIGN;
+  const int64_t np4 = n_pad / 4;
+  dim3 grid(grid_for(np4, 1));
+#define LAUNCH_ELASTIC(N, BF)                                                                                     \
+  hipLaunchKernelGGL((k_elastic_step<N, BF>), grid, dim3(kThreads), 0, st, (const f4 *)grad, (f4 *)xa, (f4 *)v,    \
+                     (f4 *)x_ref, (us4 *)xa_bf16, n, np4, eta, eta_ref, momentum, weight_decay, r, coupling_dev)
+#define PICK_ELASTIC(N)                                                    \
+  case N:                                                                  \
+    if (xa_bf16) LAUNCH_ELASTIC(N, true); else LAUNCH_ELASTIC(N, false);   \
+    break
+  switch (n) {
+    PICK_ELASTIC(1);
+    PICK_ELASTIC(2);
+    PICK_ELASTIC(3);
+    PICK_ELASTIC(4);
+    PICK_ELASTIC(5);
+    PICK_ELASTIC(6);
+    PICK_ELASTIC(7);
+    PICK_ELASTIC(8);
+    default:
+      if (xa_bf16) LAUNCH_ELASTIC(0, true); else LAUNCH_ELASTIC(0, false);
+      break;
+  }
+#undef PICK_ELASTIC
+#undef LAUNCH_ELASTIC
+  return launched();
+}
+
+extern "C" {
+
+parle_status parle_k_inner_update(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, const float *x,
+                                  float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
+                                  float alpha, float weight_decay, float g) {
+  return parle_internal_inner_update((hipStream_t)hip_stream, n, n_pad, grad, x, y, vy, z, y_bf16, eta_inner, momentum,
+                                     alpha, weight_decay, g, nullptr);
+}
+
+parle_status parle_k_elastic_step(void *hip_stream, int32_t n, int64_t n_pad, const float *grad, float *xa, float *v,
+                                  float *x_ref, void *xa_bf16, float eta, float eta_ref, float momentum,
+                                  float weight_decay, float r) {
+  return parle_internal_elastic_step((hipStream_t)hip_stream, n, n_pad, grad, xa, v, x_ref, xa_bf16, eta, eta_ref,
+                                     momentum, weight_decay, r, nullptr);
 }
 
 parle_status parle_k_replica_mean(void *hip_stream, int32_t n, int64_t n_pad, const float *x, float *x_ref) {

@@ -86,6 +86,8 @@ def test_layout_matches_oracle_small_sizes():
     dict(n_replicas=1, n_params=8, gamma0=float("nan")), dict(model=9, n_replicas=1, n_params=8),
     dict(model=pb.MODEL_MLP, n_replicas=1, batch=0),
     dict(model=pb.MODEL_LENET, n_replicas=1, batch=2, in_h=6, in_w=6),
+    dict(n_replicas=1, n_params=8, algorithm=2), dict(n_replicas=1, n_params=8, graph_block=2),
+    dict(n_replicas=1, n_params=8, graph_block=1),      # a graph block needs a network model
 ])
 def test_bad_configurations_are_rejected(kw):
     with pytest.raises(pb.ParleError) as e:
@@ -104,6 +106,7 @@ def test_null_arguments_do_not_crash():
     assert L.parle_query_sizes(None, None) == pb.PARLE_EINVAL
     assert L.parle_outer_step(None) == pb.PARLE_EINVAL
     assert L.parle_inner_step(None, None, None, None) == pb.PARLE_EINVAL
+    assert L.parle_inner_block(None, None, None, 1, None) == pb.PARLE_EINVAL
     L.parle_destroy(None)
     cfg = pb.make_config(n_replicas=2, n_params=100)
     h = C.c_void_p()
@@ -113,3 +116,25 @@ def test_null_arguments_do_not_crash():
     assert b"NULL" in L.parle_last_error(None)
     bufs = pb.parle_buffers(*([256 + 8] * 10))   # misaligned fake pointers: rejected before any use
     assert L.parle_init(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == pb.PARLE_EALIGN
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors of the ABI structs have the size and field offsets a C compiler gives the header."""
+    structs = {"parle_config": pb.parle_config, "parle_sizes": pb.parle_sizes, "parle_segment": pb.parle_segment,
+               "parle_buffers": pb.parle_buffers, "parle_conv_desc": pb.parle_conv_desc}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "parle.h"', 'int main(void) {']
+    for name, st in structs.items():
+        lines.append(f'  printf("{name} %zu\\n", sizeof({name}));')
+        for field, _ in st._fields_:
+            lines.append(f'  printf("{name}.{field} %zu\\n", offsetof({name}, {field}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    import subprocess
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for name, st in structs.items():
+        assert int(out[name]) == C.sizeof(st), name
+        for field, _ in st._fields_:
+            assert int(out[f"{name}.{field}"]) == getattr(st, field).offset, (name, field)

@@ -246,3 +246,59 @@ def test_call_order_and_argument_errors(gpu):
     P.parle_outer_step()
     P.parle_set_state(50, 2, 0.5, 2.0)
     assert P.parle_get_state() == (50, 2, 0.5, 2.0)
+
+
+# ---------------------------------------------------------------------------------------------
+# Elastic-SGD (Section 2.2) with scoping on rho
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,N", [(1, 4), (3, 1000), (8, 70_004), (9, 2052)])
+@pytest.mark.parametrize("bf", [0, 1])
+def test_elastic_step_kernel(gpu, n, N, bf):
+    from oracle import elastic as oel
+    torch, pb = gpu
+    rng = np.random.default_rng(300 + n)
+    G, xa, v = (rng.standard_normal((n, N)).astype(np.float32) * s for s in (1e-2, 0.05, 0.02))
+    ref = rng.standard_normal(N).astype(np.float32) * 0.05
+    cfg = oparle.ParleConfig(n_replicas=n, eta_inner=0.1, eta_outer=0.05, momentum=0.9, weight_decay=5e-4, rho0=1.5)
+    st = oel.ElasticState(xa=xa.astype(np.float64), v=v.astype(np.float64), x=ref.astype(np.float64), r=1.5)
+    oel.step(st, G, cfg)
+    dG, dxa, dv, dr = (_dev(torch, a) for a in (G, xa, v, ref))
+    d16 = torch.zeros((n, N), dtype=torch.bfloat16, device="cuda") if bf else None
+    pb.parle_k_elastic_step(dG, dxa, dv, dr, d16, 0.1, 0.05, 0.9, 5e-4, 1.5)
+    torch.cuda.synchronize()
+    assert_close("xa", dxa.cpu().numpy(), st.xa)
+    assert_close("v", dv.cpu().numpy(), st.v)
+    assert_close("x", dr.cpu().numpy(), st.x)
+    assert np.array_equal(dG.cpu().numpy(), G)
+    if bf:
+        assert np.array_equal(d16.view(torch.int16).cpu().numpy().view(np.uint16), bf16_rne_bits(dxa.cpu().numpy()))
+
+
+def test_elastic_flat_workload_with_scoping(gpu):
+    """Elastic-SGD through the C ABI on the update-only inputs: 40 steps, rule (9) on rho every 5."""
+    from oracle import elastic as oel
+    torch, pb = gpu
+    n, N, steps, every = 4, 30_001, 40, 5
+    x0 = synth.flat_params(21, n, N)
+    base = dict(n_replicas=n, L=every, eta_inner=0.1, eta_outer=0.1, momentum=0.9, rho0=1.0, scoping_B=3,
+                weight_decay=1e-4)
+    ocfg = oparle.ParleConfig(**base)
+    st = oel.init_state(x0, ocfg)
+    P = pb.Parle(pb.make_config(model=pb.MODEL_FLAT, n_params=N, algorithm=pb.ALG_ELASTIC, **base), x0)
+    for k in range(steps):
+        G = synth.flat_grads(21, k, n, N)
+        P.grad[:, :N].copy_(torch.as_tensor(G))
+        P.parle_inner_step()
+        oel.step(st, G, ocfg)
+        if (k + 1) % every == 0:
+            P.parle_outer_step()
+            oel.scope(st, ocfg)
+    got = P.state()
+    assert_close("xa", got["y"], st.xa)
+    assert_close("v", got["vy"], st.v)
+    assert_close("x", got["x_ref"], st.x)
+    k, od, g, r = P.parle_get_state()
+    assert (k, od) == (steps, steps // every) and abs(r - st.r) <= 1e-6 * st.r and st.r > 1.0
+    _, _, sp = P.parle_eval()
+    want = float(((st.xa - st.x) ** 2).sum())
+    assert abs(sp - want) <= 1e-5 * want

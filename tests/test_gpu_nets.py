@@ -287,3 +287,89 @@ def test_eval_matches_oracle(gpu, name, bf16):
         for r in range(n):
             ref = np.concatenate([np.concatenate(O.bn[r][name_]) for name_, _ in onets.bn_layers(a)])
             check("bn running stats", got[r], ref, 1e-4 if not bf16 else 2e-2)
+
+
+# ---------------------------------------------------------------------------------------------
+# Elastic-SGD (Section 2.2) on networks, and blocks of inner steps replayed from a HIP graph
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,bf16,tol", [("mlp_vec", 0, 1e-5), ("wrn_vec", 1, 2e-2)])
+def test_elastic_sgd_on_networks(gpu, name, bf16, tol):
+    torch, pb = gpu
+    # bf16 gradients agree with exact arithmetic only in direction (see test_one_step_loss_and_gradient), and with
+    # no proximal term pulling the iterate back the difference adds up step by step: fewer, smaller steps there
+    a, n, B = SMALL[name], 3, 16
+    steps, every, eta = (4, 2, 0.02) if bf16 else (8, 4, 0.05)
+    model, arch = model_pair(pb, a)
+    base = dict(n_replicas=n, L=every, eta_inner=eta, eta_outer=0.05, momentum=0.9, rho0=1.0, scoping_B=3)
+    cfg = pb.make_config(model=model, batch=B, compute_bf16=bf16, in_h=a["H"], in_w=a["W"], in_c=a["C"],
+                         n_classes=a["classes"], arch=arch, algorithm=pb.ALG_ELASTIC, **base)
+    lay = pb.parle_query_layout(cfg)
+    wi = "uniform" if a["model"] in ("mlp", "lenet") else "he_normal"
+    x0 = np.stack([synth.init_params(lay, 5 + 17 * i, wi) for i in range(n)])
+    P = pb.Parle(cfg, x0)
+    O = otrainer.ElasticNet(a, oparle.ParleConfig(**base), x0)
+    X, Y = synth.image_batches(4, steps, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    loss = torch.zeros((steps, n), dtype=torch.float32, device="cuda")
+    ref_loss = np.zeros((steps, n))
+    for k in range(steps):
+        P.parle_inner_step(dX[k], dY[k], loss[k])
+        ref_loss[k] = O.step(X[k], Y[k])
+        if (k + 1) % every == 0:
+            P.parle_outer_step()
+            O.scope()
+    got = P.state()
+    check("xa", got["y"], O.st.xa, tol)
+    check("x", got["x_ref"], O.st.x, tol)
+    if not bf16:
+        check("v", got["vy"], O.st.v, 1e-4)
+    np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=max(tol, 1e-4), atol=2e-6)
+    Xe, Ye = synth.image_batches(9, 1, 1, 11, a["H"], a["W"], a["C"], a["classes"])
+    for which in (-1, 1):
+        l, nerr, sp = P.parle_eval(which, dev(torch, Xe[0, 0]), dev(torch, Ye[0, 0]))
+        rl, rn, rsp = O.eval(which, Xe[0, 0], Ye[0, 0])
+        assert abs(l - rl) <= max(tol, 1e-4) * 2 * abs(rl) and abs(sp - rsp) <= max(tol, 1e-4) * 2 * rsp
+
+
+@pytest.mark.parametrize("name,bf16,alg", [("lenet_vec", 0, 0), ("wrn_vec", 1, 0), ("mlp_vec", 0, 1)])
+def test_inner_block_graph_replays_equal_step_by_step(gpu, name, bf16, alg):
+    """A block of inner steps through parle_inner_block with graph_block = 1: first call step by step,
+    second call records and replays, later calls replay.  Every block is compared bit for bit with a
+    second context that runs parle_inner_step; outer steps (eager kernels, scoping that changes the
+    multipliers the captured launches read) and synchronisations sit between the replays."""
+    torch, pb = gpu
+    a, n, B, L, blocks = SMALL[name], 2, 8, 4, 5
+    model, arch = model_pair(pb, a)
+    base = dict(n_replicas=n, L=L, eta_inner=0.05, eta_outer=0.1, momentum=0.9, gamma0=0.03, rho0=1.0, scoping_B=2,
+                algorithm=alg)
+    mk = lambda graph: pb.make_config(model=model, batch=B, compute_bf16=bf16, in_h=a["H"], in_w=a["W"], in_c=a["C"],
+                                      n_classes=a["classes"], arch=arch, graph_block=graph, **base)
+    lay = pb.parle_query_layout(mk(0))
+    wi = "uniform" if a["model"] in ("mlp", "lenet") else "he_normal"
+    x0 = np.tile(synth.init_params(lay, 2, wi), (n, 1))
+    Pg, Ps = pb.Parle(mk(1), x0), pb.Parle(mk(0), x0)
+    X, Y = synth.image_batches(6, L, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    loss_g = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+    loss_s = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+    for b in range(blocks):
+        Pg.parle_inner_block(dX, dY, loss_g)
+        for k in range(L):
+            Ps.parle_inner_step(dX[k], dY[k], loss_s[k])
+        sg, ss = Pg.state(), Ps.state()
+        for t in ("y", "z", "vy", "grad", "x_ref"):
+            assert np.array_equal(sg[t], ss[t]), (b, t)
+        assert np.array_equal(loss_g.cpu().numpy(), loss_s.cpu().numpy()), b
+        loss_g.zero_()
+        Pg.parle_outer_step()
+        Ps.parle_outer_step()
+        assert Pg.parle_get_state() == Ps.parle_get_state()
+        sg, ss = Pg.state(), Ps.state()
+        for t in ("x", "y", "z", "vx", "x_ref"):
+            assert np.array_equal(sg[t], ss[t]), (b, "outer", t)
+    # other arguments: step by step again, and remembered in place of the old ones
+    Pg.parle_inner_block(dX[:2].contiguous(), dY[:2].contiguous(), None)
+    for k in range(2):
+        Ps.parle_inner_step(dX[k], dY[k], None)
+    assert np.array_equal(Pg.state()["y"], Ps.state()["y"])
+    assert Pg.parle_get_state()[0] == blocks * L + 2
