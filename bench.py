@@ -72,47 +72,53 @@ def read_traffic():
 
 
 MODEL_WORKLOADS = {
-    # name: (oracle arch name, library model, n, compute_bf16, weight init)
-    "mlp_n3_fp32": ("mlp", 1, 3, 0, "uniform"),
-    "lenet_n6_fp32": ("lenet", 2, 6, 0, "uniform"),
-    "allcnn_c_n3_bf16": ("allcnn", 3, 3, 1, "he_normal"),
-    "wrn16_4_n3_bf16": ("wrn", 4, 3, 1, "he_normal"),
+    # name: (library model, arch[], n, compute_bf16, weight init)
+    "mlp_n3_fp32": (1, (128,), 3, 0, "uniform"),
+    "lenet_n6_fp32": (2, (20, 50, 5, 500), 6, 0, "uniform"),
+    "allcnn_c_n3_bf16": (3, (96, 192), 3, 1, "he_normal"),
+    "wrn16_4_n3_bf16": (4, (16, 4, 2), 3, 1, "he_normal"),
+    # the network of the paper's own timing figure (Section 4.1: 528 ms per mini-batch of 128 on one of its GPUs)
+    "wrn28_10_n3_bf16": (4, (16, 10, 4), 3, 1, "he_normal"),
 }
 MFMA_PEAK_TFLOPS = {0: 157.3, 1: 2500.0}
 
 
-def bench_model(name, torch, pb, blocks=2, warmup=5):
+def bench_model(name, torch, pb, blocks=2, graph=True):
     """Replica-images/s of the whole step (forward, loss, backward, fused update; outer step every
     L = 25) on synthetic class-conditional Gaussian images, batch 128 per replica."""
-    from oracle import nets as onets          # only for the flop count of the roofline figure
     from paper_1707_00424_amd import synth
-    arch_name, model, n, bf16, wi = MODEL_WORKLOADS[name]
+    model, arch, n, bf16, wi = MODEL_WORKLOADS[name]
     B, Lm = 128, 25
-    cfg = pb.make_config(model=model, n_replicas=n, batch=B, L=Lm, compute_bf16=bf16, eta_inner=0.01, eta_outer=0.01,
-                         gamma0=0.03, rho0=1.0, fuse_outer=1, scoping_B=390 if model == 4 else 0)
+    a = dict(H=28, W=28, C=1, classes=10) if model in (1, 2) else dict(H=32, W=32, C=3, classes=10)
+    cfg = pb.make_config(model=model, n_replicas=n, batch=B, L=Lm, compute_bf16=bf16, in_h=a["H"], in_w=a["W"],
+                         in_c=a["C"], n_classes=a["classes"], arch=arch, eta_inner=0.01, eta_outer=0.01,
+                         gamma0=0.03, rho0=1.0, fuse_outer=1, scoping_B=390 if model == 4 else 0,
+                         graph_block=1 if graph else 0)
     lay = pb.parle_query_layout(cfg)
     x0 = np.tile(synth.init_params(lay, 0, wi), (n, 1))
     P = pb.Parle(cfg, x0)
-    a = onets.arch(arch_name)
-    X, Y = synth.image_batches(0, 5, n, B, a["H"], a["W"], a["C"], a["classes"])
+    # L distinct mini-batches per replica, resident on the device; every block of L steps walks them once
+    X, Y = synth.image_batches(0, Lm, n, B, a["H"], a["W"], a["C"], a["classes"])
     dX, dY = torch.as_tensor(X).cuda(), torch.as_tensor(Y).cuda()
-    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
-    for i in range(warmup):
-        P.parle_inner_step(dX[i % 5], dY[i % 5], loss)
-    P.parle_outer_step()
+    loss = torch.zeros((Lm, n), dtype=torch.float32, device="cuda")
+    # warm-up: the first block call runs step by step, the second records the HIP graph and replays it
+    for _ in range(2):
+        P.parle_inner_block(dX, dY, loss)
+        P.parle_outer_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for blk in range(blocks):
-        for i in range(Lm):
-            P.parle_inner_step(dX[i % 5], dY[i % 5], loss)
+        P.parle_inner_block(dX, dY, loss)
         P.parle_outer_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     steps = blocks * Lm
-    flops_step = 3 * onets.flops_forward_per_image(a) * n * B     # forward + two backward contractions
+    loss = loss[-1]
+    flops_step = 3 * P.sizes.forward_flops_per_image * n * B     # forward + two backward contractions
     ips = steps * n * B / dt
     out = {"replica_images_per_sec": round(ips, 1), "ms_per_inner_step": round(dt / steps * 1e3, 4),
            "n_replicas": n, "batch_per_replica": B, "dtype": "bf16" if bf16 else "f32",
+           "launch": "HIP graph of 25 inner steps" if graph else "step by step",
            "contraction_tflops": round(flops_step * steps / dt / 1e12, 2),
            "mfma_peak_tflops": MFMA_PEAK_TFLOPS[bf16],
            "frac_of_mfma_peak": round(flops_step * steps / dt / 1e12 / MFMA_PEAK_TFLOPS[bf16], 4),
@@ -134,6 +140,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="profiling aid: also run 3 plain device copies of one [n, n_pad] fp32 tensor, "
                          "the known-size kernel the HBM counters are scaled by")
+    ap.add_argument("--no-graph", action="store_true", help="model workloads: enqueue every step instead of replaying "
+                                                            "a HIP graph of L inner steps")
     ap.add_argument("--only-models", action="store_true",
                     help="profiling aid: skip the headline workload and print only the model timings")
     args = ap.parse_args()
@@ -151,7 +159,7 @@ def main():
     torch.cuda.set_device(0)
     names = list(MODEL_WORKLOADS) if args.models == "all" else [m for m in args.models.split(",") if m and m != "none"]
     if args.only_models:
-        print(json.dumps({"models": {nm: bench_model(nm, torch, pb) for nm in names}}))
+        print(json.dumps({"models": {nm: bench_model(nm, torch, pb, graph=not args.no_graph) for nm in names}}))
         return
     n, N = N_REPLICAS, N_PARAMS
     cfg = pb.make_config(model=pb.MODEL_FLAT, n_replicas=n, n_params=N, L=L, eta_inner=0.1, eta_outer=0.1,
@@ -213,7 +221,7 @@ def main():
     del P
     torch.cuda.empty_cache()
     if names:
-        out["models"] = {nm: bench_model(nm, torch, pb) for nm in names}
+        out["models"] = {nm: bench_model(nm, torch, pb, graph=not args.no_graph) for nm in names}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))

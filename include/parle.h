@@ -124,6 +124,7 @@ typedef struct {
   int64_t workspace_bytes; /* bytes of scratch the kernels need (activations, partial sums) */
   int32_t n_segments;      /* entries parle_query_layout can return */
   int32_t image_elems;     /* H*W*C of one input image; 0 for FLAT */
+  int64_t forward_flops_per_image; /* 2*M*N*K summed over the contractions of one forward pass, per image */
 } parle_sizes;
 
 typedef enum { PARLE_SEG_WEIGHT = 0, PARLE_SEG_BIAS = 1, PARLE_SEG_BN_GAMMA = 2, PARLE_SEG_BN_BETA = 3 } parle_seg_kind;

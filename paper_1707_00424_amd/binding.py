@@ -36,7 +36,8 @@ class parle_config(C.Structure):
 class parle_sizes(C.Structure):
     _fields_ = [("n_params", C.c_int64), ("n_pad", C.c_int64), ("state_bytes", C.c_int64),
                 ("shadow_bytes", C.c_int64), ("bn_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
-                ("n_segments", C.c_int32), ("image_elems", C.c_int32)]
+                ("n_segments", C.c_int32), ("image_elems", C.c_int32),
+                ("forward_flops_per_image", C.c_int64)]
 
 
 class parle_segment(C.Structure):

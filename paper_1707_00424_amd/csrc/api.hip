@@ -124,6 +124,7 @@ parle_status compute_sizes(const parle_config *cfg, parle_sizes *out, Arch &arch
     if (!net) return PARLE_EINVAL;
     out->workspace_bytes += net_workspace_bytes(net);
     out->bn_bytes = net_bn_floats_per_replica(net) * cfg->n_replicas * (int64_t)sizeof(float);
+    out->forward_flops_per_image = net_forward_flops_per_image(net);
     if (net_out)
       *net_out = net;
     else
@@ -177,7 +178,7 @@ parle_status enqueue_inner(parle_ctx *ctx, hipStream_t st, const float *images_d
 }
 
 void drop_graph(parle_ctx *ctx) {
-  if (ctx->gexec) hipGraphExecDestroy(ctx->gexec);
+  if (ctx->gexec) (void)hipGraphExecDestroy(ctx->gexec);
   ctx->gexec = nullptr;
 }
 
@@ -330,11 +331,11 @@ parle_status parle_inner_block(parle_ctx *ctx, const float *images_dev, const in
       hipGraph_t graph = nullptr;
       e = hipStreamEndCapture(ctx->gstream, &graph);  // always closes the capture, also after a failed launch
       if (rc || e != hipSuccess) {
-        if (graph) hipGraphDestroy(graph);
+        if (graph) (void)hipGraphDestroy(graph);
         return rc ? rc : hip_fail(ctx, e, "end capture");
       }
       e = hipGraphInstantiate(&ctx->gexec, graph, nullptr, nullptr, 0);
-      hipGraphDestroy(graph);
+      (void)hipGraphDestroy(graph);
       if (e != hipSuccess) {
         ctx->gexec = nullptr;
         return hip_fail(ctx, e, "graph instantiate");
@@ -469,9 +470,9 @@ const char *parle_last_error(const parle_ctx *ctx) { return ctx ? ctx->err.c_str
 void parle_destroy(parle_ctx *ctx) {
   if (!ctx) return;
   drop_graph(ctx);
-  if (ctx->ev_in) hipEventDestroy(ctx->ev_in);
-  if (ctx->ev_out) hipEventDestroy(ctx->ev_out);
-  if (ctx->gstream) hipStreamDestroy(ctx->gstream);
+  if (ctx->ev_in) (void)hipEventDestroy(ctx->ev_in);
+  if (ctx->ev_out) (void)hipEventDestroy(ctx->ev_out);
+  if (ctx->gstream) (void)hipStreamDestroy(ctx->gstream);
   net_destroy(ctx->net);
   delete ctx;
 }

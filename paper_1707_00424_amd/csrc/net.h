@@ -12,6 +12,8 @@ Net *net_create(const parle_config &cfg, const Arch &a, const std::vector<Segmen
 void net_destroy(Net *net);
 int64_t net_workspace_bytes(const Net *net);
 int64_t net_bn_floats_per_replica(const Net *net);
+// 2*M*N*K over the contractions of one forward pass, per image
+int64_t net_forward_flops_per_image(const Net *net);
 
 // Enqueues forward + loss + backward for all n replicas.  Parameters are read from `params`
 // ([n, n_pad] fp32) and, in bf16 mode, from `params_bf16`; gradients go to `grad` ([n, n_pad] fp32,

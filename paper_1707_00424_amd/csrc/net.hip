@@ -437,6 +437,12 @@ Net *net_create(const parle_config &cfg, const Arch &a, const std::vector<Segmen
 void net_destroy(Net *net) { delete net; }
 int64_t net_workspace_bytes(const Net *net) { return net->ws_bytes; }
 int64_t net_bn_floats_per_replica(const Net *net) { return net->bn_floats; }
+int64_t net_forward_flops_per_image(const Net *net) {
+  int64_t f = 0;
+  for (const Op &op : net->ops)
+    if (op.type == OP_CONV) f += 2LL * op.Ho * op.Wo * op.Cout * op.R * op.R * op.Cin;
+  return f;
+}
 
 hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const void *params_bf16, float *grad,
                           float *bn_stats, void *workspace, const float *images, const int32_t *labels,

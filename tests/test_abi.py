@@ -58,6 +58,16 @@ def test_layout_matches_oracle_default_sizes(model):
         off += s["size"]
     sizes = pb.parle_query_sizes(cfg)
     assert sizes.n_params == off == nets.n_params(nets.arch(ORACLE_ARCH[model][0]))
+    assert sizes.forward_flops_per_image == nets.flops_forward_per_image(nets.arch(ORACLE_ARCH[model][0]))
+
+
+def test_wrn_28_10_has_the_size_the_paper_quotes():
+    """WRN-28-10 (Section 4.3) as arch = (16, 10, 4): about 36.5 million weights."""
+    cfg = pb.make_config(model=pb.MODEL_WRN, n_replicas=3, batch=128, compute_bf16=1, arch=(16, 10, 4))
+    sizes = pb.parle_query_sizes(cfg)
+    a = nets.arch("wrn", widen=10, nb=4)
+    assert sizes.n_params == nets.n_params(a) and abs(sizes.n_params / 1e6 - 36.5) < 0.1
+    assert sizes.forward_flops_per_image == nets.flops_forward_per_image(a)
 
 
 def test_layout_matches_oracle_small_sizes():
