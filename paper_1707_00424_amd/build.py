@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libparle.so")
 
-SOURCES = ["update.hip", "api.hip", "arch.cpp", "net.hip", "igemm.hip", "igemm_fast.hip", "igemm_halo.hip", "nn.hip", "conv_api.hip"]
+SOURCES = ["update.hip", "api.hip", "arch.cpp", "net.hip", "igemm.hip", "igemm_fast.hip", "igemm_halo.hip", "igemm_wgrad9.hip", "nn.hip", "conv_api.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-pass-failed", "-Wno-bitwise-instead-of-logical",
@@ -20,7 +20,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("PARLE_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [HIPCC, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)

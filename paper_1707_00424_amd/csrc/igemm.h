@@ -105,5 +105,9 @@ hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, con
 bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
 void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
 hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
+// Stride-1 'same' 3x3 backward-weight with the patch staged in LDS and nine taps per wavefront (igemm_wgrad9.hip).
+bool wgrad9_applicable(int dtype, const ConvGeom &g);
+int wgrad9_plan(int replicas, const ConvGeom &g, int *chunk_out);
+hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Rows of M per split so that the launch has enough workgroups; returns the split count.
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out);

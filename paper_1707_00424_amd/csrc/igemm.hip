@@ -387,6 +387,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || io.splits < 1 || (long long)replicas * io.splits > 65535 ||
       io.chunk < 32 || (io.chunk & 31))
     return hipErrorInvalidValue;
+  if (wgrad9_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad9(st, replicas, g, io);
   if (wgrad_fast_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad_fast(st, replicas, g, io);
   if (dtype == 0) return run_wgrad<float, 2, 2, 1, 1>(st, replicas, g, io);
   switch (bf16_ntile(g.N)) {
@@ -398,6 +399,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 }
 
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
+  if (wgrad9_applicable(dtype, g)) return wgrad9_plan(replicas, g, chunk_out);
   int bm, bn;
   if (wgrad_fast_applicable(dtype, g)) {
     wgrad_fast_tile(g, &bm, &bn);

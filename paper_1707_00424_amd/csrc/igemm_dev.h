@@ -200,25 +200,64 @@ __device__ __forceinline__ void store_tile_t(const ConvGeom &g, const GemmIO &io
 // the strip in row-major order, four consecutive channels per lane and consecutive lanes on
 // consecutive channels -- reads of the residual / mask / old output and the final store all hit
 // contiguous runs of a row (the whole row when the tile spans it) instead of 16 bytes per row.
-// Requires N % 4 == 0 and ldc % 4 == 0.  `stage` is this wavefront's strip of kStageFloats<TN>
-// floats; the caller has made sure (barrier) that no wavefront still reads LDS that it aliases.
-// Every wavefront of the workgroup must call this (it contains workgroup barriers).
+//
+// A wavefront issues one vector instruction per four cycles, and with one or two wavefronts per
+// SIMD the epilogue is bound by its instruction count, so the walk is kept lean:
+//   * lane l handles vectors c = 64*it + l of the strip; (row, channel) of c repeat with period
+//     PER = CPR / gcd(64, CPR) in `it`, so PER base offsets are computed once and every vector costs
+//     one add (LDS addresses are compile-time offsets from the bases);
+//   * global accesses are raw buffer loads / stores: a lane outside the tile gets an offset beyond
+//     the buffer and the hardware drops it -- no branches, no 64-bit address arithmetic;
+//   * a batch issues all its LDS reads, then all its global reads, then arithmetic and stores, and
+//     pays one LDS and one memory latency instead of one per vector.
+// Requires N % 4 == 0, ldc % 4 == 0 and M * ldc * 4 < 2^31.  `stage` is this wavefront's strip of
+// kStageFloats<TN> floats; the caller has made sure (barrier) that no wavefront still reads LDS
+// that it aliases.  A strip is private to its wavefront, whose LDS accesses execute in order: no
+// workgroup barrier is needed here.
 template <int TN>
 constexpr int kStageFloats = 32 * (TN * 32 + 4);
 
+constexpr uint32_t kOobOffset = 0x80000000u;  // beyond any per-replica tensor (each is < 2 GiB)
+
 template <typename T, int TM, int TN, bool OUT_F32>
 __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
-                                               f16v (&acc)[TM][TN], float *stage) {
-  typedef typename Vec4<T>::type TV;
+                                               f16v (&acc)[TM][TN], float *stage, unsigned long long *kpe = nullptr) {
+  typedef unsigned int u2v __attribute__((ext_vector_type(2)));
   constexpr int CW = TN * 32, LD = CW + 4, CPR = CW / 4;
+  constexpr int NIT = CPR / 2;                                  // vectors per lane and 32-row strip
+  constexpr int PER = CPR % 3 == 0 ? 3 : 1;                     // CPR = 8, 16, 32 divide 64; 24 has period 3
+  constexpr int RPP = 64 * PER / CPR;                           // rows per period
+  constexpr int BATCH = NIT <= 8 ? NIT : NIT / 2;
+  static_assert(NIT % PER == 0 && BATCH % PER == 0 && NIT % BATCH == 0, "walk must split into whole periods");
+  constexpr int ES = (int)sizeof(T), OS = OUT_F32 ? 4 : ES;
   const int row_l = lane & 31, h = lane >> 5;
-  const float *bias = io.bias ? io.bias + rep * io.bias_rs : nullptr;
-  const T *resid = io.resid ? (const T *)io.resid + rep * io.resid_rs : nullptr;
-  const T *mask = io.mask ? (const T *)io.mask + rep * io.mask_rs : nullptr;
-  const bool bias_vec = (reinterpret_cast<uintptr_t>(bias) & 15) == 0;  // segment offsets need not be 16-byte aligned
+  const uint32_t tensor_elems = (uint32_t)g.M * (uint32_t)io.ldc;
+  const __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((char *)io.out + (long long)rep * io.out_rs * OS), 0, (int)(tensor_elems * OS), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((const T *)io.resid + rep * io.resid_rs), 0, io.resid ? (int)(tensor_elems * ES) : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t m_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)((const T *)io.mask + rep * io.mask_rs), 0, io.mask ? (int)(tensor_elems * ES) : 0, 0x00020000);
+  // per lane and phase of the period: strip address, element offset inside a 32-row strip, validity
+  int lds_b[PER], row_b[PER], ch_b[PER];
+  f4 bias_b[PER];
+#pragma unroll
+  for (int r = 0; r < PER; ++r) {
+    const int c = 64 * r + lane;
+    row_b[r] = c / CPR;
+    ch_b[r] = (c - row_b[r] * CPR) * 4;
+    lds_b[r] = row_b[r] * LD + ch_b[r];
+    bias_b[r] = f4{0.f, 0.f, 0.f, 0.f};
+    const int n = ncol0 + ch_b[r];
+    if (io.bias && n < g.N) {
+      const float *bp = io.bias + rep * io.bias_rs + n;   // segment offsets need not be 16-byte aligned
+      bias_b[r] = f4{bp[0], bp[1], bp[2], bp[3]};
+    }
+  }
+  if (kpe) kpe[0] = clock64();
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
-    if (tm) __syncthreads();  // the strip has been read out
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the strip has been read out
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
@@ -226,42 +265,79 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
         const f4 val = {acc[tm][tn][4 * vg], acc[tm][tn][4 * vg + 1], acc[tm][tn][4 * vg + 2], acc[tm][tn][4 * vg + 3]};
         *(f4 *)&stage[row_l * LD + tn * 32 + 8 * vg + 4 * h] = val;
       }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (kpe && tm == 0) kpe[1] = clock64();
+    const int mbase = mrow0 + tm * 32;
 #pragma unroll
-    for (int it = 0; it < CPR / 2; ++it) {
-      const int c = it * 64 + lane;
-      const int row = c / CPR, ch = (c - row * CPR) * 4;
-      const int m = mrow0 + tm * 32 + row, n = ncol0 + ch;
-      if (m >= g.M || n >= g.N) continue;
-      const long long o = (long long)row_pixel(g, (uint32_t)m) * io.ldc + n;
-      f4 val = *(const f4 *)&stage[row * LD + ch];
-      if (bias) {
-        if (bias_vec) {
-          val += *(const f4 *)(bias + n);
-        } else {
-          val.x += bias[n], val.y += bias[n + 1], val.z += bias[n + 2], val.w += bias[n + 3];
+    for (int b0 = 0; b0 < NIT; b0 += BATCH) {
+      f4 val[BATCH], of[BATCH];
+      uint32_t off[BATCH];  // element offset, or kOobOffset
+      u2v rv[BATCH], mv[BATCH], ov[BATCH];
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        const int it = b0 + i, r = it % PER, j = it / PER;
+        const int row = row_b[r] + j * RPP, m = mbase + row;
+        const bool ok = m < g.M && ncol0 + ch_b[r] < g.N;
+        const uint32_t pix = g.plq == 0 ? (uint32_t)m : row_pixel(g, (uint32_t)(ok ? m : 0));
+        off[i] = ok ? pix * (uint32_t)io.ldc + (uint32_t)(ncol0 + ch_b[r]) : kOobOffset;
+        val[i] = *(const f4 *)&stage[lds_b[r] + j * RPP * LD];
+      }
+      if (kpe && tm == 0 && b0 == 0) kpe[2] = clock64() + 0 * (unsigned long long)val[BATCH - 1].x;
+      if (io.resid) {
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          if (ES == 4) {
+            const u4 t = __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 4, 0, 0);
+            val[i] += __builtin_bit_cast(f4, t);
+          } else {
+            rv[i] = __builtin_amdgcn_raw_buffer_load_b64(r_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
+          }
         }
       }
-      if (resid) val += Vec4<T>::to_f32(*(const TV *)(resid + o));
-      if (io.relu) {
-        val.x = val.x > 0.f ? val.x : 0.f, val.y = val.y > 0.f ? val.y : 0.f;
-        val.z = val.z > 0.f ? val.z : 0.f, val.w = val.w > 0.f ? val.w : 0.f;
+      u4 mv4[ES == 4 ? BATCH : 1];
+      if (io.mask) {
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          if (ES == 4)
+            mv4[i] = __builtin_amdgcn_raw_buffer_load_b128(m_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 4, 0, 0);
+          else
+            mv[i] = __builtin_amdgcn_raw_buffer_load_b64(m_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
+        }
       }
-      if (mask) {
-        const f4 mk = Vec4<T>::to_f32(*(const TV *)(mask + o));
-        val.x = mk.x > 0.f ? val.x : 0.f, val.y = mk.y > 0.f ? val.y : 0.f;
-        val.z = mk.z > 0.f ? val.z : 0.f, val.w = mk.w > 0.f ? val.w : 0.f;
+      if (io.accumulate) {
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          if (OS == 4)
+            of[i] = __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(o_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 4, 0, 0));
+          else
+            ov[i] = __builtin_amdgcn_raw_buffer_load_b64(o_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
+        }
       }
-      if (OUT_F32) {
-        float *out = (float *)io.out + rep * io.out_rs;
-        if (io.accumulate) val += *(const f4 *)(out + o);
-        *(f4 *)(out + o) = val;
-      } else {
-        T *out = (T *)io.out + rep * io.out_rs;
-        if (io.accumulate) val += Vec4<T>::to_f32(*(const TV *)(out + o));
-        *(TV *)(out + o) = Vec4<T>::from_f32(val);
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        f4 v = val[i] + bias_b[(b0 + i) % PER];
+        if (ES == 2 && io.resid) v += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, rv[i]));
+        if (io.relu) {
+          v.x = v.x > 0.f ? v.x : 0.f, v.y = v.y > 0.f ? v.y : 0.f;
+          v.z = v.z > 0.f ? v.z : 0.f, v.w = v.w > 0.f ? v.w : 0.f;
+        }
+        if (io.mask) {
+          const f4 mk = ES == 4 ? __builtin_bit_cast(f4, mv4[ES == 4 ? i : 0]) : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, mv[i]));
+          v.x = mk.x > 0.f ? v.x : 0.f, v.y = mk.y > 0.f ? v.y : 0.f;
+          v.z = mk.z > 0.f ? v.z : 0.f, v.w = mk.w > 0.f ? v.w : 0.f;
+        }
+        if (OS == 4) {
+          if (io.accumulate) v += of[i];
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), o_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 4, 0, 0);
+        } else {
+          if (io.accumulate) v += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
+          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(v)), o_rsrc,
+                                                off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
+        }
       }
+      if (kpe && tm == 0 && b0 == 0) kpe[3] = clock64();
     }
+    if (kpe && tm == 0) kpe[4] = clock64();
   }
 }
 

@@ -19,6 +19,12 @@ namespace {
 using namespace igemm_dev;
 
 constexpr uint32_t kOob = 0x80000000u;
+#ifdef PARLE_KPROF
+__device__ unsigned long long g_prof[8 * 4096];
+#define KPROF_STAMP(i) if (threadIdx.x == 0) kp[i] = clock64()
+#else
+#define KPROF_STAMP(i)
+#endif
 constexpr int kHaloSlots = 400;  // LDS patch capacity in pixels (32 KB at 32 channels + padding)
 
 struct HaloGeom {
@@ -27,6 +33,7 @@ struct HaloGeom {
   int HR, HC;      // patch rows / columns per image = TH + R - 1, Q + S - 1
   int slots;       // nimg * HR * HC
   int omin_h, omin_w;  // smallest tap offset (input row = output row + offset)
+  FastDiv dImg, dHC, dRows;  // by HR*HC, HC and TH*Q (no integer division on the device)
 };
 
 template <int TN>
@@ -36,13 +43,18 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
   constexpr int TM = 2, BM = 256, BN = TN * 32;  // four wavefronts stacked along the pixel axis
   constexpr int B_IT = (BN + 63) / 64;
   constexpr int H_IT = (kHaloSlots * 4 + kThreads - 1) / kThreads;
-  // patch + double-buffered weight tiles; the epilogue reuses the same LDS as its staging strips
-  constexpr int kPipeBytes = (kHaloSlots + 2 * BN) * LK * (int)sizeof(T);
+  // patch + a ring of three weight tiles; the epilogue reuses the same LDS as its staging strips
+  constexpr int kPipeBytes = (kHaloSlots + 3 * BN) * LK * (int)sizeof(T);
   constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
   __shared__ __attribute__((aligned(16))) char smem[kPipeBytes > kStageBytes ? kPipeBytes : kStageBytes];
   T *Hs = reinterpret_cast<T *>(smem);
-  T(*Bs)[BN * LK] = reinterpret_cast<T(*)[BN * LK]>(smem + kHaloSlots * LK * sizeof(T));
+  T *Bs = reinterpret_cast<T *>(smem + kHaloSlots * LK * sizeof(T));  // tile i of the ring at Bs + i * BN * LK
 
+#ifdef PARLE_KPROF
+  unsigned long long kp[5], kpe[5] = {0, 0, 0, 0, 0};
+  const unsigned long long wall0 = wall_clock64();
+#endif
+  KPROF_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
@@ -55,15 +67,15 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
       (void *)((const T *)io.w + rep * io.w_rs), 0, (int)((long long)g.N * g.K * sizeof(T)), 0x00020000);
 
   // patch loader: vector v = it*256 + tid covers patch pixel v/4, channels 8*(v%4) .. +7 of the chunk
-  const int b0 = m0 / PQ, p0 = (m0 % PQ) / g.Q;
+  const int b0 = (int)fdiv((uint32_t)m0, g.dPQ), p0 = (int)fdiv((uint32_t)(m0 - b0 * PQ), g.dQ);
   uint32_t h_off[H_IT];
 #pragma unroll
   for (int it = 0; it < H_IT; ++it) {
     const int v = it * kThreads + tid, slot = v >> 2;
     uint32_t off = kOob;
     if (slot < hg.slots) {
-      const int img = slot / (hg.HR * hg.HC), rem = slot % (hg.HR * hg.HC);
-      const int hh = rem / hg.HC, ww = rem % hg.HC;
+      const int img = (int)fdiv((uint32_t)slot, hg.dImg), rem = slot - img * hg.HR * hg.HC;
+      const int hh = (int)fdiv((uint32_t)rem, hg.dHC), ww = rem - hh * hg.HC;
       const int b = b0 + img, ih = p0 + hh + hg.omin_h, iw = ww + hg.omin_w;
       if ((b * PQ < g.M) && ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win)
         off = (uint32_t)((((b * g.Hin + ih) * g.Win + iw) * g.Cc + (v & 3) * VW) * (int)sizeof(T));
@@ -81,8 +93,8 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
     const int ml = wave * (TM * 32) + tm * 32 + (lane & 31);
-    const int img = ml / (hg.TH * g.Q), rem = ml % (hg.TH * g.Q);
-    const int ph = rem / g.Q, pw = rem % g.Q;
+    const int img = (int)fdiv((uint32_t)ml, hg.dRows), rem = ml - img * hg.TH * g.Q;
+    const int ph = (int)fdiv((uint32_t)rem, g.dQ), pw = rem - ph * g.Q;
     a_lds[tm] = (((img * hg.HR + ph) * hg.HC + pw) * LK + (lane >> 5) * VW);
   }
   const int b_lds = (lane & 31) * LK + (lane >> 5) * VW;
@@ -121,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
       const int row = i * 64 + lrow;
-      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf][row * LK + lkv * VW] = breg[i];
+      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf * (BN * LK) + row * LK + lkv * VW] = breg[i];
     }
   };
 
@@ -133,70 +145,138 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
-  // tap shift inside the patch: rows advance with r for a forward conv (sr = +1), against it for
-  // backward-data (sr = -1); same for columns
-  int tap_r = 0, tap_s = 0, chunk = 0;
-  auto mma_step = [&](int buf) {
-    const int dh = g.sr > 0 ? tap_r : g.R - 1 - tap_r, dw = g.sr > 0 ? tap_s : g.S - 1 - tap_s;
-    const int shift = (dh * hg.HC + dw) * LK;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      u4 af[TM], bf[TN];
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&Hs[a_lds[tm] + shift + sub * 2 * VW];
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&Bs[buf][tn * 32 * LK + b_lds + sub * 2 * VW];
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) mma<T>(bf[tn], af[tm], acc[tm][tn]);
-    }
+  // Contraction step t = (channel chunk, tap).  A step is two MFMA sub-steps of 16 channels; the
+  // fragments of a sub-step are fetched from LDS one sub-step ahead of the MFMAs that use them
+  // (sub 1 of step t during sub 0 of step t, sub 0 of step t+1 during sub 1 of step t), so the
+  // matrix units do not wait for LDS latency.  The weight tiles form a ring of three in LDS: while
+  // step t multiplies, tile t+1 is being read for the next sub-step and tile t+2 is written from
+  // registers; one workgroup barrier per step.  Global memory (L2) answers in more cycles than a
+  // step lasts, so four weight tiles are in flight in registers: the tile stored to LDS in step t
+  // was requested in step t-4.  The patch is single-buffered: at the last tap of a chunk two
+  // extra barriers fence its replacement.
+  // Tap shift inside the patch: rows advance with r for a forward conv (sr = +1), against it for
+  // backward-data (sr = -1); same for columns.
+  auto shift_of = [&](int r, int c) {
+    const int dh = g.sr > 0 ? r : g.R - 1 - r, dw = g.sr > 0 ? c : g.S - 1 - c;
+    return (dh * hg.HC + dw) * LK;
   };
-  // after the MFMAs of a step: move to the next tap; at the end of a chunk swap in the next patch
-  auto next_tap = [&]() {
-    if (++tap_s == g.S) {
-      tap_s = 0;
-      if (++tap_r == g.R) {
-        tap_r = 0;
-        ++chunk;
-        __syncthreads();   // every wavefront is done reading the patch
-        store_halo();
-        load_halo(chunk + 1);
-      }
-    }
+  auto read_sub = [&](int sub, int buf, int shift, u4 (&af)[TM], u4 (&bf)[TN]) {
+    const T *bt = Bs + buf * (BN * LK) + b_lds + sub * 2 * VW;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) af[tm] = *(const u4 *)&Hs[a_lds[tm] + shift + sub * 2 * VW];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) bf[tn] = *(const u4 *)&bt[tn * 32 * LK];
+  };
+  auto mma_sub = [&](const u4 (&af)[TM], const u4 (&bf)[TN]) {
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) mma<T>(bf[tn], af[tm], acc[tm][tn]);
   };
 
-  u4 b0r[B_IT], b1r[B_IT];
+  u4 r0[B_IT], r1[B_IT], r2[B_IT], r3[B_IT];  // weight tiles in flight from global memory
+  u4 fa_a[TM], fa_b[TN];          // fragments of sub-step 0
+  u4 fb_a[TM], fb_b[TN];          // fragments of sub-step 1
+  int tap_r = 0, tap_s = 0, chunk = 0;  // tap of the step after the current one, chunk in the patch
+  int shift_cur = shift_of(0, 0);
+  int ring = 0;                   // ring slot of the current step's weight tile
   load_halo(0);
-  load_b(b0r);
-  load_b(b1r);
+  load_b(r0);
+  load_b(r1);
   store_halo();
   load_halo(1);
-  store_b(0, b0r);
+  KPROF_STAMP(1);
+  store_b(0, r0);
+  store_b(1, r1);
+  load_b(r2);
+  load_b(r3);
+  load_b(r0);
+  load_b(r1);
   __syncthreads();
+  KPROF_STAMP(2);
+  read_sub(0, 0, shift_cur, fa_a, fa_b);
+  // A wavefront issues in order: LDS reads placed in a burst before the MFMAs leave the matrix unit
+  // idle while they issue.  Ask the scheduler to alternate them: one fragment read after each MFMA.
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN, 0);
+  };
+  // one step; `ra` holds tile t+2 (stored to the ring now) and then receives tile t+6
+  auto step = [&](int t, u4 (&ra)[B_IT]) {
+    const int ring1 = ring == 2 ? 0 : ring + 1, ring2 = ring1 == 2 ? 0 : ring1 + 1;
+    read_sub(1, ring, shift_cur, fb_a, fb_b);
+    if (++tap_s == g.S) {
+      tap_s = 0;
+      if (++tap_r == g.R) tap_r = 0;
+    }
+    const bool more = t + 1 < KT;
+    const bool swap_patch = more && tap_r == 0 && tap_s == 0;
+    shift_cur = shift_of(tap_r, tap_s);
+    mma_sub(fa_a, fa_b);
+    interleave();
+    if (swap_patch) {
+      __syncthreads();  // every wavefront has its fragments of the old patch
+      ++chunk;
+      store_halo();
+      load_halo(chunk + 1);
+      __syncthreads();
+    }
+    read_sub(0, ring1, shift_cur, fa_a, fa_b);  // past the last step: a harmless read of live LDS
+    mma_sub(fb_a, fb_b);
+    interleave();
+    store_b(ring2, ra);
+    load_b(ra);
+    ring = ring1;
+    __syncthreads();
+  };
   int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    load_b(b0r);
-    mma_step(0);
-    store_b(1, b1r);
-    next_tap();
-    __syncthreads();
-    load_b(b1r);
-    mma_step(1);
-    store_b(0, b0r);
-    next_tap();
-    __syncthreads();
+  for (; kt + 3 < KT; kt += 4) {
+    step(kt, r2);
+    step(kt + 1, r3);
+    step(kt + 2, r0);
+    step(kt + 3, r1);
   }
-  if (kt < KT) mma_step(0);
-  __syncthreads();  // patch and weight tiles are dead: their LDS becomes the staging strips
+  if (kt < KT) step(kt, r2);
+  if (kt + 1 < KT) step(kt + 1, r3);
+  if (kt + 2 < KT) step(kt + 2, r0);
+  // the barrier that ends the last step: patch and weight tiles are dead, their LDS becomes the staging strips
+  KPROF_STAMP(3);
+#ifdef PARLE_KPROF
+  store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
+                                   reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>, threadIdx.x == 0 ? kpe : nullptr);
+#else
   store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
                                    reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
+#endif
+  KPROF_STAMP(4);
+#ifdef PARLE_KPROF
+  if (threadIdx.x == 0) {
+    const int id = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (id < 4096) {
+      for (int i = 0; i < 5; ++i) g_prof[id * 8 + i] = kp[i];
+      g_prof[id * 8 + 6] = wall_clock64() - wall0;
+      g_prof[id * 8 + 7] = ((kpe[0] - kp[3]) & 0xfff) | (((kpe[1] - kpe[0]) & 0xfff) << 12) | (((kpe[2] - kpe[1]) & 0xfff) << 24) |
+                           (((kpe[3] - kpe[2]) & 0xfff) << 36) | (((kpe[4] - kpe[3]) & 0xfff) << 48);
+      g_prof[id * 8 + 5] = (unsigned long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) |
+                           ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)) << 32);  // HW_ID, XCC_ID
+    }
+  }
+#endif
 }
 
 template <int TN>
 hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, const HaloGeom &hg) {
   dim3 grid((g.M + 255) / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
+#ifdef PARLE_KPROF
+  static const int dyn = getenv("PARLE_DBG_DYNLDS") ? atoi(getenv("PARLE_DBG_DYNLDS")) : 0;
+  hipLaunchKernelGGL((k_conv_halo<TN>), grid, dim3(kThreads), dyn, st, g, io, hg);
+#else
   hipLaunchKernelGGL((k_conv_halo<TN>), grid, dim3(kThreads), 0, st, g, io, hg);
+#endif
   return hipGetLastError();
 }
 
@@ -214,6 +294,7 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
   }
   hg.HR = hg.TH + g.R - 1, hg.HC = g.Q + g.S - 1;
   hg.slots = hg.nimg * hg.HR * hg.HC;
+  hg.dImg = make_fastdiv(hg.HR * hg.HC), hg.dHC = make_fastdiv(hg.HC), hg.dRows = make_fastdiv(hg.TH * g.Q);
   const int o_first = g.off, o_last = g.off + (g.R - 1) * g.sr;
   hg.omin_h = o_first < o_last ? o_first : o_last;
   const int w_first = g.off, w_last = g.off + (g.S - 1) * g.sr;
@@ -222,6 +303,12 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
 }
 
 }  // namespace
+
+#ifdef PARLE_KPROF
+extern "C" int parle_dbg_read_prof(void *out, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), bytes, 0, hipMemcpyDeviceToHost);
+}
+#endif
 
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32) {
   HaloGeom hg;

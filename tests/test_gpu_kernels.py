@@ -74,6 +74,10 @@ CASES = [
     (2, 4, 16, 16, 32, 64, 3, 2, 1),    # stride 2, power-of-two image: backward-data rows grouped by parity class
     (1, 3, 8, 8, 32, 32, 3, 2, 1),      # same, tiles spanning several classes and images
     (2, 3, 16, 8, 16, 32, 1, 2, 0),     # strided 1x1: three of four parity classes reach no tap
+    (1, 2, 32, 32, 32, 128, 3, 1, 1),   # backward-weight with nine taps per wavefront: two column blocks, 4 dy tiles
+    (1, 3, 16, 16, 64, 160, 3, 1, 1),   # same, 5 dy tiles per workgroup
+    (2, 3, 8, 8, 32, 128, 3, 1, 1),     # same, two 8 x 8 images per block, odd batch
+    (1, 2, 24, 16, 32, 192, 3, 1, 1),   # same, two groups of 3 dy tiles, three row blocks per image
 ]
 
 
