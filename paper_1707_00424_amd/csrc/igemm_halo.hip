@@ -37,7 +37,7 @@ struct HaloGeom {
 };
 
 template <int TN>
-__global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const GemmIO io, const HaloGeom hg) {
+__device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &io, const HaloGeom &hg) {
   typedef bf16_t T;
   constexpr int VW = 8, BK = 32, LK = BK + VW;
   constexpr int TM = 2, BM = 256, BN = TN * 32;  // four wavefronts stacked along the pixel axis
@@ -151,8 +151,8 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
   // matrix units do not wait for LDS latency.  The weight tiles form a ring of three in LDS: while
   // step t multiplies, tile t+1 is being read for the next sub-step and tile t+2 is written from
   // registers; one workgroup barrier per step.  Global memory (L2) answers in more cycles than a
-  // step lasts, so four weight tiles are in flight in registers: the tile stored to LDS in step t
-  // was requested in step t-4.  The patch is single-buffered: at the last tap of a chunk two
+  // step lasts, so D weight tiles are in flight in registers: the tile stored to LDS in step t
+  // was requested in step t-D.  The patch is single-buffered: at the last tap of a chunk two
   // extra barriers fence its replacement.
   // Tap shift inside the patch: rows advance with r for a forward conv (sr = +1), against it for
   // backward-data (sr = -1); same for columns.
@@ -174,24 +174,23 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
       for (int tn = 0; tn < TN; ++tn) mma<T>(bf[tn], af[tm], acc[tm][tn]);
   };
 
-  u4 r0[B_IT], r1[B_IT], r2[B_IT], r3[B_IT];  // weight tiles in flight from global memory
+  constexpr int D = TN >= 4 ? 2 : 4;  // weight tiles in flight from global memory (registers permitting)
+  u4 rq[D][B_IT];
   u4 fa_a[TM], fa_b[TN];          // fragments of sub-step 0
   u4 fb_a[TM], fb_b[TN];          // fragments of sub-step 1
   int tap_r = 0, tap_s = 0, chunk = 0;  // tap of the step after the current one, chunk in the patch
   int shift_cur = shift_of(0, 0);
   int ring = 0;                   // ring slot of the current step's weight tile
   load_halo(0);
-  load_b(r0);
-  load_b(r1);
+  load_b(rq[0]);
+  load_b(rq[1]);
   store_halo();
   load_halo(1);
   KPROF_STAMP(1);
-  store_b(0, r0);
-  store_b(1, r1);
-  load_b(r2);
-  load_b(r3);
-  load_b(r0);
-  load_b(r1);
+  store_b(0, rq[0]);
+  store_b(1, rq[1]);
+#pragma unroll
+  for (int i = 0; i < D; ++i) load_b(rq[i]);  // tile 2 + i; step t stores set t % D and refills it with tile t + 2 + D
   __syncthreads();
   KPROF_STAMP(2);
   read_sub(0, 0, shift_cur, fa_a, fa_b);
@@ -205,7 +204,7 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
     }
     __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - TM - TN, 0);
   };
-  // one step; `ra` holds tile t+2 (stored to the ring now) and then receives tile t+6
+  // one step; `ra` holds tile t+2 (stored to the ring now) and then receives tile t+2+D
   auto step = [&](int t, u4 (&ra)[B_IT]) {
     const int ring1 = ring == 2 ? 0 : ring + 1, ring2 = ring1 == 2 ? 0 : ring1 + 1;
     read_sub(1, ring, shift_cur, fb_a, fb_b);
@@ -234,15 +233,13 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
     __syncthreads();
   };
   int kt = 0;
-  for (; kt + 3 < KT; kt += 4) {
-    step(kt, r2);
-    step(kt + 1, r3);
-    step(kt + 2, r0);
-    step(kt + 3, r1);
+  for (; kt + D - 1 < KT; kt += D) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) step(kt + i, rq[i]);
   }
-  if (kt < KT) step(kt, r2);
-  if (kt + 1 < KT) step(kt + 1, r3);
-  if (kt + 2 < KT) step(kt + 2, r0);
+#pragma unroll
+  for (int i = 0; i < D - 1; ++i)
+    if (kt + i < KT) step(kt + i, rq[i]);
   // the barrier that ends the last step: patch and weight tiles are dead, their LDS becomes the staging strips
   KPROF_STAMP(3);
 #ifdef PARLE_KPROF
@@ -266,6 +263,18 @@ __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const 
     }
   }
 #endif
+}
+
+template <int TN>
+__global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const GemmIO io, const HaloGeom hg) {
+  conv_halo_body<TN>(g, io, hg);
+}
+// 64 output channels: few enough registers for three workgroups per compute unit, which hides more of
+// the prologue and epilogue of one workgroup behind the matrix work of the others
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void k_conv_halo_n64(const ConvGeom g,
+                                                                                                   const GemmIO io,
+                                                                                                   const HaloGeom hg) {
+  conv_halo_body<2>(g, io, hg);
 }
 
 template <int TN>
@@ -321,7 +330,11 @@ hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, con
   HaloGeom hg;
   if (!make_halo_geom(g, hg)) return hipErrorInvalidValue;
   const int n = g.N;
-  if (n <= 64) return run_halo<2>(st, replicas, g, io, hg);
+  if (n <= 64) {
+    dim3 grid((g.M + 255) / 256, (g.N + 63) / 64, replicas);
+    hipLaunchKernelGGL(k_conv_halo_n64, grid, dim3(kThreads), 0, st, g, io, hg);
+    return hipGetLastError();
+  }
   if (n <= 96 || n % 96 == 0) return run_halo<3>(st, replicas, g, io, hg);
   return run_halo<4>(st, replicas, g, io, hg);
 }
