@@ -105,6 +105,11 @@ hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, con
 bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
 void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
 hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
+// Layers whose whole contraction fits one tile, K = R*S*Cin <= 32 (igemm_smallk.hip).
+bool conv_smallk_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
+hipError_t launch_conv_smallk(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+bool wgrad_smallk_applicable(int dtype, const ConvGeom &g);
+hipError_t launch_wgrad_smallk(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Stride-1 'same' 3x3 backward-weight with the patch staged in LDS and nine taps per wavefront (igemm_wgrad9.hip).
 bool wgrad9_applicable(int dtype, const ConvGeom &g);
 int wgrad9_plan(int replicas, const ConvGeom &g, int *chunk_out);

@@ -372,6 +372,7 @@ int bf16_ntile(int n) {
 
 hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
+  if (conv_smallk_applicable(dtype, g, io)) return launch_conv_smallk(st, dtype, out_f32, replicas, g, io);
   if (conv_halo_applicable(dtype, g, io, out_f32)) return launch_conv_halo(st, replicas, g, io);
   if (igemm_fast_applicable(dtype, g, io)) return launch_igemm_fast(st, dtype, out_f32, replicas, g, io);
   if (dtype == 0) return run_igemm<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
@@ -387,6 +388,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || io.splits < 1 || (long long)replicas * io.splits > 65535 ||
       io.chunk < 32 || (io.chunk & 31))
     return hipErrorInvalidValue;
+  if (wgrad_smallk_applicable(dtype, g) && aligned_to(io.dy, 16)) return launch_wgrad_smallk(st, replicas, g, io);
   if (wgrad9_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad9(st, replicas, g, io);
   if (wgrad_fast_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad_fast(st, replicas, g, io);
   if (dtype == 0) return run_wgrad<float, 2, 2, 1, 1>(st, replicas, g, io);
@@ -401,7 +403,9 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   if (wgrad9_applicable(dtype, g)) return wgrad9_plan(replicas, g, chunk_out);
   int bm, bn;
-  if (wgrad_fast_applicable(dtype, g)) {
+  if (wgrad_smallk_applicable(dtype, g)) {
+    bm = 128, bn = 32;
+  } else if (wgrad_fast_applicable(dtype, g)) {
     wgrad_fast_tile(g, &bm, &bn);
   } else if (dtype == 0) {
     bm = 64, bn = 64;

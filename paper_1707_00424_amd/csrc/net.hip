@@ -55,6 +55,7 @@ struct Net {
   int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0, wpartial_bytes = 0;
   int64_t bn_floats = 0;
   int max_bn_c = 0;
+  std::vector<TransposeTable> transposes;  // weights that backward-data reads transposed, in launch-sized groups
 
   int64_t alloc(int64_t bytes) {
     const int64_t o = ws_bytes;
@@ -244,6 +245,17 @@ bool build_plan(Net &N, std::string &err) {
       N.want_grad(op.in);
     }
   }
+  for (const Op &op : N.ops) {
+    if (op.type != OP_CONV || !op.need_dx) continue;
+    if (N.transposes.empty() || N.transposes.back().count == TransposeTable::kMax) {
+      N.transposes.emplace_back();
+      N.transposes.back().count = 0;
+    }
+    TransposeTable &t = N.transposes.back();
+    const int i = t.count++;
+    t.cout[i] = op.Cout, t.rs[i] = op.R * op.R, t.cin[i] = op.Cin;
+    t.src_off[i] = N.segs[op.wseg].offset, t.dst_off[i] = op.wt_off;
+  }
   N.wpartial_bytes = wpartial > 0 ? wpartial : 256;
   N.off_wpartial = N.alloc(N.wpartial_bytes);
   int maxc = N.max_bn_c;
@@ -337,6 +349,8 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
 hipError_t backward(const Run &r, float *grad) {
   Net &N = *r.N;
   const int vw = 16 / N.esize;
+  for (const TransposeTable &t : N.transposes)
+    HIP_TRY(launch_weight_transpose_all(r.st, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
   for (int oi = (int)N.ops.size() - 1; oi >= 0; --oi) {
     const Op &op = N.ops[oi];
     switch (op.type) {
@@ -369,10 +383,8 @@ hipError_t backward(const Run &r, float *grad) {
           }
         }
         if (op.need_dx) {
-          void *wt = r.ws + op.wt_off;
+          void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
-          HIP_TRY(launch_weight_transpose(r.st, N.dtype, r.n, op.Cout, op.R * op.R, op.Cin, r.wptr(op.wseg), r.p_rs, wt,
-                                          wsize));
           const ConvGeom gb = bwd_geom(op, r.B);
           GemmIO io{};
           io.in = dy, io.in_rs = dy_rs;

@@ -52,6 +52,17 @@ hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const v
 hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, int RS, int Cin, const void *w,
                                    long long w_rs, void *wt, long long wt_rs);
 // dst (activation dtype) = src fp32, `count` elements.
+// All layers' weight transposes in one launch.  Entry i: weights [Cout][RS][Cin] at element offset
+// src_off of a replica's parameter row -> [Cin][RS][Cout] at byte offset dst_off of `dst_base`, one
+// copy per replica (replica stride = the layer's weight count).
+struct TransposeTable {
+  enum { kMax = 40 };
+  int count;
+  int cout[kMax], rs[kMax], cin[kMax];
+  long long src_off[kMax], dst_off[kMax];
+};
+hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
+                                       long long p_rs, void *dst_base);
 hipError_t launch_convert(hipStream_t st, int dtype, const float *src, void *dst, long long count);
 hipError_t launch_fill(hipStream_t st, float *dst, long long count, float value);
 // out[i] = mean over replicas of in[rep*rs + i].

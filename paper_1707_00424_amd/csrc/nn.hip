@@ -606,6 +606,21 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose(int Cout, int RS,
 }
 
 template <typename T>
+__global__ __launch_bounds__(kThreads) void k_weight_transpose_all(const TransposeTable tab, const T *__restrict__ params,
+                                                                   long long p_rs, char *__restrict__ dst_base) {
+  const int layer = blockIdx.y, rep = blockIdx.z;
+  const int Cout = tab.cout[layer], RS = tab.rs[layer], Cin = tab.cin[layer];
+  const int total = Cout * RS * Cin;
+  const T *src = params + rep * p_rs + tab.src_off[layer];
+  T *dst = (T *)(dst_base + tab.dst_off[layer]) + (long long)rep * total;
+  for (int i = blockIdx.x * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
+    const int co = i % Cout, t = i / Cout;
+    const int rs = t % RS, ci = t / RS;
+    dst[i] = src[(co * RS + rs) * Cin + ci];
+  }
+}
+
+template <typename T>
 __global__ __launch_bounds__(kThreads) void k_convert(const float *__restrict__ src, T *__restrict__ dst,
                                                       long long count) {
   for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < count; i += (long long)gridDim.x * kThreads)
@@ -853,6 +868,18 @@ hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, i
                                 w_rs, (float *)wt, wt_rs),
              hipLaunchKernelGGL(k_weight_transpose<bf16_t>, grid, dim3(kThreads), 0, st, Cout, RS, Cin,
                                 (const bf16_t *)w, w_rs, (bf16_t *)wt, wt_rs));
+  return hipGetLastError();
+}
+
+hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
+                                       long long p_rs, void *dst_base) {
+  if (tab.count < 1) return hipSuccess;
+  dim3 grid(96, tab.count, n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_weight_transpose_all<float>, grid, dim3(kThreads), 0, st, tab, (const float *)params, p_rs,
+                                (char *)dst_base),
+             hipLaunchKernelGGL(k_weight_transpose_all<bf16_t>, grid, dim3(kThreads), 0, st, tab, (const bf16_t *)params,
+                                p_rs, (char *)dst_base));
   return hipGetLastError();
 }
 

@@ -78,6 +78,9 @@ CASES = [
     (1, 3, 16, 16, 64, 160, 3, 1, 1),   # same, 5 dy tiles per workgroup
     (2, 3, 8, 8, 32, 128, 3, 1, 1),     # same, two 8 x 8 images per block, odd batch
     (1, 2, 24, 16, 32, 192, 3, 1, 1),   # same, two groups of 3 dy tiles, three row blocks per image
+    (2, 4, 12, 12, 3, 16, 3, 1, 1),     # whole contraction in one tile (K = 27): first-layer kernel, ragged last tile
+    (2, 3, 14, 14, 1, 20, 5, 1, 0),     # same, K = 25, one input channel, 'valid' 5x5
+    (1, 5, 16, 16, 3, 96, 3, 2, 1),     # same, stride 2, three 32-channel tiles
 ]
 
 
