@@ -310,7 +310,10 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         io.resid = op.resid >= 0 ? r.tptr(op.resid) : nullptr, io.resid_rs = op.resid >= 0 ? r.trs(op.resid) : 0;
         io.relu = op.relu;
         io.vecA = (op.Cin % vw == 0) && aligned_to(io.in, 16);
-        io.vecB = (g.K % vw == 0) && (N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) && aligned_to(io.w, 16);
+        // 16-byte loads of weight rows.  Global and buffer loads need 4-byte alignment only, which fp32 rows
+        // always have; bf16 rows must start on a 16-byte boundary (two-byte offsets would misalign them).
+        io.vecB = (g.K % vw == 0) && (N.dtype == 0 || ((N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) &&
+                                                       aligned_to(io.w, 16)));
         io.in_bytes = io.in_rs * N.esize;
         HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, io));
         break;
