@@ -302,3 +302,30 @@ def test_elastic_flat_workload_with_scoping(gpu):
     _, _, sp = P.parle_eval()
     want = float(((st.xa - st.x) ** 2).sum())
     assert abs(sp - want) <= 1e-5 * want
+
+
+def test_entropy_sgd_is_parle_with_one_replica(gpu):
+    """n = 1, no elastic term: the device's (8a)-(8c) against Entropy-SGD written directly from (6a)-(6c)
+    (Section 2.1) on f(x) = |x - c|^2 / 2 with exact gradients, printed-equation scaling (xa_mode = 1)."""
+    torch, pb = gpu
+    rng = np.random.default_rng(31)
+    N, L, eta_p, eta, g, alpha = 1003, 5, 0.05, 0.7, 0.3, 0.75
+    c, x0 = rng.standard_normal(N), rng.standard_normal(N)
+    P = pb.Parle(pb.make_config(model=pb.MODEL_FLAT, n_replicas=1, n_params=N, L=L, eta_inner=eta_p, eta_outer=eta,
+                                gamma0=g, rho0=0.0, momentum=0.0, alpha=alpha, xa_mode=1, fuse_outer=1),
+                 x0[None].astype(np.float32))
+    cd = torch.as_tensor(c.astype(np.float32)).cuda()
+    x = x0.astype(np.float32).astype(np.float64)
+    c64 = c.astype(np.float32).astype(np.float64)
+    for _ in range(3):
+        y, z = x.copy(), x.copy()
+        for _ in range(L):
+            P.grad[0, :N].copy_(P.y[0, :N] - cd)          # exact gradient of f at the device's y
+            P.parle_inner_step()
+            y = y - eta_p * ((y - c64) + g * (y - x))        # (6a) without the noise term, as the paper runs it
+            z = alpha * z + (1 - alpha) * y                  # (6b)
+        P.parle_outer_step()
+        x_before = x
+        x = x - eta * (x - z)                                # (6c)
+        assert_close("x", P.state()["x"][0], x)
+        assert_close("x_ref", P.state()["x_ref"], x_before)  # the mean is taken before the replica moves

@@ -373,3 +373,26 @@ def test_inner_block_graph_replays_equal_step_by_step(gpu, name, bf16, alg):
         Ps.parle_inner_step(dX[k], dY[k], None)
     assert np.array_equal(Pg.state()["y"], Ps.state()["y"])
     assert Pg.parle_get_state()[0] == blocks * L + 2
+
+
+def test_wrn_28_10_one_step_reduced_batch(gpu):
+    """WRN-28-10 (Section 4.3, 36.5 million weights) as arch = (16, 10, 4): one inner step and the outer step for one
+    replica on a batch of 4 (the oracle needs seconds), bf16 compute with fp32 master weights."""
+    torch, pb = gpu
+    a, n, B = onets.arch("wrn", widen=10, nb=4), 1, 4
+    P, O = make(pb, a, n, B, bf16=1, seed=0, oracle_dtype=np.float32)
+    assert abs(P.sizes.n_params / 1e6 - 36.5) < 0.1
+    X, Y = synth.image_batches(0, 1, n, B, a["H"], a["W"], a["C"], a["classes"])
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    P.parle_inner_step(dev(torch, X[0]), dev(torch, Y[0]), loss)
+    ref_loss = O.inner_step(X[0], Y[0])
+    np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=2e-2)
+    got = P.state()
+    g, ref = got["grad"][0].astype(np.float64), O.last_grad[0].astype(np.float64)
+    cos = (g * ref).sum() / np.sqrt((g * g).sum() * (ref * ref).sum())
+    assert cos >= 0.9 and abs(np.linalg.norm(g) / np.linalg.norm(ref) - 1) <= 0.1, cos
+    P.parle_outer_step()
+    O.outer_step()
+    got = P.state()
+    for t in ("x", "y", "z", "x_ref"):
+        check(t, got[t], getattr(O.st, t), 2e-2)
