@@ -605,18 +605,36 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose(int Cout, int RS,
   }
 }
 
+// For every window tap rs the layer is a [Cout][Cin] matrix (row stride RS*Cin) that becomes a
+// [Cin][Cout] matrix (row stride RS*Cout): 64 x 64 tiles go through LDS so that both the reads (along
+// Cin) and the writes (along Cout) are contiguous.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_weight_transpose_all(const TransposeTable tab, const T *__restrict__ params,
                                                                    long long p_rs, char *__restrict__ dst_base) {
+  __shared__ T tile[64][64 + 2];
   const int layer = blockIdx.y, rep = blockIdx.z;
   const int Cout = tab.cout[layer], RS = tab.rs[layer], Cin = tab.cin[layer];
-  const int total = Cout * RS * Cin;
+  const long long total = (long long)Cout * RS * Cin;
   const T *src = params + rep * p_rs + tab.src_off[layer];
   T *dst = (T *)(dst_base + tab.dst_off[layer]) + (long long)rep * total;
-  for (int i = blockIdx.x * kThreads + threadIdx.x; i < total; i += gridDim.x * kThreads) {
-    const int co = i % Cout, t = i / Cout;
-    const int rs = t % RS, ci = t / RS;
-    dst[i] = src[(co * RS + rs) * Cin + ci];
+  const int tco = (Cout + 63) / 64, tci = (Cin + 63) / 64;
+  const int tiles = tco * tci * RS;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 x 4
+  for (int t = blockIdx.x; t < tiles; t += gridDim.x) {
+    const int rs = t % RS, tt = t / RS;
+    const int co0 = (tt / tci) * 64, ci0 = (tt % tci) * 64;
+#pragma unroll 4
+    for (int r = ty; r < 64; r += 4) {
+      const int co = co0 + r, ci = ci0 + tx;
+      if (co < Cout && ci < Cin) tile[r][tx] = src[((long long)co * RS + rs) * Cin + ci];
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int r = ty; r < 64; r += 4) {
+      const int ci = ci0 + r, co = co0 + tx;
+      if (ci < Cin && co < Cout) dst[((long long)ci * RS + rs) * Cout + co] = tile[tx][r];
+    }
+    __syncthreads();
   }
 }
 
@@ -874,7 +892,7 @@ hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, i
 hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
                                        long long p_rs, void *dst_base) {
   if (tab.count < 1) return hipSuccess;
-  dim3 grid(96, tab.count, n);
+  dim3 grid(256, tab.count, n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_weight_transpose_all<float>, grid, dim3(kThreads), 0, st, tab, (const float *)params, p_rs,
                                 (char *)dst_base),
