@@ -21,6 +21,17 @@ Conventions (they define the function the device must reproduce):
   running statistics updated with momentum 0.1 and the unbiased variance;
   evaluation uses the running statistics.
 
+* dropout (Section 4: 0.25 for LeNet, 0.3 / 0.4 for the wide residual networks, 0.5 for All-CNN) is
+  off unless a ``drop`` description is passed: a unit is kept when a counter-based hash of
+  (seed, inner step, replica, dropout site, element index) is at least p * 2^24 in its top 24
+  bits, kept units are scaled by 1 / (1 - p); evaluation applies no dropout.  The paper names the
+  rates only; the sites are a reading: LeNet after each pooling and after fc's ReLU, All-CNN after
+  its two stride-2 convolutions, wide residual blocks between their two convolutions.  The hash is
+  two rounds of a 32-bit multiply-xorshift finaliser (the device implements the same definition;
+  the two sides share no code).
+* ``lenet`` with ``bn=1`` (Section 4.2 lists batch-norm for LeNet): batch-norm follows both
+  convolutions and fc1, before the ReLU.
+
 Architectures (sizes are parameters so tests can shrink them):
 ``mlp``      in-hidden-classes, ReLU.
 ``lenet``    conv k x k (valid) - ReLU - pool - conv k x k - ReLU - pool - fc - ReLU - fc.
@@ -48,7 +59,7 @@ def arch(model: str, **kw):
     if model == "mlp":
         a = dict(model="mlp", H=28, W=28, C=1, hidden=128, classes=10)
     elif model == "lenet":
-        a = dict(model="lenet", H=28, W=28, C=1, c1=20, c2=50, k=5, fc=500, classes=10)
+        a = dict(model="lenet", H=28, W=28, C=1, c1=20, c2=50, k=5, fc=500, classes=10, bn=0)
     elif model == "allcnn":
         a = dict(model="allcnn", H=32, W=32, C=3, ca=96, cb=192, classes=10)
     elif model == "wrn":
@@ -100,9 +111,16 @@ def layout(a):
         h1, w1 = (a["H"] - k + 1) // 2, (a["W"] - k + 1) // 2
         h2, w2 = (h1 - k + 1) // 2, (w1 - k + 1) // 2
         d = h2 * w2 * a["c2"]
+        bn = a.get("bn", 0)
         segs += _conv_segs("conv1", a["c1"], k, a["C"])
+        if bn:
+            segs += _bn_segs("bn1", a["c1"])
         segs += _conv_segs("conv2", a["c2"], k, a["c1"])
+        if bn:
+            segs += _bn_segs("bn2", a["c2"])
         segs += [_seg("fc1.w", (a["fc"], d), "weight", d), _seg("fc1.b", (a["fc"],), "bias", d)]
+        if bn:
+            segs += _bn_segs("bn3", a["fc"])
         segs += [_seg("fc2.w", (a["classes"], a["fc"]), "weight", a["fc"]),
                  _seg("fc2.b", (a["classes"],), "bias", a["fc"])]
     elif m == "allcnn":
@@ -291,6 +309,37 @@ def batchnorm(t, x, gam, bet, stats, train):
     return o
 
 
+def mix32(x):
+    """32-bit multiply-xorshift finaliser on uint32 arrays (wraps modulo 2^32)."""
+    x = np.asarray(x, dtype=np.uint32).copy()
+    x ^= x >> np.uint32(16)
+    x *= np.uint32(0x7FEB352D)
+    x ^= x >> np.uint32(15)
+    x *= np.uint32(0x846CA68B)
+    x ^= x >> np.uint32(16)
+    return x
+
+
+def dropout_keep(seed, step, replica, site, count, p):
+    """Boolean keep-mask of ``count`` elements for dropout probability ``p`` (taken in float32)."""
+    m32 = (1 << 32) - 1
+    key = mix32(np.uint32((int(seed) + 0x9E3779B9 * int(step)) & m32))
+    key = mix32(key ^ np.uint32((int(replica) * 0x85EBCA6B + int(site) * 0xC2B2AE35 + 1) & m32))
+    idx = np.arange(count, dtype=np.uint32)
+    h = mix32(mix32(idx ^ key) + key)
+    thresh = int(np.floor(float(np.float32(p)) * (1 << 24)))
+    return (h >> np.uint32(8)) >= np.uint32(thresh)
+
+
+def dropout(t, x, keep, p):
+    """Inverted dropout with a given keep-mask (flat, in the element order of ``x``)."""
+    scale = 1.0 / (1.0 - float(np.float32(p)))
+    m = keep.reshape(x.v.shape).astype(x.v.dtype) * x.v.dtype.type(scale)
+    o = Var(x.v * m)
+    t.back.append(lambda: x.acc(o.g * m))
+    return o
+
+
 def add(t, p, q):
     o = Var(p.v + q.v)
 
@@ -322,16 +371,34 @@ def softmax_xent(t, logits, labels):
 # ----------------------------------------------------------------------------
 # networks
 # ----------------------------------------------------------------------------
-def forward(a, P, x, t, train=True, bn_state=None):
-    """Logits of architecture ``a`` with parameter Vars ``P`` on images ``x`` (a Var)."""
+def forward(a, P, x, t, train=True, bn_state=None, drop=None):
+    """Logits of architecture ``a`` with parameter Vars ``P`` on images ``x`` (a Var).
+
+    ``drop`` = dict(p, seed, step, replica) switches dropout on (training only)."""
     m = a["model"]
+    site = [0]
+
+    def dropped(h):
+        if not train or drop is None or drop["p"] <= 0:
+            return h
+        keep = dropout_keep(drop["seed"], drop["step"], drop["replica"], site[0], h.v.size, drop["p"])
+        site[0] += 1
+        return dropout(t, h, keep, drop["p"])
+
     if m == "mlp":
         h = relu(t, linear(t, x, P["fc1.w"], P["fc1.b"]))
         return linear(t, h, P["fc2.w"], P["fc2.b"])
     if m == "lenet":
-        h = maxpool2(t, relu(t, conv2d(t, x, P["conv1.w"], P["conv1.b"], 1, 0)))
-        h = maxpool2(t, relu(t, conv2d(t, h, P["conv2.w"], P["conv2.b"], 1, 0)))
-        h = relu(t, linear(t, h, P["fc1.w"], P["fc1.b"]))
+        bn = a.get("bn", 0)
+
+        def act(h, name):
+            if bn:
+                h = batchnorm(t, h, P[name + ".g"], P[name + ".b"], bn_state[name], train)
+            return relu(t, h)
+
+        h = dropped(maxpool2(t, act(conv2d(t, x, P["conv1.w"], P["conv1.b"], 1, 0), "bn1")))
+        h = dropped(maxpool2(t, act(conv2d(t, h, P["conv2.w"], P["conv2.b"], 1, 0), "bn2")))
+        h = dropped(act(linear(t, h, P["fc1.w"], P["fc1.b"]), "bn3"))   # batch-norm over the batch, per feature
         return linear(t, h, P["fc2.w"], P["fc2.b"])
     if m == "allcnn":
         strides = [1, 1, 2, 1, 1, 2, 1, 1, 1]
@@ -341,6 +408,8 @@ def forward(a, P, x, t, train=True, bn_state=None):
             h = conv2d(t, h, P[f"conv{i + 1}.w"], P[f"conv{i + 1}.b"], strides[i], pads[i])
             if i < 8:
                 h = relu(t, h)
+            if strides[i] == 2:
+                h = dropped(h)
         return gap(t, h)
     if m == "wrn":
         h = conv2d(t, x, P["conv1.w"], None, 1, 1)
@@ -348,7 +417,7 @@ def forward(a, P, x, t, train=True, bn_state=None):
             o = relu(t, batchnorm(t, h, P[name + ".bn1.g"], P[name + ".bn1.b"], bn_state[name + ".bn1"], train))
             u = conv2d(t, o, P[name + ".conv1.w"], None, stride, 1)
             u = relu(t, batchnorm(t, u, P[name + ".bn2.g"], P[name + ".bn2.b"], bn_state[name + ".bn2"], train))
-            u = conv2d(t, u, P[name + ".conv2.w"], None, 1, 1)
+            u = conv2d(t, dropped(u), P[name + ".conv2.w"], None, 1, 1)
             if cin != cout or stride != 1:
                 sc = conv2d(t, o, P[name + ".sc.w"], None, stride, 0)
             else:
@@ -359,7 +428,7 @@ def forward(a, P, x, t, train=True, bn_state=None):
     raise ValueError(m)
 
 
-def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64):
+def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop=None):
     """Mini-batch loss at the flat parameter vector and its gradient (same packing).
 
     In training mode batch-norm running statistics in ``bn_state`` are updated in place.
@@ -368,7 +437,7 @@ def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64):
     t = Tape()
     P = {k: Var(v) for k, v in unpack(a, flat).items()}
     x = Var(np.asarray(images, dtype=dtype))
-    logits = forward(a, P, x, t, train=True, bn_state=bn_state)
+    logits = forward(a, P, x, t, train=True, bn_state=bn_state, drop=drop)
     loss, _ = softmax_xent(t, logits, np.asarray(labels))
     t.backward()
     grad = np.concatenate([P[s["name"]].g.reshape(-1) for s in layout(a)])

@@ -55,6 +55,8 @@ class ParleConfig:
     xa_mode: int = 0
     xref_mode: int = 0
     reset_flags: int = 3
+    dropout: float = 0.0             # Section 4 (networks only); 0 = off
+    dropout_seed: int = 0
 
 
 @dataclass

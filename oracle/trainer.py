@@ -24,8 +24,10 @@ class ParleNet:
         losses = np.zeros(n)
         G = np.zeros_like(self.st.y)
         for a_i in range(n):
+            drop = (dict(p=self.cfg.dropout, seed=self.cfg.dropout_seed, step=self.st.k, replica=a_i)
+                    if self.cfg.dropout > 0 else None)
             losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.y[a_i], images[a_i], labels[a_i],
-                                                     bn_state=self.bn[a_i], dtype=self.dtype)
+                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop)
         parle.inner_update(self.st, G, self.cfg)
         self.last_grad = G
         return losses

@@ -250,3 +250,85 @@ def test_trainer_with_one_replica_and_no_coupling_is_sgd_on_the_network():
         net.inner_step(x[None], y[None])
         p = p - 0.05 * nets.loss_and_grad(a, p, x, y)[1]
         assert np.allclose(net.st.y[0], p, atol=1e-14)
+
+
+# ---- dropout (Section 4) and LeNet with batch-norm (Section 4.2) -----------------------------------------
+def test_mix32_is_a_bijection_on_a_sample_and_avalanches():
+    x = np.arange(1 << 16, dtype=np.uint32)
+    h = nets.mix32(x)
+    assert len(np.unique(h)) == len(x)                      # an invertible finaliser has no collisions
+    flips = np.unpackbits((nets.mix32(x) ^ nets.mix32(x ^ np.uint32(1))).view(np.uint8)).reshape(len(x), 32).mean()
+    assert 0.45 < flips < 0.55                              # one input bit flips about half of the output bits
+    assert nets.mix32(np.uint32(0)) == 0 and nets.mix32(np.uint32(1)) != 1
+
+
+def test_dropout_mask_rate_scale_and_independence():
+    n = 1_000_000
+    for p in (0.25, 0.5, 0.3):
+        keep = nets.dropout_keep(seed=7, step=3, replica=1, site=0, count=n, p=p)
+        rate = keep.mean()
+        assert abs(rate - (1 - p)) < 4 * np.sqrt(p * (1 - p) / n) + 2 ** -24
+        assert abs((keep / (1 - np.float32(p))).mean() - 1) < 3e-3          # inverted dropout keeps the mean
+    assert nets.dropout_keep(7, 3, 1, 0, 1000, 0.0).all()                   # p = 0 keeps everything
+    base = nets.dropout_keep(7, 3, 1, 0, n, 0.5)
+    assert np.array_equal(base, nets.dropout_keep(7, 3, 1, 0, n, 0.5))      # a pure function of its counters
+    for other in (nets.dropout_keep(8, 3, 1, 0, n, 0.5), nets.dropout_keep(7, 4, 1, 0, n, 0.5),
+                  nets.dropout_keep(7, 3, 2, 0, n, 0.5), nets.dropout_keep(7, 3, 1, 1, n, 0.5)):
+        agree = (base == other).mean()                                      # independent masks agree half the time
+        assert abs(agree - 0.5) < 4 * 0.5 / np.sqrt(n)
+    # prefix property: the mask of a shorter tensor is the start of the mask of a longer one (element counters)
+    assert np.array_equal(nets.dropout_keep(7, 3, 1, 0, 100, 0.5), base[:100])
+
+
+DROP_NETS = {
+    "lenet_bn": nets.arch("lenet", H=10, W=10, C=1, c1=2, c2=3, k=3, fc=5, classes=3, bn=1),
+    "lenet": nets.arch("lenet", H=10, W=10, C=1, c1=2, c2=3, k=3, fc=5, classes=3),
+    "allcnn": nets.arch("allcnn", H=8, W=8, C=2, ca=3, cb=4, classes=3),
+    "wrn": nets.arch("wrn", H=8, W=8, C=2, base=2, widen=2, nb=1, classes=3),
+}
+
+
+@pytest.mark.parametrize("name", list(DROP_NETS))
+def test_gradient_with_dropout_matches_finite_differences(name):
+    """The mask is a fixed function of its counters, so the loss is still differentiable in the weights."""
+    a = DROP_NETS[name]
+    rng = np.random.default_rng(11)
+    flat = rng.standard_normal(nets.n_params(a)) * 0.3
+    off = 0
+    for s in nets.layout(a):                 # batch-norm scales near one, as in training
+        size = int(np.prod(s["shape"]))
+        if s["kind"] == "bn_gamma":
+            flat[off:off + size] = 1 + 0.1 * rng.standard_normal(size)
+        off += size
+    X = rng.standard_normal((5, a["H"], a["W"], a["C"]))
+    Y = rng.integers(0, a["classes"], 5)
+    drop = dict(p=0.4, seed=5, step=2, replica=1)
+
+    def f(v):
+        return nets.loss_and_grad(a, v, X, Y, bn_state=nets.new_bn_state(a), drop=drop)[0]
+
+    loss, g = nets.loss_and_grad(a, flat, X, Y, bn_state=nets.new_bn_state(a), drop=drop)
+    loss0, _ = nets.loss_and_grad(a, flat, X, Y, bn_state=nets.new_bn_state(a))
+    assert loss != loss0                                   # dropout is on
+    idx = rng.choice(len(flat), size=min(60, len(flat)), replace=False)
+    eps = 1e-6
+    for i in idx:
+        e = np.zeros_like(flat)
+        e[i] = eps
+        fd = (f(flat + e) - f(flat - e)) / (2 * eps)
+        assert abs(fd - g[i]) <= 1e-5 * max(1.0, abs(fd)), (name, i, fd, g[i])
+
+
+def test_dropout_off_in_evaluation_and_lenet_bn_layout():
+    a = DROP_NETS["lenet_bn"]
+    names = [s["name"] for s in nets.layout(a)]
+    assert names == ["conv1.w", "conv1.b", "bn1.g", "bn1.b", "conv2.w", "conv2.b", "bn2.g", "bn2.b", "fc1.w", "fc1.b",
+                     "bn3.g", "bn3.b", "fc2.w", "fc2.b"]
+    assert [n for n, _ in nets.bn_layers(a)] == ["bn1", "bn2", "bn3"]
+    rng = np.random.default_rng(3)
+    flat = rng.standard_normal(nets.n_params(a)) * 0.3
+    X, Y = rng.standard_normal((4, 10, 10, 1)), rng.integers(0, 3, 4)
+    bn = nets.new_bn_state(a)
+    nets.loss_and_grad(a, flat, X, Y, bn_state=bn, drop=dict(p=0.5, seed=1, step=0, replica=0))
+    assert not np.allclose(bn["bn3"][0], 0)                # running statistics moved
+    assert nets.evaluate(a, flat, X, Y, bn_state=bn) == nets.evaluate(a, flat, X, Y, bn_state=bn)
