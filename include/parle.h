@@ -82,6 +82,16 @@ typedef enum {
  *            shape changes; BN ReLU, global average pool, fc.  No conv bias.  BN: batch statistics
  *            per replica (biased variance), eps 1e-5, running statistics with momentum 0.1 and
  *            unbiased variance.                                         default 32x32x3, 16/4/2 (WRN-16-4)
+ *   LENET with lenet_bn = 1 (Section 4.2 lists batch-norm for LeNet): batch-norm follows both
+ *            convolutions and fc1, before the ReLU; segments bn1, bn2, bn3 follow conv1, conv2, fc1.
+ * Dropout (Section 4: 0.25 LeNet, 0.3 / 0.4 wide residual networks, 0.5 All-CNN; `dropout` = 0 switches
+ * it off): sites are LENET after each pooling and after fc's ReLU, ALLCNN_C after its two stride-2
+ * convolutions, WRN between the two convolutions of every block; numbered in execution order.
+ * Element i of site s of replica a at inner step k (the value of k before the step) is kept iff
+ *   (mix(mix(i ^ key) + key) >> 8) >= floor(dropout * 2^24),
+ *   key = mix(mix(seed + 0x9E3779B9*k) ^ (a*0x85EBCA6B + s*0xC2B2AE35 + 1)),   all modulo 2^32,
+ *   mix(x): x ^= x >> 16; x *= 0x7FEB352D; x ^= x >> 15; x *= 0x846CA68B; x ^= x >> 16,
+ * kept elements are multiplied by 1 / (1 - dropout); parle_eval applies no dropout.
  * Loss: mean over the replica's mini-batch of the softmax cross-entropy (Section 1.1).
  * ReLU'(0) = 0.  maxpool2 = 2x2 window, stride 2, floor; gradient to the first maximum in
  * row-major window order.
@@ -113,6 +123,9 @@ typedef struct {
   int32_t algorithm;     /* parle_algorithm */
   int32_t graph_block;   /* 1 = parle_inner_block replays a captured HIP graph (see there); 0 = it enqueues
                             the steps one by one */
+  float dropout;         /* dropout probability in [0, 1) at the sites listed above; 0 = off */
+  int32_t lenet_bn;      /* LENET: 1 = batch-norm after conv1, conv2 and fc1 */
+  int64_t dropout_seed;  /* low 32 bits seed the keep-masks */
 } parle_config;
 
 typedef struct {

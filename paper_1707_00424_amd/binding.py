@@ -30,7 +30,8 @@ class parle_config(C.Structure):
                 ("gamma0", C.c_float), ("rho0", C.c_float), ("gamma_max", C.c_float), ("rho_max", C.c_float),
                 ("scoping_B", C.c_int64),
                 ("xa_mode", C.c_int32), ("xref_mode", C.c_int32), ("reset_flags", C.c_int32),
-                ("fuse_outer", C.c_int32), ("algorithm", C.c_int32), ("graph_block", C.c_int32)]
+                ("fuse_outer", C.c_int32), ("algorithm", C.c_int32), ("graph_block", C.c_int32),
+                ("dropout", C.c_float), ("lenet_bn", C.c_int32), ("dropout_seed", C.c_int64)]
 
 
 class parle_sizes(C.Structure):
@@ -125,11 +126,13 @@ def _check(status, ctx=None):
 def make_config(model=MODEL_FLAT, n_replicas=1, batch=0, L=25, compute_bf16=0, in_h=0, in_w=0, in_c=0, n_classes=0,
                 arch=(0, 0, 0, 0), n_params=0, eta_inner=0.1, eta_outer=0.1, momentum=0.9, alpha=0.75,
                 weight_decay=0.0, gamma0=0.01, rho0=1.0, gamma_max=1.0, rho_max=10.0, scoping_B=0, xa_mode=0,
-                xref_mode=0, reset_flags=3, fuse_outer=0, algorithm=ALG_PARLE, graph_block=0) -> parle_config:
+                xref_mode=0, reset_flags=3, fuse_outer=0, algorithm=ALG_PARLE, graph_block=0, dropout=0.0,
+                lenet_bn=0, dropout_seed=0) -> parle_config:
     a = list(arch) + [0] * (4 - len(arch))
     return parle_config(model, n_replicas, batch, L, compute_bf16, in_h, in_w, in_c, n_classes, (C.c_int32 * 4)(*a),
                         n_params, eta_inner, eta_outer, momentum, alpha, weight_decay, gamma0, rho0, gamma_max,
-                        rho_max, scoping_B, xa_mode, xref_mode, reset_flags, fuse_outer, algorithm, graph_block)
+                        rho_max, scoping_B, xa_mode, xref_mode, reset_flags, fuse_outer, algorithm, graph_block, dropout,
+                        lenet_bn, dropout_seed)
 
 
 def parle_query_sizes(cfg: parle_config) -> parle_sizes:

@@ -34,6 +34,7 @@ constexpr int64_t kRowAlign = 1024;      // elements: every replica row starts 4
 constexpr int64_t kHeaderBytes = 65536;  // front of the workspace: spread partials and result scalars
 constexpr int64_t kScalarOff = 32768;
 constexpr int64_t kCouplingOff = kScalarOff + 64;  // {g, r} for launches that read them from memory
+constexpr int64_t kStepOff = kScalarOff + 128;     // inner-step counter k that the dropout masks are keyed by
 
 thread_local std::string g_init_err;
 
@@ -84,6 +85,10 @@ parle_status check_config(const parle_config *cfg, Arch &arch, std::string &msg)
   }
   if ((cfg->algorithm | 1) != 1 || (cfg->graph_block | 1) != 1) {
     msg = "algorithm or graph_block out of range";
+    return PARLE_EINVAL;
+  }
+  if (!(cfg->dropout >= 0.f) || !(cfg->dropout < 1.f) || (cfg->lenet_bn | 1) != 1) {
+    msg = "dropout must be in [0, 1), lenet_bn 0 or 1";
     return PARLE_EINVAL;
   }
   if (cfg->graph_block && cfg->model == PARLE_MODEL_FLAT) {
@@ -143,6 +148,17 @@ float *coupling_dev(parle_ctx *ctx) {
   return ctx->cfg.graph_block ? (float *)((char *)ctx->buf.workspace + kCouplingOff) : nullptr;
 }
 
+// The dropout kernels read k from device memory (a captured launch cannot change its arguments); it is
+// advanced by a one-thread kernel after every inner step.
+long long *step_dev(parle_ctx *ctx) {
+  return ctx->cfg.dropout > 0.f && ctx->cfg.model != PARLE_MODEL_FLAT ? (long long *)((char *)ctx->buf.workspace + kStepOff)
+                                                                       : nullptr;
+}
+parle_status push_step(parle_ctx *ctx) {
+  if (!step_dev(ctx)) return PARLE_OK;
+  return parle_internal_set_step(ctx->stream, step_dev(ctx), ctx->k);
+}
+
 // g, r changed on the host: refresh the copy that captured launches read
 parle_status push_coupling(parle_ctx *ctx) {
   if (!ctx->cfg.graph_block) return PARLE_OK;
@@ -160,8 +176,9 @@ parle_status enqueue_inner(parle_ctx *ctx, hipStream_t st, const float *images_d
   const parle_config &c = ctx->cfg;
   if (c.model != PARLE_MODEL_FLAT) {
     hipError_t e = net_train_step(ctx->net, st, ctx->buf.y, ctx->buf.y_bf16, ctx->buf.grad, (float *)ctx->buf.bn_stats,
-                                  net_ws(ctx), images_dev, labels_dev, loss_dev);
+                                  net_ws(ctx), images_dev, labels_dev, loss_dev, step_dev(ctx));
     if (e != hipSuccess) return hip_fail(ctx, e, "forward/backward");
+    if (step_dev(ctx) && parle_internal_advance_step(st, step_dev(ctx))) return fail(ctx, PARLE_EHIP, "step counter launch failed");
   }
   void *shadow = c.compute_bf16 ? ctx->buf.y_bf16 : nullptr;
   parle_status s;
@@ -268,6 +285,7 @@ parle_status parle_init(const parle_config *cfg, const parle_buffers *buf, void 
       return bail(PARLE_EHIP, std::string("bn init: ") + hipGetErrorString(e));
   }
   if (push_coupling(ctx)) return bail(PARLE_EHIP, "coupling upload launch failed");
+  if (push_step(ctx)) return bail(PARLE_EHIP, "step counter launch failed");
   *out = ctx;
   return PARLE_OK;
 }
@@ -462,6 +480,7 @@ parle_status parle_set_state(parle_ctx *ctx, int64_t k, int64_t outer_done, floa
   ctx->inner_since_outer = ctx->cfg.L > 0 ? k - outer_done * (int64_t)ctx->cfg.L : 0;
   if (ctx->inner_since_outer < 0) ctx->inner_since_outer = 0;
   if (push_coupling(ctx)) return fail(ctx, PARLE_EHIP, "coupling upload launch failed");
+  if (push_step(ctx)) return fail(ctx, PARLE_EHIP, "step counter launch failed");
   return PARLE_OK;
 }
 

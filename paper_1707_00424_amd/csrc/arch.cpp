@@ -61,6 +61,7 @@ bool resolve_arch(const parle_config &cfg, Arch &a, std::string &msg) {
     case PARLE_MODEL_LENET: {
       a.H = pick(cfg.in_h, 28), a.W = pick(cfg.in_w, 28), a.C = pick(cfg.in_c, 1), a.classes = pick(cfg.n_classes, 10);
       a.a0 = pick(cfg.arch[0], 20), a.a1 = pick(cfg.arch[1], 50), a.a2 = pick(cfg.arch[2], 5), a.a3 = pick(cfg.arch[3], 500);
+      a.bn = cfg.lenet_bn;
       const int k = a.a2;
       const int h1 = (a.H - k + 1) / 2, w1 = (a.W - k + 1) / 2;
       const int h2 = (h1 - k + 1) / 2, w2 = (w1 - k + 1) / 2;
@@ -116,8 +117,11 @@ std::vector<Segment> build_layout(const Arch &a) {
       const int h1 = (a.H - k + 1) / 2, w1 = (a.W - k + 1) / 2;
       const int h2 = (h1 - k + 1) / 2, w2 = (w1 - k + 1) / 2;
       add_conv(v, off, "conv1", a.a0, k, a.C, true);
+      if (a.bn) add_bn(v, off, "bn1", a.a0);
       add_conv(v, off, "conv2", a.a1, k, a.a0, true);
+      if (a.bn) add_bn(v, off, "bn2", a.a1);
       add_fc(v, off, "fc1", a.a3, h2 * w2 * a.a1);
+      if (a.bn) add_bn(v, off, "bn3", a.a3);
       add_fc(v, off, "fc2", a.classes, a.a3);
       break;
     }

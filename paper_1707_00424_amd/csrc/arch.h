@@ -9,6 +9,7 @@ struct Arch {
   int model = 0;
   int H = 0, W = 0, C = 0, classes = 0;
   int a0 = 0, a1 = 0, a2 = 0, a3 = 0;  // model-specific sizes after defaults
+  int bn = 0;                          // LeNet: batch-norm after conv1, conv2 and fc1
 };
 
 struct Segment {

@@ -53,6 +53,9 @@ parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst,
 // override the by-value multipliers (a captured launch cannot change its arguments).  NULL = use the
 // arguments.
 parle_status parle_internal_set_coupling(hipStream_t st, float *coupling_dev, float g, float r);
+// The inner-step counter in device memory: set it, add one to it (one-thread kernels).
+parle_status parle_internal_set_step(hipStream_t st, long long *step_dev, long long k);
+parle_status parle_internal_advance_step(hipStream_t st, long long *step_dev);
 parle_status parle_internal_inner_update(hipStream_t st, int32_t n, int64_t n_pad, const float *grad, const float *x,
                                          float *y, float *vy, float *z, void *y_bf16, float eta_inner, float momentum,
                                          float alpha, float weight_decay, float g, const float *coupling_dev);

@@ -18,9 +18,10 @@ int64_t net_forward_flops_per_image(const Net *net);
 // Enqueues forward + loss + backward for all n replicas.  Parameters are read from `params`
 // ([n, n_pad] fp32) and, in bf16 mode, from `params_bf16`; gradients go to `grad` ([n, n_pad] fp32,
 // every parameter element is overwritten, padding untouched).  `loss_dev` ([n]) may be NULL.
+// `step_dev`: the inner-step counter in device memory, read by the dropout masks (NULL without dropout).
 hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const void *params_bf16, float *grad,
                           float *bn_stats, void *workspace, const float *images, const int32_t *labels,
-                          float *loss_dev);
+                          float *loss_dev, const long long *step_dev);
 
 // Enqueues a forward pass of ONE parameter row over `count` images in evaluation mode (BN uses
 // `bn_row`, the statistics of one replica or their average).  Results: loss_sum_dev[0] = sum of

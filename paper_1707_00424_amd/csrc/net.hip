@@ -9,7 +9,7 @@
 
 namespace {
 
-enum OpType { OP_CONV = 0, OP_POOL = 1, OP_GAP = 2, OP_BNRELU = 3 };
+enum OpType { OP_CONV = 0, OP_POOL = 1, OP_GAP = 2, OP_BNRELU = 3, OP_DROP = 4 };
 
 struct Tensor {
   int H = 0, W = 0, C = 0;
@@ -38,6 +38,9 @@ struct Op {
   int gseg = -1, betaseg = -1;
   int64_t saved_off = -1, sums_off = -1, run_off = 0;  // run_off in floats inside a replica's BN row
   int bn_add = -1;         // tensor whose gradient is added to this op's input gradient
+  // dropout
+  int site = 0;            // index of the dropout site in execution order (part of the mask's key)
+  bool drop_relu = false;  // the input is a ReLU output whose backward mask this op applies
 };
 
 }  // namespace
@@ -107,6 +110,20 @@ struct Net {
     ops.push_back(op);
     return (int)ops.size() - 1;
   }
+  int n_drop_sites = 0;
+  // dropout on tensor `in` (no-op when the rate is zero): returns the tensor the next layer reads
+  int add_drop(int in, bool relu_input) {
+    if (!(cfg.dropout > 0.f)) return in;
+    Op op;
+    op.type = OP_DROP;
+    op.in = in;
+    const Tensor t = tensors[in];
+    op.out = add_tensor(t.H, t.W, t.C);
+    op.site = n_drop_sites++;
+    op.drop_relu = relu_input;
+    ops.push_back(op);
+    return op.out;
+  }
 };
 
 namespace {
@@ -128,23 +145,36 @@ bool build_plan(Net &N, std::string &err) {
     }
     case PARLE_MODEL_LENET: {
       const int k = a.a2;
-      const int c1 = N.add_conv(img, a.H, a.W, a.C, "conv1", a.a0, k, 1, 0, true, true);
+      const bool bn = a.bn != 0, drop = N.cfg.dropout > 0.f;
+      // conv (+ ReLU in its epilogue, or batch-norm + ReLU as an op of its own), pooling, dropout
+      const int c1 = N.add_conv(img, a.H, a.W, a.C, "conv1", a.a0, k, 1, 0, true, !bn);
+      int h1 = N.ops[c1].out;
+      if (bn) h1 = N.ops[N.add_bn(h1, "bn1")].out;
       Op p1;
-      p1.type = OP_POOL, p1.in = N.ops[c1].out, p1.pool_relu_mask = true;
+      p1.type = OP_POOL, p1.in = h1, p1.pool_relu_mask = !bn;
       p1.out = N.add_tensor(N.ops[c1].Ho / 2, N.ops[c1].Wo / 2, a.a0);
       N.ops.push_back(p1);
       const Tensor tp1 = N.tensors[p1.out];
-      const int c2 = N.add_conv(p1.out, tp1.H, tp1.W, a.a0, "conv2", a.a1, k, 1, 0, true, true);
+      const int d1 = N.add_drop(p1.out, false);
+      const int c2 = N.add_conv(d1, tp1.H, tp1.W, a.a0, "conv2", a.a1, k, 1, 0, true, !bn);
       N.ops[c2].need_dx = true;
+      int h2 = N.ops[c2].out;
+      if (bn) h2 = N.ops[N.add_bn(h2, "bn2")].out;
       Op p2;
-      p2.type = OP_POOL, p2.in = N.ops[c2].out, p2.pool_relu_mask = true;
+      p2.type = OP_POOL, p2.in = h2, p2.pool_relu_mask = !bn;
       p2.out = N.add_tensor(N.ops[c2].Ho / 2, N.ops[c2].Wo / 2, a.a1);
       N.ops.push_back(p2);
       const Tensor tp2 = N.tensors[p2.out];
-      const int f1 = N.add_conv(p2.out, 1, 1, tp2.H * tp2.W * tp2.C, "fc1", a.a3, 1, 1, 0, true, true);
+      const int d2 = N.add_drop(p2.out, false);
+      const int f1 = N.add_conv(d2, 1, 1, tp2.H * tp2.W * tp2.C, "fc1", a.a3, 1, 1, 0, true, !bn);
       N.ops[f1].need_dx = true;
-      const int f2 = N.add_conv(N.ops[f1].out, 1, 1, a.a3, "fc2", a.classes, 1, 1, 0, true, false, true);
-      N.ops[f2].need_dx = true, N.ops[f2].mask_in = true;
+      int h3 = N.ops[f1].out;
+      if (bn) h3 = N.ops[N.add_bn(h3, "bn3")].out;
+      // the ReLU mask of fc1's output is applied by whoever writes its gradient: fc2's backward-data, or the
+      // dropout in between; after batch-norm the batch-norm backward applies it itself
+      const int d3 = N.add_drop(h3, !bn);
+      const int f2 = N.add_conv(d3, 1, 1, a.a3, "fc2", a.classes, 1, 1, 0, true, false, true);
+      N.ops[f2].need_dx = true, N.ops[f2].mask_in = !bn && !drop;
       N.t_logits = N.ops[f2].out;
       break;
     }
@@ -157,8 +187,11 @@ bool build_plan(Net &N, std::string &err) {
       for (int i = 0; i < 9; ++i) {
         const int c = N.add_conv(cur, H, W, C, "conv" + std::to_string(i + 1), cout[i], ks[i], st[i], ks[i] == 3 ? 1 : 0,
                                  true, i < 8);
-        if (i > 0) N.ops[c].need_dx = true, N.ops[c].mask_in = true;
+        // the gradient of a ReLU output is masked by its consumer: the next conv, or the dropout in between
+        const bool after_drop = N.cfg.dropout > 0.f && i > 0 && st[i - 1] == 2;
+        if (i > 0) N.ops[c].need_dx = true, N.ops[c].mask_in = !after_drop;
         cur = N.ops[c].out, H = N.ops[c].Ho, W = N.ops[c].Wo, C = cout[i];
+        if (st[i] == 2) cur = N.add_drop(cur, true);
       }
       Op g;
       g.type = OP_GAP, g.in = cur;
@@ -184,8 +217,9 @@ bool build_plan(Net &N, std::string &err) {
         const int cv1 = N.add_conv(o, H, W, b.cin, b.name + ".conv1", b.cout, 3, b.stride, 1, false, false);
         N.ops[cv1].need_dx = true;
         const int bn2 = N.add_bn(N.ops[cv1].out, b.name + ".bn2");
-        const int cv2 = N.add_conv(N.ops[bn2].out, N.ops[cv1].Ho, N.ops[cv1].Wo, b.cout, b.name + ".conv2", b.cout, 3, 1,
-                                   1, false, false);
+        const int cv1_ho = N.ops[cv1].Ho, cv1_wo = N.ops[cv1].Wo;
+        const int mid = N.add_drop(N.ops[bn2].out, false);
+        const int cv2 = N.add_conv(mid, cv1_ho, cv1_wo, b.cout, b.name + ".conv2", b.cout, 3, 1, 1, false, false);
         N.ops[cv2].need_dx = true;
         N.ops[cv2].resid = b.has_sc ? s : h;
         const int v = N.ops[cv2].out;
@@ -197,7 +231,7 @@ bool build_plan(Net &N, std::string &err) {
         } else {
           N.ops[bn1].bn_add = v;
         }
-        h = v, H = N.ops[cv1].Ho, W = N.ops[cv1].Wo;
+        h = v, H = cv1_ho, W = cv1_wo;
       }
       const int bno = N.add_bn(h, "bn_out");
       Op g;
@@ -275,6 +309,7 @@ struct Run {
   int64_t p_rs;
   char *ws;
   const float *images;
+  const long long *step_dev;  // inner-step counter (dropout key); NULL outside training
   void *tptr(int t) const {
     const Tensor &T = N->tensors[t];
     return T.external ? (void *)images : (void *)(ws + T.off);
@@ -328,6 +363,15 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         const Tensor &ti = N.tensors[op.in];
         HIP_TRY(launch_gap_fwd(r.st, N.dtype, N.tensors[op.out].f32, r.n, r.B, ti.H * ti.W, ti.C, r.tptr(op.in),
                                r.trs(op.in), r.tptr(op.out), r.trs(op.out)));
+        break;
+      }
+      case OP_DROP: {
+        const Tensor &ti = N.tensors[op.in];
+        const float p = N.cfg.dropout;
+        const unsigned thresh = train ? (unsigned)floor((double)p * 16777216.0) : 0u;
+        HIP_TRY(launch_dropout(r.st, N.dtype, r.n, (long long)r.B * ti.H * ti.W * ti.C, r.tptr(op.in), r.trs(op.in),
+                               r.tptr(op.out), r.trs(op.out), nullptr, 0, (unsigned)N.cfg.dropout_seed, r.step_dev,
+                               op.site, thresh, train ? 1.0f / (1.0f - p) : 1.0f));
         break;
       }
       case OP_BNRELU: {
@@ -414,6 +458,15 @@ hipError_t backward(const Run &r, float *grad) {
                                r.trs(op.in)));
         break;
       }
+      case OP_DROP: {
+        const Tensor &ti = N.tensors[op.in];
+        const float p = N.cfg.dropout;
+        HIP_TRY(launch_dropout(r.st, N.dtype, r.n, (long long)r.B * ti.H * ti.W * ti.C, r.gptr(op.out), r.trs(op.out),
+                               r.gptr(op.in), r.trs(op.in), op.drop_relu ? r.tptr(op.in) : nullptr, r.trs(op.in),
+                               (unsigned)N.cfg.dropout_seed, r.step_dev, op.site, (unsigned)floor((double)p * 16777216.0),
+                               1.0f / (1.0f - p)));
+        break;
+      }
       case OP_BNRELU: {
         const Tensor &ti = N.tensors[op.in];
         const int M = r.B * ti.H * ti.W;
@@ -461,9 +514,11 @@ int64_t net_forward_flops_per_image(const Net *net) {
 
 hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const void *params_bf16, float *grad,
                           float *bn_stats, void *workspace, const float *images, const int32_t *labels,
-                          float *loss_dev) {
+                          float *loss_dev, const long long *step_dev) {
   Net &N = *net;
-  Run r{net, st, N.n, N.B, params, N.dtype ? params_bf16 : (const void *)params, N.n_pad, (char *)workspace, images};
+  if (N.cfg.dropout > 0.f && !step_dev) return hipErrorInvalidValue;
+  Run r{net, st, N.n, N.B, params, N.dtype ? params_bf16 : (const void *)params, N.n_pad, (char *)workspace, images,
+        step_dev};
   if (N.dtype == 1) {
     const Tensor &ti = N.tensors[N.t_images];
     HIP_TRY(launch_convert(st, 1, images, r.ws + ti.off, (long long)N.n * N.B * ti.H * ti.W * ti.C));
@@ -484,7 +539,7 @@ hipError_t net_eval(Net *net, hipStream_t st, const float *param_row, const floa
     HIP_TRY(launch_convert(st, 1, param_row, ws + N.off_rowcopy, N.n_pad));
     row_t = ws + N.off_rowcopy;
   }
-  Run r{net, st, 1, count, param_row, row_t, N.n_pad, ws, images};
+  Run r{net, st, 1, count, param_row, row_t, N.n_pad, ws, images, nullptr};
   if (N.dtype == 1) {
     const Tensor &ti = N.tensors[N.t_images];
     HIP_TRY(launch_convert(st, 1, images, ws + ti.off, (long long)count * ti.H * ti.W * ti.C));

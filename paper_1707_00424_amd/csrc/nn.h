@@ -63,6 +63,12 @@ struct TransposeTable {
 };
 hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
                                        long long p_rs, void *dst_base);
+// Dropout with keep-masks from a counter-based hash (definition in parle.h).  `count` elements per replica;
+// step_dev holds the inner-step counter.  out = keep ? in * scale : 0; with relu_src the result is also
+// zeroed where relu_src <= 0 (backward through a ReLU that the dropout followed).  thresh = 0 copies.
+hipError_t launch_dropout(hipStream_t st, int dtype, int n, long long count, const void *in, long long in_rs, void *out,
+                          long long out_rs, const void *relu_src, long long relu_rs, unsigned seed,
+                          const long long *step_dev, int site, unsigned thresh, float scale);
 hipError_t launch_convert(hipStream_t st, int dtype, const float *src, void *dst, long long count);
 hipError_t launch_fill(hipStream_t st, float *dst, long long count, float value);
 // out[i] = mean over replicas of in[rep*rs + i].

@@ -638,6 +638,36 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose_all(const Transpo
   }
 }
 
+__device__ __forceinline__ unsigned mix32(unsigned x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_dropout(long long count, const T *__restrict__ in, long long in_rs,
+                                                      T *__restrict__ out, long long out_rs,
+                                                      const T *__restrict__ relu_src, long long relu_rs, unsigned seed,
+                                                      const long long *__restrict__ step_dev, unsigned site,
+                                                      unsigned thresh, float scale) {
+  const unsigned rep = blockIdx.y;
+  const unsigned k = step_dev ? (unsigned)step_dev[0] : 0u;
+  unsigned key = mix32(seed + 0x9E3779B9u * k);
+  key = mix32(key ^ (rep * 0x85EBCA6Bu + site * 0xC2B2AE35u + 1u));
+  const T *ip = in + rep * in_rs;
+  T *op = out + rep * out_rs;
+  const T *rp = relu_src ? relu_src + rep * relu_rs : nullptr;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < count; i += (long long)gridDim.x * kThreads) {
+    const unsigned h = mix32(mix32((unsigned)i ^ key) + key);
+    float v = (h >> 8) >= thresh ? ldf<T>(ip, i) * scale : 0.f;
+    if (rp && !(ldf<T>(rp, i) > 0.f)) v = 0.f;
+    stf<T>(op, i, v);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_convert(const float *__restrict__ src, T *__restrict__ dst,
                                                       long long count) {
@@ -898,6 +928,19 @@ hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const T
                                 (char *)dst_base),
              hipLaunchKernelGGL(k_weight_transpose_all<bf16_t>, grid, dim3(kThreads), 0, st, tab, (const bf16_t *)params,
                                 p_rs, (char *)dst_base));
+  return hipGetLastError();
+}
+
+hipError_t launch_dropout(hipStream_t st, int dtype, int n, long long count, const void *in, long long in_rs, void *out,
+                          long long out_rs, const void *relu_src, long long relu_rs, unsigned seed,
+                          const long long *step_dev, int site, unsigned thresh, float scale) {
+  dim3 grid(blocks_for(count, 16384), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_dropout<float>, grid, dim3(kThreads), 0, st, count, (const float *)in, in_rs, (float *)out,
+                                out_rs, (const float *)relu_src, relu_rs, seed, step_dev, (unsigned)site, thresh, scale),
+             hipLaunchKernelGGL(k_dropout<bf16_t>, grid, dim3(kThreads), 0, st, count, (const bf16_t *)in, in_rs,
+                                (bf16_t *)out, out_rs, (const bf16_t *)relu_src, relu_rs, seed, step_dev, (unsigned)site,
+                                thresh, scale));
   return hipGetLastError();
 }
 

@@ -315,6 +315,21 @@ parle_status parle_internal_to_bf16(hipStream_t st, const float *src, void *dst,
   return launched();
 }
 
+__global__ void k_set_step(long long *dst, long long k, int add) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) dst[0] = add ? dst[0] + 1 : k;
+}
+
+parle_status parle_internal_set_step(hipStream_t st, long long *step_dev, long long k) {
+  if (!step_dev) return PARLE_EINVAL;
+  hipLaunchKernelGGL(k_set_step, dim3(1), dim3(64), 0, st, step_dev, k, 0);
+  return launched();
+}
+parle_status parle_internal_advance_step(hipStream_t st, long long *step_dev) {
+  if (!step_dev) return PARLE_EINVAL;
+  hipLaunchKernelGGL(k_set_step, dim3(1), dim3(64), 0, st, step_dev, 0LL, 1);
+  return launched();
+}
+
 parle_status parle_internal_set_coupling(hipStream_t st, float *coupling_dev, float g, float r) {
   if (!coupling_dev) return PARLE_EINVAL;
   hipLaunchKernelGGL(k_set_coupling, dim3(1), dim3(64), 0, st, coupling_dev, g, r);

@@ -61,6 +61,15 @@ def test_layout_matches_oracle_default_sizes(model):
     assert sizes.forward_flops_per_image == nets.flops_forward_per_image(nets.arch(ORACLE_ARCH[model][0]))
 
 
+def test_lenet_with_batch_norm_layout_matches_oracle():
+    cfg = pb.make_config(model=pb.MODEL_LENET, n_replicas=2, batch=8, lenet_bn=1)
+    a = nets.arch("lenet", bn=1)
+    segs = pb.parle_query_layout(cfg)
+    assert [(s["name"], s["shape"], s["kind"]) for s in segs] == [(r["name"], r["shape"], r["kind"]) for r in nets.layout(a)]
+    sizes = pb.parle_query_sizes(cfg)
+    assert sizes.n_params == nets.n_params(a) and sizes.bn_bytes == 2 * 2 * (20 + 50 + 500) * 4
+
+
 def test_wrn_28_10_has_the_size_the_paper_quotes():
     """WRN-28-10 (Section 4.3) as arch = (16, 10, 4): about 36.5 million weights."""
     cfg = pb.make_config(model=pb.MODEL_WRN, n_replicas=3, batch=128, compute_bf16=1, arch=(16, 10, 4))
@@ -98,6 +107,8 @@ def test_layout_matches_oracle_small_sizes():
     dict(model=pb.MODEL_LENET, n_replicas=1, batch=2, in_h=6, in_w=6),
     dict(n_replicas=1, n_params=8, algorithm=2), dict(n_replicas=1, n_params=8, graph_block=2),
     dict(n_replicas=1, n_params=8, graph_block=1),      # a graph block needs a network model
+    dict(n_replicas=1, n_params=8, dropout=1.0), dict(n_replicas=1, n_params=8, dropout=-0.1),
+    dict(n_replicas=1, n_params=8, lenet_bn=2),
 ])
 def test_bad_configurations_are_rejected(kw):
     with pytest.raises(pb.ParleError) as e:

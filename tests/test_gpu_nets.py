@@ -63,7 +63,7 @@ def make(pb, a, n, B, bf16=0, seed=0, distinct_init=False, oracle_dtype=np.float
     base = dict(n_replicas=n, L=25, eta_inner=0.1, eta_outer=0.1, momentum=0.9, alpha=0.75, gamma0=0.03, rho0=1.0)
     base.update(kw)
     cfg = pb.make_config(model=model, batch=B, compute_bf16=bf16, in_h=a["H"], in_w=a["W"], in_c=a["C"],
-                         n_classes=a["classes"], arch=arch, **base)
+                         n_classes=a["classes"], arch=arch, lenet_bn=a.get("bn", 0), **base)
     lay = pb.parle_query_layout(cfg)
     assert [(s["name"], s["shape"]) for s in lay] == [(s["name"], s["shape"]) for s in onets.layout(a)]
     wi = "uniform" if a["model"] in ("mlp", "lenet") else "he_normal"
@@ -72,7 +72,7 @@ def make(pb, a, n, B, bf16=0, seed=0, distinct_init=False, oracle_dtype=np.float
     else:
         x0 = np.tile(synth.init_params(lay, seed, wi), (n, 1))
     P = pb.Parle(cfg, x0)
-    ocfg = oparle.ParleConfig(**{k: v for k, v in base.items() if k != "fuse_outer"})
+    ocfg = oparle.ParleConfig(**{k: v for k, v in base.items() if k not in ("fuse_outer", "graph_block")})
     O = otrainer.ParleNet(a, ocfg, x0, dtype=oracle_dtype)
     return P, O
 
@@ -396,3 +396,72 @@ def test_wrn_28_10_one_step_reduced_batch(gpu):
     got = P.state()
     for t in ("x", "y", "z", "x_ref"):
         check(t, got[t], getattr(O.st, t), 2e-2)
+
+
+# ---------------------------------------------------------------------------------------------
+# dropout (Section 4 rates) and LeNet with batch-norm (Section 4.2)
+# ---------------------------------------------------------------------------------------------
+DROP = {
+    "lenet_bn": (onets.arch("lenet", H=20, W=20, C=1, c1=8, c2=16, k=5, fc=40, classes=10, bn=1), 0.25),
+    "lenet": (SMALL["lenet_vec"], 0.25),
+    "allcnn": (SMALL["allcnn_vec"], 0.5),
+    "wrn": (SMALL["wrn_vec"], 0.3),
+}
+
+
+@pytest.mark.parametrize("name", list(DROP))
+def test_dropout_one_step_fp32(gpu, name):
+    """Same keep-masks on both sides (they are a function of seed, step, replica, site and element index):
+    loss, gradient and the updated state of one step agree as without dropout; the step counter keys the
+    mask, so the case starts from a restored state with k = 7."""
+    torch, pb = gpu
+    a, p = DROP[name]
+    n, B = 2, 9
+    P, O = make(pb, a, n, B, bf16=0, seed=3, distinct_init=True, dropout=p, dropout_seed=1234)
+    P.parle_set_state(7, 0, 0.03, 1.0)
+    O.st.k = 7
+    X, Y = synth.image_batches(5, 2, n, B, a["H"], a["W"], a["C"], a["classes"])
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    for k in range(2):
+        P.parle_inner_step(dev(torch, X[k]), dev(torch, Y[k]), loss)
+        ref_loss = O.inner_step(X[k], Y[k])
+        np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=1e-5)
+        got = P.state()
+        for r in range(n):
+            check(f"{name} grad[{r}] step {k}", got["grad"][r], O.last_grad[r], 1e-4)
+        for t in ("y", "z", "vy"):
+            check(f"{name} {t}", got[t], getattr(O.st, t), 1e-5)
+    # dropout really is on: the same loss without it is another number
+    l_on = onets.loss_and_grad(a, O.st.y[0], X[0][0], Y[0][0], bn_state=onets.new_bn_state(a),
+                               drop=dict(p=p, seed=1234, step=0, replica=0))[0]
+    l_off = onets.loss_and_grad(a, O.st.y[0], X[0][0], Y[0][0], bn_state=onets.new_bn_state(a))[0]
+    assert abs(l_on - l_off) > 1e-6
+    # evaluation applies no dropout
+    Xe, Ye = synth.image_batches(9, 1, 1, 11, a["H"], a["W"], a["C"], a["classes"])
+    for which in (-1, 0):
+        l, nerr, _ = P.parle_eval(which, dev(torch, Xe[0, 0]), dev(torch, Ye[0, 0]))
+        rl, rn, _ = O.eval(which, Xe[0, 0], Ye[0, 0])
+        assert abs(l - rl) <= 1e-4 * abs(rl) and nerr == rn
+
+
+@pytest.mark.parametrize("name", ["lenet_bn", "allcnn", "wrn"])
+def test_dropout_bf16_cycle_and_graph_replay(gpu, name):
+    """bf16 compute with dropout through a block of inner steps replayed from a HIP graph (the masks read the
+    step counter from device memory, so every replay draws new masks) against the oracle."""
+    torch, pb = gpu
+    a, p = DROP[name]
+    n, B, L, blocks = 2, 16, 3, 3
+    P, O = make(pb, a, n, B, bf16=1, seed=1, L=L, dropout=p, dropout_seed=77, eta_inner=0.02, graph_block=1)
+    X, Y = synth.image_batches(1, L, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    loss = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+    for b in range(blocks):                        # step by step, then record + replay, then replay
+        P.parle_inner_block(dX, dY, loss)
+        ref = np.stack([O.inner_step(X[k], Y[k]) for k in range(L)])
+        np.testing.assert_allclose(loss.cpu().numpy(), ref, rtol=3e-2)
+        P.parle_outer_step()
+        O.outer_step()
+    got = P.state()
+    for t in ("x", "y", "z", "x_ref"):
+        check(t, got[t], getattr(O.st, t), 2e-2)
+    assert P.parle_get_state()[0] == blocks * L
