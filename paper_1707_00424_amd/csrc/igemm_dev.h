@@ -221,7 +221,7 @@ constexpr uint32_t kOobOffset = 0x80000000u;  // beyond any per-replica tensor (
 
 template <typename T, int TM, int TN, bool OUT_F32>
 __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
-                                               f16v (&acc)[TM][TN], float *stage, unsigned long long *kpe = nullptr) {
+                                               f16v (&acc)[TM][TN], float *stage) {
   typedef unsigned int u2v __attribute__((ext_vector_type(2)));
   constexpr int CW = TN * 32, LD = CW + 4, CPR = CW / 4;
   constexpr int NIT = CPR / 2;                                  // vectors per lane and 32-row strip
@@ -254,7 +254,6 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
       bias_b[r] = f4{bp[0], bp[1], bp[2], bp[3]};
     }
   }
-  if (kpe) kpe[0] = clock64();
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the strip has been read out
@@ -266,7 +265,6 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
         *(f4 *)&stage[row_l * LD + tn * 32 + 8 * vg + 4 * h] = val;
       }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    if (kpe && tm == 0) kpe[1] = clock64();
     const int mbase = mrow0 + tm * 32;
 #pragma unroll
     for (int b0 = 0; b0 < NIT; b0 += BATCH) {
@@ -282,7 +280,6 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
         off[i] = ok ? pix * (uint32_t)io.ldc + (uint32_t)(ncol0 + ch_b[r]) : kOobOffset;
         val[i] = *(const f4 *)&stage[lds_b[r] + j * RPP * LD];
       }
-      if (kpe && tm == 0 && b0 == 0) kpe[2] = clock64() + 0 * (unsigned long long)val[BATCH - 1].x;
       if (io.resid) {
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
@@ -313,31 +310,68 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
             ov[i] = __builtin_amdgcn_raw_buffer_load_b64(o_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
         }
       }
-#pragma unroll
-      for (int i = 0; i < BATCH; ++i) {
-        f4 v = val[i] + bias_b[(b0 + i) % PER];
-        if (ES == 2 && io.resid) v += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, rv[i]));
+      if constexpr (PER == 1) {
+        // one uniform branch per optional stage and batch, not per vector: a taken branch costs a wavefront
+        // tens of cycles of instruction refetch
+  #pragma unroll
+        for (int i = 0; i < BATCH; ++i) val[i] += bias_b[(b0 + i) % PER];
+        if (ES == 2 && io.resid) {
+  #pragma unroll
+          for (int i = 0; i < BATCH; ++i) val[i] += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, rv[i]));
+        }
         if (io.relu) {
-          v.x = v.x > 0.f ? v.x : 0.f, v.y = v.y > 0.f ? v.y : 0.f;
-          v.z = v.z > 0.f ? v.z : 0.f, v.w = v.w > 0.f ? v.w : 0.f;
+  #pragma unroll
+          for (int i = 0; i < BATCH; ++i) {
+            f4 &v = val[i];
+            v.x = v.x > 0.f ? v.x : 0.f, v.y = v.y > 0.f ? v.y : 0.f;
+            v.z = v.z > 0.f ? v.z : 0.f, v.w = v.w > 0.f ? v.w : 0.f;
+          }
         }
         if (io.mask) {
-          const f4 mk = ES == 4 ? __builtin_bit_cast(f4, mv4[ES == 4 ? i : 0]) : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, mv[i]));
-          v.x = mk.x > 0.f ? v.x : 0.f, v.y = mk.y > 0.f ? v.y : 0.f;
-          v.z = mk.z > 0.f ? v.z : 0.f, v.w = mk.w > 0.f ? v.w : 0.f;
+  #pragma unroll
+          for (int i = 0; i < BATCH; ++i) {
+            f4 &v = val[i];
+            const f4 mk = ES == 4 ? __builtin_bit_cast(f4, mv4[ES == 4 ? i : 0]) : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, mv[i]));
+            v.x = mk.x > 0.f ? v.x : 0.f, v.y = mk.y > 0.f ? v.y : 0.f;
+            v.z = mk.z > 0.f ? v.z : 0.f, v.w = mk.w > 0.f ? v.w : 0.f;
+          }
         }
-        if (OS == 4) {
-          if (io.accumulate) v += of[i];
-          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), o_rsrc, off[i] == kOobOffset ? kOobOffset : off[i] * 4, 0, 0);
-        } else {
-          if (io.accumulate) v += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
-          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(v)), o_rsrc,
-                                                off[i] == kOobOffset ? kOobOffset : off[i] * 2, 0, 0);
+        if (io.accumulate) {
+  #pragma unroll
+          for (int i = 0; i < BATCH; ++i) val[i] += OS == 4 ? of[i] : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
+        }
+  #pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          const uint32_t bo = off[i] == kOobOffset ? kOobOffset : off[i] * OS;
+          if (OS == 4)
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, val[i]), o_rsrc, bo, 0, 0);
+          else
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(val[i])), o_rsrc, bo, 0, 0);
+        }
+      } else {
+        // 96-wide tiles (period 3): the per-vector form measured faster there
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+          f4 v = val[i] + bias_b[(b0 + i) % PER];
+          if (ES == 2 && io.resid) v += Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, rv[i]));
+          if (io.relu) {
+            v.x = v.x > 0.f ? v.x : 0.f, v.y = v.y > 0.f ? v.y : 0.f;
+            v.z = v.z > 0.f ? v.z : 0.f, v.w = v.w > 0.f ? v.w : 0.f;
+          }
+          if (io.mask) {
+            const f4 mk = ES == 4 ? __builtin_bit_cast(f4, mv4[ES == 4 ? i : 0]) : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, mv[i]));
+            v.x = mk.x > 0.f ? v.x : 0.f, v.y = mk.y > 0.f ? v.y : 0.f;
+            v.z = mk.z > 0.f ? v.z : 0.f, v.w = mk.w > 0.f ? v.w : 0.f;
+          }
+          if (io.accumulate) v += OS == 4 ? of[i] : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
+          const uint32_t bo = off[i] == kOobOffset ? kOobOffset : off[i] * OS;
+          if (OS == 4)
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), o_rsrc, bo, 0, 0);
+          else
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(v)), o_rsrc, bo, 0, 0);
         }
       }
-      if (kpe && tm == 0 && b0 == 0) kpe[3] = clock64();
     }
-    if (kpe && tm == 0) kpe[4] = clock64();
   }
 }
 

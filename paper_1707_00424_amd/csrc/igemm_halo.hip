@@ -19,12 +19,6 @@ namespace {
 using namespace igemm_dev;
 
 constexpr uint32_t kOob = 0x80000000u;
-#ifdef PARLE_KPROF
-__device__ unsigned long long g_prof[8 * 4096];
-#define KPROF_STAMP(i) if (threadIdx.x == 0) kp[i] = clock64()
-#else
-#define KPROF_STAMP(i)
-#endif
 constexpr int kHaloSlots = 400;  // LDS patch capacity in pixels (32 KB at 32 channels + padding)
 
 struct HaloGeom {
@@ -50,11 +44,6 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   T *Hs = reinterpret_cast<T *>(smem);
   T *Bs = reinterpret_cast<T *>(smem + kHaloSlots * LK * sizeof(T));  // tile i of the ring at Bs + i * BN * LK
 
-#ifdef PARLE_KPROF
-  unsigned long long kp[5], kpe[5] = {0, 0, 0, 0, 0};
-  const unsigned long long wall0 = wall_clock64();
-#endif
-  KPROF_STAMP(0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
@@ -186,13 +175,11 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   load_b(rq[1]);
   store_halo();
   load_halo(1);
-  KPROF_STAMP(1);
   store_b(0, rq[0]);
   store_b(1, rq[1]);
 #pragma unroll
   for (int i = 0; i < D; ++i) load_b(rq[i]);  // tile 2 + i; step t stores set t % D and refills it with tile t + 2 + D
   __syncthreads();
-  KPROF_STAMP(2);
   read_sub(0, 0, shift_cur, fa_a, fa_b);
   // A wavefront issues in order: LDS reads placed in a burst before the MFMAs leave the matrix unit
   // idle while they issue.  Ask the scheduler to alternate them: one fragment read after each MFMA.
@@ -241,28 +228,8 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   for (int i = 0; i < D - 1; ++i)
     if (kt + i < KT) step(kt + i, rq[i]);
   // the barrier that ends the last step: patch and weight tiles are dead, their LDS becomes the staging strips
-  KPROF_STAMP(3);
-#ifdef PARLE_KPROF
-  store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
-                                   reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>, threadIdx.x == 0 ? kpe : nullptr);
-#else
   store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
                                    reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
-#endif
-  KPROF_STAMP(4);
-#ifdef PARLE_KPROF
-  if (threadIdx.x == 0) {
-    const int id = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    if (id < 4096) {
-      for (int i = 0; i < 5; ++i) g_prof[id * 8 + i] = kp[i];
-      g_prof[id * 8 + 6] = wall_clock64() - wall0;
-      g_prof[id * 8 + 7] = ((kpe[0] - kp[3]) & 0xfff) | (((kpe[1] - kpe[0]) & 0xfff) << 12) | (((kpe[2] - kpe[1]) & 0xfff) << 24) |
-                           (((kpe[3] - kpe[2]) & 0xfff) << 36) | (((kpe[4] - kpe[3]) & 0xfff) << 48);
-      g_prof[id * 8 + 5] = (unsigned long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) |
-                           ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11)) << 32);  // HW_ID, XCC_ID
-    }
-  }
-#endif
 }
 
 template <int TN>
@@ -280,12 +247,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
 template <int TN>
 hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, const HaloGeom &hg) {
   dim3 grid((g.M + 255) / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
-#ifdef PARLE_KPROF
-  static const int dyn = getenv("PARLE_DBG_DYNLDS") ? atoi(getenv("PARLE_DBG_DYNLDS")) : 0;
-  hipLaunchKernelGGL((k_conv_halo<TN>), grid, dim3(kThreads), dyn, st, g, io, hg);
-#else
   hipLaunchKernelGGL((k_conv_halo<TN>), grid, dim3(kThreads), 0, st, g, io, hg);
-#endif
   return hipGetLastError();
 }
 
@@ -312,12 +274,6 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
 }
 
 }  // namespace
-
-#ifdef PARLE_KPROF
-extern "C" int parle_dbg_read_prof(void *out, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), bytes, 0, hipMemcpyDeviceToHost);
-}
-#endif
 
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32) {
   HaloGeom hg;
