@@ -189,6 +189,7 @@ class Var:
 class Tape:
     def __init__(self):
         self.back = []
+        self.relu_margin = np.inf  # smallest non-zero |input| any ReLU saw (diagnostic, see relu())
 
     def backward(self):
         for fn in reversed(self.back):
@@ -247,7 +248,12 @@ def linear(t, x, w, b):
 
 
 def relu(t, x):
+    """max(x, 0).  The gradient jumps where an input crosses zero, so two correct implementations in
+    different precisions may disagree there; the tape records how close the inputs came to that."""
     o = Var(np.maximum(x.v, 0))
+    nz = np.abs(x.v[x.v != 0])
+    if nz.size:
+        t.relu_margin = min(t.relu_margin, float(nz.min()))
     t.back.append(lambda: x.acc(o.g * (x.v > 0)))
     return o
 
@@ -428,10 +434,11 @@ def forward(a, P, x, t, train=True, bn_state=None, drop=None):
     raise ValueError(m)
 
 
-def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop=None):
+def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop=None, diag=None):
     """Mini-batch loss at the flat parameter vector and its gradient (same packing).
 
-    In training mode batch-norm running statistics in ``bn_state`` are updated in place.
+    In training mode batch-norm running statistics in ``bn_state`` are updated in place.  A dict passed
+    as ``diag`` receives ``relu_margin``, the smallest non-zero |input| of any ReLU in the pass.
     """
     flat = np.asarray(flat, dtype=dtype)
     t = Tape()
@@ -440,6 +447,8 @@ def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop
     logits = forward(a, P, x, t, train=True, bn_state=bn_state, drop=drop)
     loss, _ = softmax_xent(t, logits, np.asarray(labels))
     t.backward()
+    if diag is not None:
+        diag["relu_margin"] = t.relu_margin
     grad = np.concatenate([P[s["name"]].g.reshape(-1) for s in layout(a)])
     return float(loss), grad
 

@@ -17,6 +17,7 @@ class ParleNet:
         self.a, self.cfg, self.dtype = a, cfg, dtype
         self.st = parle.init_state(x0, cfg, dtype=dtype)
         self.bn = [nets.new_bn_state(a, dtype) for _ in range(cfg.n_replicas)]
+        self.relu_margin = np.inf  # smallest non-zero |ReLU input| over all steps so far (diagnostic)
 
     def inner_step(self, images, labels):
         """images ``[n, B, H, W, C]``, labels ``[n, B]``; returns the per-replica losses at y^a."""
@@ -26,8 +27,10 @@ class ParleNet:
         for a_i in range(n):
             drop = (dict(p=self.cfg.dropout, seed=self.cfg.dropout_seed, step=self.st.k, replica=a_i)
                     if self.cfg.dropout > 0 else None)
+            diag = {}
             losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.y[a_i], images[a_i], labels[a_i],
-                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop)
+                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop, diag=diag)
+            self.relu_margin = min(self.relu_margin, diag["relu_margin"])
         parle.inner_update(self.st, G, self.cfg)
         self.last_grad = G
         return losses
@@ -59,14 +62,19 @@ class ElasticNet:
         self.a, self.cfg, self.dtype = a, cfg, dtype
         self.st = elastic.init_state(x0, cfg, dtype=dtype)
         self.bn = [nets.new_bn_state(a, dtype) for _ in range(cfg.n_replicas)]
+        self.relu_margin = np.inf  # smallest non-zero |ReLU input| over all steps so far (diagnostic)
 
     def step(self, images, labels):
         n = self.cfg.n_replicas
         losses = np.zeros(n)
         G = np.zeros_like(self.st.xa)
         for a_i in range(n):
+            drop = (dict(p=self.cfg.dropout, seed=self.cfg.dropout_seed, step=self.st.k, replica=a_i)
+                    if self.cfg.dropout > 0 else None)
+            diag = {}
             losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.xa[a_i], images[a_i], labels[a_i],
-                                                     bn_state=self.bn[a_i], dtype=self.dtype)
+                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop, diag=diag)
+            self.relu_margin = min(self.relu_margin, diag["relu_margin"])
         self._el.step(self.st, G, self.cfg)
         self.last_grad = G
         return losses

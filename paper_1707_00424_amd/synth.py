@@ -95,3 +95,44 @@ def init_params(layout, seed: int, weight_init: str = "he_normal") -> np.ndarray
             raise ValueError(f"unknown segment kind {kind!r}")
         parts.append(v.astype(np.float32))
     return np.concatenate(parts) if parts else np.zeros(0, np.float32)
+
+
+def split_shards(seed: int, n_samples: int, n: int, fraction: float) -> np.ndarray:
+    """Index sets of a data set divided between ``n`` replicas (Section 5: every replica sees only a
+    subset, all subsets have the same size and every sample lies in at least one of them).
+
+    The samples are permuted once; replica ``a`` takes the cyclic window of ``ceil(fraction * n_samples)``
+    permuted samples that starts at ``a * n_samples // n``.  Needs ``n * fraction >= 1`` so that the windows
+    cover the set.  Returns int64 ``[n, m]``.
+    """
+    m = int(np.ceil(fraction * n_samples))
+    if n * m < n_samples or m > n_samples:
+        raise ValueError("subsets of this size cannot cover the data set")
+    perm = np.random.default_rng([seed, 5005]).permutation(n_samples)
+    starts = (np.arange(n) * n_samples) // n
+    return perm[(starts[:, None] + np.arange(m)[None, :]) % n_samples].astype(np.int64)
+
+
+def split_image_batches(seed: int, steps: int, n: int, batch: int, h: int, w: int, c: int,
+                        n_samples: int, fraction: float, n_classes: int = 10):
+    """Mini-batches for ``n`` replicas that each draw from their own subset of one fixed synthetic
+    data set of ``n_samples`` class-conditional Gaussian images (Section 5; 50 % for three replicas and
+    25 % for six in Table 2).  A replica walks its subset in reshuffled epochs.
+
+    Returns (images ``[steps, n, batch, h, w, c]`` float32, labels ``[steps, n, batch]`` int32,
+    sample index ``[steps, n, batch]`` int64, shards ``[n, m]`` int64).
+    """
+    means = class_means(seed, n_classes, h, w, c)
+    rng = np.random.default_rng([seed, 6006])
+    all_labels = rng.integers(0, n_classes, size=n_samples).astype(np.int32)
+    all_images = means[all_labels] + rng.standard_normal((n_samples, h, w, c)).astype(np.float32)
+    shards = split_shards(seed, n_samples, n, fraction)
+    m = shards.shape[1]
+    index = np.empty((steps, n, batch), dtype=np.int64)
+    for a in range(n):
+        order_rng = np.random.default_rng([seed, 7007, a])
+        need = steps * batch
+        walk = np.concatenate([shards[a][order_rng.permutation(m)] for _ in range(-(-need // m))])[:need]
+        index[:, a, :] = walk.reshape(steps, batch)
+    images = np.ascontiguousarray(all_images[index], dtype=np.float32)
+    return images, all_labels[index], index, shards

@@ -465,3 +465,50 @@ def test_dropout_bf16_cycle_and_graph_replay(gpu, name):
     for t in ("x", "y", "z", "x_ref"):
         check(t, got[t], getattr(O.st, t), 2e-2)
     assert P.parle_get_state()[0] == blocks * L
+
+
+@pytest.mark.parametrize("n,fraction,alg", [(3, 0.5, "parle"), (6, 0.25, "parle"), (3, 0.5, "elastic")])
+def test_split_data_between_replicas(gpu, n, fraction, alg):
+    """Section 5: every replica draws its mini-batches from its own subset of one data set (50 % each for three
+    replicas, 25 % each for six), All-CNN with dropout 0.5 and weight decay 1e-3, Parle and Elastic-SGD.  The
+    library sees nothing but per-replica batch tensors, so the bar is the usual one against the oracle.
+
+    With 8 images per batch one ReLU input that rounds to the other side of zero in fp32 moves a filter's
+    gradient by a part in a few hundred (the mask is a step function), so the seeded inputs are chosen,
+    and checked through the oracle, to keep every ReLU input further from zero than fp32 rounding reaches."""
+    torch, pb = gpu
+    a, B, L, outer = SMALL["allcnn_odd"], 8, 3, 2
+    X, Y, idx, shards = synth.split_image_batches(30, L * outer, n, B, a["H"], a["W"], a["C"], 96, fraction,
+                                                  a["classes"])
+    for r in range(n):
+        assert np.isin(idx[:, r], shards[r]).all()
+    dX, dY = dev(torch, X), dev(torch, Y)
+    loss = torch.zeros((L * outer, n), dtype=torch.float32, device="cuda")
+    ref_loss = np.zeros((L * outer, n))
+    kw = dict(L=L, dropout=0.5, dropout_seed=5, weight_decay=1e-3, eta_inner=0.05, eta_outer=0.05, scoping_B=4)
+    if alg == "parle":
+        P, O = make(pb, a, n, B, bf16=0, seed=3, distinct_init=True, **kw)
+        step, sync = O.inner_step, O.outer_step
+    else:
+        model, arch = model_pair(pb, a)
+        base = dict(n_replicas=n, momentum=0.9, rho0=1.0, **kw)
+        cfg = pb.make_config(model=model, batch=B, compute_bf16=0, in_h=a["H"], in_w=a["W"], in_c=a["C"],
+                             n_classes=a["classes"], arch=arch, algorithm=pb.ALG_ELASTIC, **base)
+        x0 = np.stack([synth.init_params(pb.parle_query_layout(cfg), 3 + 17 * i, "he_normal") for i in range(n)])
+        P, O = pb.Parle(cfg, x0), otrainer.ElasticNet(a, oparle.ParleConfig(**base), x0)
+        step, sync = O.step, O.scope
+    for k in range(L * outer):
+        P.parle_inner_step(dX[k], dY[k], loss[k])
+        ref_loss[k] = step(X[k], Y[k])
+        if (k + 1) % L == 0:
+            P.parle_outer_step()
+            sync()
+    got = P.state()
+    assert O.relu_margin > 2e-6, O.relu_margin
+    np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=1e-4, atol=2e-6)
+    if alg == "parle":
+        for t in ("x", "y", "z", "vy", "x_ref"):
+            check(t, got[t], getattr(O.st, t), 1e-5)
+    else:
+        check("xa", got["y"], O.st.xa, 1e-5)
+        check("x", got["x_ref"], O.st.x, 1e-5)
