@@ -129,6 +129,28 @@ def bench_model(name, torch, pb, blocks=2, graph=True):
     return out
 
 
+def stream_reference(torch, pb, count, reps=10):
+    """What the memory system of this GPU gives plain streams of the update kernels' access shape
+    (GB/s, bytes moved / HIP-event time): one array read, one written, a copy, and the fused inner
+    update's mix of five arrays read and three written.  `count` floats per array."""
+    src = torch.zeros(5 * count, dtype=torch.float32, device="cuda")
+    dst = torch.zeros(3 * count, dtype=torch.float32, device="cuda")
+    out = {"unit": "GB/s", "floats_per_array": count}
+    for name, (r, w) in {"read": (1, 0), "write": (0, 1), "copy": (1, 1), "read5_write3": (5, 3)}.items():
+        for _ in range(2):
+            pb.parle_k_stream_reference(r, w, count, src, dst)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            pb.parle_k_stream_reference(r, w, count, src, dst)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round((r + w) * count * 4 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,6 +164,8 @@ def main():
                          "the known-size kernel the HBM counters are scaled by")
     ap.add_argument("--no-graph", action="store_true", help="model workloads: enqueue every step instead of replaying "
                                                             "a HIP graph of L inner steps")
+    ap.add_argument("--no-stream-reference", action="store_true",
+                    help="skip the plain-stream kernels that show what HBM gives the update's access mix")
     ap.add_argument("--only-models", action="store_true",
                     help="profiling aid: skip the headline workload and print only the model timings")
     args = ap.parse_args()
@@ -220,6 +244,10 @@ def main():
     P.close()
     del P
     torch.cuda.empty_cache()
+    if not args.no_stream_reference:
+        ref = stream_reference(torch, pb, n * n_pad)
+        ref["inner_update_vs_read5_write3"] = round(achieved / ref["read5_write3"], 4)
+        out["stream_reference"] = ref
     if names:
         out["models"] = {nm: bench_model(nm, torch, pb, graph=not args.no_graph) for nm in names}
     if not args.no_cpu_baseline:

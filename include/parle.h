@@ -23,6 +23,9 @@
  * device memory and frees none.  All device work is enqueued on the HIP stream given at init
  * and is asynchronous unless stated.  Buffers must not alias.  Calls on one context must not
  * overlap in time.  Non-finite values are not trapped by the step calls (parle_eval reports them).
+ * Arguments are checked before anything is enqueued: EINVAL, EALIGN, ESIZE and ESTATE leave the
+ * context and the device state as they were.  After EHIP from a step call part of the step may have
+ * been enqueued: the state tensors are then to be restored from the caller's last copy.
  */
 #ifndef PARLE_H
 #define PARLE_H
@@ -269,6 +272,15 @@ parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, fl
 /* sum_a ||x^a - x_ref||^2 -> out_dev[0] (fp32).  partial_dev: scratch of >= 4096 doubles. */
 parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
                             double *partial_dev, float *out_dev);
+
+/* Measurement aid, not a step of the method: `reads` arrays of `count` floats are read from src_dev
+ * (laid out one after the other) and `writes` arrays of `count` floats written to dst_dev, with the
+ * access shape of the update kernels (16 bytes per lane, non-temporal) and no arithmetic that matters.
+ * The rate it reaches is what the memory system gives that mix; (reads, writes) must be (1,0), (0,1),
+ * (1,1) or (5,3), the last being the mix of the fused inner update.  count % 4 == 0; dst_dev holds
+ * max(writes, 1) * count floats (a read-only run writes nothing for finite inputs); EINVAL otherwise. */
+parle_status parle_k_stream_reference(void *hip_stream, int32_t reads, int32_t writes, int64_t count,
+                                      const float *src_dev, float *dst_dev);
 
 /* ------------------------------------------------------------------------------------------
  * The replica-grouped convolution kernels behind grad f(y^a) of (8a), one launch each.

@@ -79,6 +79,7 @@ _SIGNATURES = {
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float,
                              C.c_int32, C.c_int32, C.c_int32],
     "parle_k_spread": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_k_stream_reference": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
     "parle_k_conv_forward": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int32, C.c_void_p],
     "parle_k_conv_backward_data": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -187,6 +188,10 @@ def parle_k_outer_update(x, z, vx, y, vy, x_ref, y_bf16, eta_outer, momentum, c_
     _check(lib().parle_k_outer_update(_stream_handle(stream), n, n_pad, _ptr(x), _ptr(z), _ptr(vx), _ptr(y),
                                       _ptr(vy), _ptr(x_ref), _ptr(y_bf16), eta_outer, momentum, c_z, r, reset_flags,
                                       fuse_mean, lagged))
+
+
+def parle_k_stream_reference(reads, writes, count, src, dst, stream=None):
+    _check(lib().parle_k_stream_reference(_stream_handle(stream), reads, writes, count, _ptr(src), _ptr(dst)))
 
 
 def parle_k_spread(x, x_ref, partial, out, stream=None):

@@ -336,12 +336,11 @@ parle_status parle_inner_block(parle_ctx *ctx, const float *images_dev, const in
     }
   } else {
     hipError_t e;
-    if (!ctx->gstream) {
-      if ((e = hipStreamCreateWithFlags(&ctx->gstream, hipStreamNonBlocking)) != hipSuccess ||
-          (e = hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming)) != hipSuccess ||
-          (e = hipEventCreateWithFlags(&ctx->ev_out, hipEventDisableTiming)) != hipSuccess)
-        return hip_fail(ctx, e, "graph stream setup");
-    }
+    // each of the three is created once; a call after a failed set-up creates what is still missing
+    if ((!ctx->gstream && (e = hipStreamCreateWithFlags(&ctx->gstream, hipStreamNonBlocking)) != hipSuccess) ||
+        (!ctx->ev_in && (e = hipEventCreateWithFlags(&ctx->ev_in, hipEventDisableTiming)) != hipSuccess) ||
+        (!ctx->ev_out && (e = hipEventCreateWithFlags(&ctx->ev_out, hipEventDisableTiming)) != hipSuccess))
+      return hip_fail(ctx, e, "graph stream setup");
     if (!ctx->gexec) {
       if ((e = hipStreamBeginCapture(ctx->gstream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
         return hip_fail(ctx, e, "begin capture");
@@ -472,13 +471,15 @@ parle_status parle_set_state(parle_ctx *ctx, int64_t k, int64_t outer_done, floa
   if (!ctx) return PARLE_EINVAL;
   if (k < 0 || outer_done < 0 || !isfinite(g) || !isfinite(r) || g < 0.f || r < 0.f)
     return fail(ctx, PARLE_EINVAL, "state values must be finite and >= 0");
+  if (outer_done > k) return fail(ctx, PARLE_EINVAL, "more outer steps than inner steps");
   ctx->k = k;
   ctx->outer_done = outer_done;
   ctx->g = g;
   ctx->r = r;
   // a resumed run may go straight to an outer step only if the block it interrupts had begun
-  ctx->inner_since_outer = ctx->cfg.L > 0 ? k - outer_done * (int64_t)ctx->cfg.L : 0;
-  if (ctx->inner_since_outer < 0) ctx->inner_since_outer = 0;
+  // (outer_done <= k, so the quotient test keeps the product inside int64)
+  const int64_t L = ctx->cfg.L;
+  ctx->inner_since_outer = outer_done <= k / L ? k - outer_done * L : 0;
   if (push_coupling(ctx)) return fail(ctx, PARLE_EHIP, "coupling upload launch failed");
   if (push_step(ctx)) return fail(ctx, PARLE_EHIP, "step counter launch failed");
   return PARLE_OK;

@@ -92,6 +92,40 @@ __global__ __launch_bounds__(kThreads) void k_inner_update(const f4 *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
+// Plain streams with the access shape of the update kernels and no arithmetic to speak of: R arrays
+// read, W arrays written, 16 bytes per lane, four vectors in flight per array.  What this reaches is
+// what the memory system gives that mix of reads and writes; the update kernels are measured against it.
+// ---------------------------------------------------------------------------------------------
+template <int R, int W>
+__global__ __launch_bounds__(kThreads) void k_stream(const f4 *__restrict__ src, f4 *__restrict__ dst, int64_t n4) {
+  constexpr int U = 4;
+  const int64_t trip = (int64_t)gridDim.x * kThreads * U;
+  f4 keep = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t q0 = (int64_t)blockIdx.x * kThreads * U + threadIdx.x; q0 < n4; q0 += trip) {
+    f4 v[R > 0 ? R : 1][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * kThreads;
+#pragma unroll
+      for (int r = 0; r < R; ++r) v[r][u] = q < n4 ? ld4<true>(src + r * n4 + q) : keep;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * kThreads;
+      f4 s = {1.f, 2.f, 3.f, 4.f};
+#pragma unroll
+      for (int r = 0; r < R; ++r) s += v[r][u];
+      if (W == 0) keep += s;
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        if (q < n4) st4<true>(dst + w * n4 + q, s);
+    }
+  }
+  // read-only: the loads must stay live; a sum of finite inputs never takes this value
+  if (W == 0 && keep.x + keep.y + keep.z + keep.w == __builtin_inff()) dst[0] = keep;
+}
+
+// ---------------------------------------------------------------------------------------------
 // (8d) with eta'' = rho/n: column mean of the stacked replicas, summed in replica order.
 // ---------------------------------------------------------------------------------------------
 template <bool NT>
@@ -505,6 +539,29 @@ parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const fl
   hipLaunchKernelGGL(k_spread_partial, dim3((int)blocks), dim3(kThreads), 0, st, (const f4 *)x, (const f4 *)x_ref, n,
                      np4, partial_dev);
   hipLaunchKernelGGL(k_spread_final, dim3(1), dim3(kThreads), 0, st, (const double *)partial_dev, (int)blocks, out_dev);
+  return launched();
+}
+
+parle_status parle_k_stream_reference(void *hip_stream, int32_t reads, int32_t writes, int64_t count,
+                                      const float *src_dev, float *dst_dev) {
+  if (count < 4 || count % 4 || count > (1LL << 40)) return PARLE_ESIZE;
+  if (!dst_dev || (reads > 0 && !src_dev)) return PARLE_EINVAL;
+  if (!aligned_to(src_dev, 16) || !aligned_to(dst_dev, 16)) return PARLE_EALIGN;
+  const int64_t n4 = count / 4;
+  const dim3 grid(grid_for(n4, 4));
+  hipStream_t st = (hipStream_t)hip_stream;
+  const f4 *src = (const f4 *)src_dev;
+  f4 *dst = (f4 *)dst_dev;
+  if (reads == 1 && writes == 0)
+    hipLaunchKernelGGL((k_stream<1, 0>), grid, dim3(kThreads), 0, st, src, dst, n4);
+  else if (reads == 0 && writes == 1)
+    hipLaunchKernelGGL((k_stream<0, 1>), grid, dim3(kThreads), 0, st, src, dst, n4);
+  else if (reads == 1 && writes == 1)
+    hipLaunchKernelGGL((k_stream<1, 1>), grid, dim3(kThreads), 0, st, src, dst, n4);
+  else if (reads == 5 && writes == 3)
+    hipLaunchKernelGGL((k_stream<5, 3>), grid, dim3(kThreads), 0, st, src, dst, n4);
+  else
+    return PARLE_EINVAL;
   return launched();
 }
 

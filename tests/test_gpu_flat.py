@@ -329,3 +329,28 @@ def test_entropy_sgd_is_parle_with_one_replica(gpu):
         x = x - eta * (x - z)                                # (6c)
         assert_close("x", P.state()["x"][0], x)
         assert_close("x_ref", P.state()["x_ref"], x_before)  # the mean is taken before the replica moves
+
+
+@pytest.mark.parametrize("count", [4, 4 * 1023, 4 * (256 * 4 * 7 + 5)])
+def test_stream_reference_kernel_moves_what_it_says(gpu, count):
+    """The measurement aid: every array it claims to read reaches the result and every array it claims to
+    write is written in full and nothing beyond (ragged tails, one to many blocks)."""
+    torch, pb = gpu
+    rng = np.random.default_rng(count)
+    src = rng.standard_normal(5 * count).astype(np.float32)
+    pattern = np.tile(np.array([1, 2, 3, 4], np.float32), count // 4)
+    for r, w in [(1, 1), (5, 3), (0, 1), (1, 0)]:
+        d_src = torch.as_tensor(src).cuda()
+        d_dst = torch.full((3 * count + 8,), -7.0, dtype=torch.float32, device="cuda")
+        pb.parle_k_stream_reference(r, w, count, d_src, d_dst)
+        got = d_dst.cpu().numpy()
+        want = pattern.copy()
+        for i in range(r):                      # summed in array order, like the kernel
+            want = want + src[i * count:(i + 1) * count]
+        for j in range(w):
+            np.testing.assert_array_equal(got[j * count:(j + 1) * count], want)
+        assert (got[w * count:] == -7.0).all()
+    with pytest.raises(pb.ParleError):
+        pb.parle_k_stream_reference(2, 2, count, d_src, d_dst)
+    with pytest.raises(pb.ParleError):
+        pb.parle_k_stream_reference(1, 1, count + 2, d_src, d_dst)
