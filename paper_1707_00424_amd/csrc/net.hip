@@ -2,6 +2,8 @@
 // the caller's workspace; every op is one (or a few) grouped launches covering all replicas.
 // The backward pass walks the list in reverse with hand-written gradient routing (which tensor
 // receives which gradient, written or accumulated) fixed at plan time.
+#include <stdlib.h>
+
 #include "net.h"
 
 #include "igemm.h"
@@ -56,6 +58,19 @@ struct Net {
   int t_images = -1, t_logits = -1;
   int64_t ws_bytes = 0;
   int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0, wpartial_bytes = 0;
+  // Weight and bias gradients are leaves of the backward pass: they run on a second stream beside the
+  // chain of input gradients (own column-partial scratch; the weight partials are used there only).
+  int64_t off_colpartial_side = 0;
+  bool overlap = true;
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> dy_ready;  // one per op: its output gradient is final
+  hipEvent_t side_done = nullptr;
+  ~Net() {
+    for (hipEvent_t e : dy_ready)
+      if (e) (void)hipEventDestroy(e);
+    if (side_done) (void)hipEventDestroy(side_done);
+    if (side) (void)hipStreamDestroy(side);
+  }
   int64_t bn_floats = 0;
   int max_bn_c = 0;
   std::vector<TransposeTable> transposes;  // weights that backward-data reads transposed, in launch-sized groups
@@ -296,6 +311,7 @@ bool build_plan(Net &N, std::string &err) {
   for (const Op &op : N.ops)
     if (op.type == OP_CONV && op.bseg >= 0 && op.Cout > maxc) maxc = op.Cout;
   N.off_colpartial = N.alloc((int64_t)N.n * 1024 * 2 * (maxc > 0 ? maxc : 1) * 8);
+  N.off_colpartial_side = N.alloc((int64_t)N.n * 1024 * 2 * (maxc > 0 ? maxc : 1) * 8);
   N.off_rowcopy = N.alloc(bf ? N.n_pad * 2 : 256);  // bf16 copy of one parameter row for parle_eval
   return true;
 }
@@ -405,8 +421,16 @@ hipError_t backward(const Run &r, float *grad) {
         const void *dy = r.gptr(op.dy);
         const int64_t dy_rs = r.trs(op.dy);
         const ConvGeom gf = fwd_geom(op, r.B);
+        // leaves: on the second stream once this op's output gradient is final
+        hipStream_t lst = r.st;
+        int64_t colpartial = N.off_colpartial;
+        if (N.side) {
+          HIP_TRY(hipEventRecord(N.dy_ready[oi], r.st));
+          HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
+          lst = N.side, colpartial = N.off_colpartial_side;
+        }
         if (op.bseg >= 0)
-          HIP_TRY(launch_bias_grad(r.st, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + N.off_colpartial),
+          HIP_TRY(launch_bias_grad(lst, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + colpartial),
                                    grad + N.segs[op.bseg].offset, r.p_rs));
         {
           WgradIO io{};
@@ -420,13 +444,13 @@ hipError_t backward(const Run &r, float *grad) {
           const int64_t wsize = N.segs[op.wseg].size;
           if (S == 1) {
             io.out = grad + N.segs[op.wseg].offset, io.out_rs = r.p_rs, io.split_stride = 0;
-            HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
+            HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));
           } else {
             // never launch with more partials than the plan reserved room for
             if ((int64_t)r.n * S * wsize * 4 > N.wpartial_bytes) return hipErrorInvalidValue;
             io.out = (float *)(r.ws + N.off_wpartial), io.out_rs = (int64_t)S * wsize, io.split_stride = wsize;
-            HIP_TRY(launch_wgrad(r.st, N.dtype, r.n, gf, io));
-            HIP_TRY(launch_reduce_partials(r.st, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
+            HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));
+            HIP_TRY(launch_reduce_partials(lst, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
           }
         }
         if (op.need_dx) {
@@ -480,6 +504,34 @@ hipError_t backward(const Run &r, float *grad) {
       }
     }
   }
+  if (N.side) {  // join: the update that follows reads every gradient
+    HIP_TRY(hipEventRecord(N.side_done, N.side));
+    HIP_TRY(hipStreamWaitEvent(r.st, N.side_done, 0));
+  }
+  return hipSuccess;
+}
+
+// The second stream and its events are made on the first training step outside a stream capture (making
+// them is not a stream operation and is not allowed while the calling thread records one).
+hipError_t make_side_stream(Net &N, hipStream_t st) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  HIP_TRY(hipStreamIsCapturing(st, &cs));
+  if (cs != hipStreamCaptureStatusNone) return hipSuccess;  // this step runs on one stream
+  hipStream_t side = nullptr;
+  HIP_TRY(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
+  std::vector<hipEvent_t> ev(N.ops.size() + 1, nullptr);
+  for (hipEvent_t &e : ev) {
+    if (hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming)) {
+      for (hipEvent_t d : ev)
+        if (d) (void)hipEventDestroy(d);
+      (void)hipStreamDestroy(side);
+      return rc;
+    }
+  }
+  N.side_done = ev.back();
+  ev.pop_back();
+  N.dy_ready = ev;
+  N.side = side;
   return hipSuccess;
 }
 
@@ -499,6 +551,7 @@ Net *net_create(const parle_config &cfg, const Arch &a, const std::vector<Segmen
     delete N;
     return nullptr;
   }
+  if (const char *e = getenv("PARLE_OVERLAP_WGRAD")) N->overlap = atoi(e) != 0;
   return N;
 }
 
@@ -517,6 +570,7 @@ hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const v
                           float *loss_dev, const long long *step_dev) {
   Net &N = *net;
   if (N.cfg.dropout > 0.f && !step_dev) return hipErrorInvalidValue;
+  if (N.overlap && !N.side) HIP_TRY(make_side_stream(N, st));
   Run r{net, st, N.n, N.B, params, N.dtype ? params_bf16 : (const void *)params, N.n_pad, (char *)workspace, images,
         step_dev};
   if (N.dtype == 1) {
