@@ -15,18 +15,38 @@ namespace {
 
 using namespace igemm_dev;
 typedef short s4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+template <int BYTES>
+struct GatherVec;
+template <>
+struct GatherVec<16> {
+  typedef u4 type;
+  static __device__ __forceinline__ u4 zero() { return u4{0u, 0u, 0u, 0u}; }
+};
+template <>
+struct GatherVec<8> {
+  typedef u2 type;
+  static __device__ __forceinline__ u2 zero() { return u2{0u, 0u}; }
+};
 
 // ---------------------------------------------------------------------------------------------
 // forward / backward-data, vector path
 // ---------------------------------------------------------------------------------------------
-template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32>
+// GB: bytes per gather (16, or 8 for channel counts that are only a multiple of half a vector, e.g. 50 fp32
+// channels); the LDS layout and the fragment reads are the same for both.
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32, int GB>
 __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const GemmIO io) {
-  constexpr int VW = 16 / sizeof(T);
+  constexpr int VW = 16 / sizeof(T);   // elements per fragment read
+  constexpr int GV = GB / sizeof(T);   // elements per gather
   constexpr int BK = 4 * VW;
   constexpr int LK = BK + VW;
+  constexpr int LPR = BK / GV;         // lanes that share a tile row
+  constexpr int RPP = kThreads / LPR;  // tile rows per pass
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   static_assert(BM % 64 == 0, "row tile must be a multiple of 64");
-  constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
+  constexpr int A_IT = BM / RPP, B_IT = (BN + RPP - 1) / RPP;
+  typedef typename GatherVec<GB>::type gvec;
   __shared__ __attribute__((aligned(16))) T As[2][BM * LK];
   __shared__ __attribute__((aligned(16))) T Bs[2][BN * LK];
 
@@ -36,14 +56,14 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const T *__restrict__ in = (const T *)io.in + rep * io.in_rs;
   const T *__restrict__ w = (const T *)io.w + rep * io.w_rs;
-  const int lrow = tid >> 2, lkv = tid & 3;
+  const int lrow = tid / LPR, lkv = tid % LPR;
   const int PQ = g.P * g.Q;
 
   int a_base[A_IT];
   uint32_t a_hmask[A_IT], a_wmask[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
-    const int m = m0 + i * 64 + lrow;
+    const int m = m0 + i * RPP + lrow;
     const bool ok = m < g.M;
     const uint32_t mm = ok ? m : 0;
     const int b = fdiv(mm, g.dPQ), rem = mm - b * PQ;
@@ -64,10 +84,10 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
   int b_row[B_IT];
 #pragma unroll
   for (int i = 0; i < B_IT; ++i) {
-    const int row = i * 64 + lrow, nrow = n0 + row;
+    const int row = i * RPP + lrow, nrow = n0 + row;
     b_row[i] = (row < BN && nrow < g.N) ? nrow * g.K : -1;
   }
-  int kk = lkv * VW, kr, ks, kc;
+  int kk = lkv * GV, kr, ks, kc;
   {
     const uint32_t rs = fdiv(kk, g.dCc);
     kc = kk - rs * g.Cc;
@@ -75,23 +95,23 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
     ks = rs - kr * g.S;
   }
 
-  const u4 zero4 = {0u, 0u, 0u, 0u};
+  const gvec zero4 = GatherVec<GB>::zero();
 
   // Loads of steps past the end are fully masked (tap row index beyond the window, kk >= K), so
   // the pipeline below may always run two steps ahead without touching memory out of range.
-  auto load_tiles = [&](u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
+  auto load_tiles = [&](gvec (&areg)[A_IT], gvec (&breg)[B_IT]) {
     const int toff = g.sr * (((kr >> g.dshift) * g.Win + (ks >> g.dshift)) * g.Cc) + kc;
     const int krs = kr < 31 ? kr : 31;
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const bool ok = ((a_hmask[i] >> krs) & (a_wmask[i] >> ks) & 1u) != 0;
-      areg[i] = ok ? *(const u4 *)(in + a_base[i] + toff) : zero4;
+      areg[i] = ok ? *(const gvec *)(in + a_base[i] + toff) : zero4;
     }
     const bool kok = kk < g.K;
 #pragma unroll
-    for (int i = 0; i < B_IT; ++i) breg[i] = (kok && b_row[i] >= 0) ? *(const u4 *)(w + b_row[i] + kk) : zero4;
+    for (int i = 0; i < B_IT; ++i) breg[i] = (kok && b_row[i] >= 0) ? *(const gvec *)(w + b_row[i] + kk) : zero4;
   };
-  // branch-free: Cc >= VW, so one step of BK = 4*VW crosses at most four tap boundaries
+  // branch-free: Cc >= VW (applicability test), so one step of BK = 4*VW crosses at most four tap boundaries
   auto advance_k = [&]() {
     kk += BK;
     kc += BK;
@@ -105,13 +125,13 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
       kr += wrap_s ? 1 : 0;
     }
   };
-  auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const u4 (&breg)[B_IT]) {
+  auto store_tiles = [&](int buf, const gvec (&areg)[A_IT], const gvec (&breg)[B_IT]) {
 #pragma unroll
-    for (int i = 0; i < A_IT; ++i) *(u4 *)&As[buf][(i * 64 + lrow) * LK + lkv * VW] = areg[i];
+    for (int i = 0; i < A_IT; ++i) *(gvec *)&As[buf][(i * RPP + lrow) * LK + lkv * GV] = areg[i];
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
-      const int row = i * 64 + lrow;
-      if (BN % 64 == 0 || row < BN) *(u4 *)&Bs[buf][row * LK + lkv * VW] = breg[i];
+      const int row = i * RPP + lrow;
+      if (BN % RPP == 0 || row < BN) *(gvec *)&Bs[buf][row * LK + lkv * GV] = breg[i];
     }
   };
 
@@ -127,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
   // step t, the registers of step t+1 go to the other LDS buffer after them, one barrier per step.
   // Two register sets, so the loop is unrolled by two; the body has no data-dependent branches.
   const int KT = (g.K + BK - 1) / BK;
-  u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
+  gvec a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
   load_tiles(a0, b0);
   advance_k();
   load_tiles(a1, b1);
@@ -441,14 +461,14 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
   }
 }
 
-template <typename T, int WM, int WN, int TM, int TN>
+template <typename T, int WM, int WN, int TM, int TN, int GB = 16>
 hipError_t run_v(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   dim3 grid((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, replicas);
   if (out_f32)
-    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, true, GB>), grid, dim3(kThreads), 0, st, g, io);
   else
-    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+    hipLaunchKernelGGL((k_igemm_v<T, WM, WN, TM, TN, false, GB>), grid, dim3(kThreads), 0, st, g, io);
   return hipGetLastError();
 }
 
@@ -479,9 +499,20 @@ bool tall_ok(const ConvGeom &g, int bn, int replicas) {
 
 }  // namespace
 
-bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
+namespace {
+bool full_vector_ok(int dtype, const ConvGeom &g, const GemmIO &io) {
   const int vw = dtype ? 8 : 4;
   return io.vecA && io.vecB && g.Cc % vw == 0 && g.K % vw == 0 && g.R <= 16 && g.S <= 16;
+}
+// fp32 channel counts that are even but no multiple of four (LeNet's 50): 8-byte gathers
+bool half_vector_ok(int dtype, const ConvGeom &g, const GemmIO &io) {
+  return dtype == 0 && g.Cc % 2 == 0 && g.Cc >= 4 && g.R <= 16 && g.S <= 16 && aligned_to(io.in, 8) &&
+         io.in_rs % 2 == 0 && aligned_to(io.w, 8) && io.w_rs % 2 == 0;
+}
+}  // namespace
+
+bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
+  return full_vector_ok(dtype, g, io) || half_vector_ok(dtype, g, io);
 }
 
 // Uniform-tap kernel: a whole contraction step inside one tap, vector epilogue, 32-bit byte offsets.
@@ -495,7 +526,7 @@ hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replic
                              const GemmIO &io) {
   ConvGeom g = g_in;
   g.plp = g.plq = 0;
-  if (uniform_ok(dtype, g, io)) {
+  if (full_vector_ok(dtype, g, io) && uniform_ok(dtype, g, io)) {
     // stride-2 backward data on power-of-two images: rows grouped by parity class
     auto log2_exact = [](int v) {
       int l = 0;
@@ -516,7 +547,13 @@ hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replic
     if (n <= 192 || n % 192 == 0) return run_u<bf16_t, 2, 2, 2, 3>(st, out_f32, replicas, g, io);
     return run_u<bf16_t, 2, 2, 2, 4>(st, out_f32, replicas, g, io);
   }
-  if (dtype == 0) return run_v<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
+  if (dtype == 0) {
+    if (!full_vector_ok(dtype, g, io))
+      return g.N <= 32 ? run_v<float, 4, 1, 1, 1, 8>(st, out_f32, replicas, g, io)
+                       : run_v<float, 2, 2, 1, 1, 8>(st, out_f32, replicas, g, io);
+    return g.N <= 32 ? run_v<float, 4, 1, 1, 1>(st, out_f32, replicas, g, io)
+                     : run_v<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
+  }
   const int n = g.N;
   if (n <= 32) return run_v<bf16_t, 4, 1, 1, 1>(st, out_f32, replicas, g, io);
   if (n <= 64)

@@ -81,6 +81,8 @@ CASES = [
     (2, 4, 12, 12, 3, 16, 3, 1, 1),     # whole contraction in one tile (K = 27): first-layer kernel, ragged last tile
     (2, 3, 14, 14, 1, 20, 5, 1, 0),     # same, K = 25, one input channel, 'valid' 5x5
     (1, 5, 16, 16, 3, 96, 3, 2, 1),     # same, stride 2, three 32-channel tiles
+    (2, 4, 12, 12, 20, 50, 5, 1, 0),    # LeNet's second conv: backward-data over 50 channels (8-byte gathers in fp32)
+    (1, 3, 8, 8, 6, 40, 3, 1, 1),       # forward over 6 channels: 8-byte gathers, 64-wide tile with a ragged edge
 ]
 
 
