@@ -294,17 +294,25 @@ bool build_plan(Net &N, std::string &err) {
       N.want_grad(op.in);
     }
   }
-  for (const Op &op : N.ops) {
-    if (op.type != OP_CONV || !op.need_dx) continue;
-    if (N.transposes.empty() || N.transposes.back().count == TransposeTable::kMax) {
-      N.transposes.emplace_back();
-      N.transposes.back().count = 0;
+  // two kinds of tables: layers whose rows fill whole 16-byte vectors (tiled, vector kernel) and the rest
+  for (int vec = 1; vec >= 0; --vec) {
+    bool open = false;
+    for (const Op &op : N.ops) {
+      if (op.type != OP_CONV || !op.need_dx) continue;
+      if ((int)transpose_vector_ok(N.dtype, op.Cout, op.Cin, N.segs[op.wseg].offset) != vec) continue;
+      if (!open || N.transposes.back().count == TransposeTable::kMax) {
+        N.transposes.emplace_back();
+        N.transposes.back().count = 0;
+        N.transposes.back().vec = vec;
+        open = true;
+      }
+      TransposeTable &t = N.transposes.back();
+      const int i = t.count++;
+      t.cout[i] = op.Cout, t.rs[i] = op.R * op.R, t.cin[i] = op.Cin;
+      t.src_off[i] = N.segs[op.wseg].offset, t.dst_off[i] = op.wt_off;
     }
-    TransposeTable &t = N.transposes.back();
-    const int i = t.count++;
-    t.cout[i] = op.Cout, t.rs[i] = op.R * op.R, t.cin[i] = op.Cin;
-    t.src_off[i] = N.segs[op.wseg].offset, t.dst_off[i] = op.wt_off;
   }
+  for (TransposeTable &t : N.transposes) transpose_table_finish(t);
   N.wpartial_bytes = wpartial > 0 ? wpartial : 256;
   N.off_wpartial = N.alloc(N.wpartial_bytes);
   int maxc = N.max_bn_c;

@@ -60,7 +60,15 @@ struct TransposeTable {
   int count;
   int cout[kMax], rs[kMax], cin[kMax];
   long long src_off[kMax], dst_off[kMax];
+  // vec != 0: every entry has Cout, Cin and src_off that are multiples of the 16-byte vector width of the
+  // dtype, one workgroup per 64 x 64 tile, tiles of entry i are workgroups tile_begin[i] .. tile_begin[i+1]-1
+  int vec;
+  int tile_begin[kMax + 1];
 };
+// True when a layer may enter a table with vec != 0.
+bool transpose_vector_ok(int dtype, int cout, int cin, long long src_off);
+// Fills tile_begin (call once the entries of a vec table are complete).
+void transpose_table_finish(TransposeTable &tab);
 hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
                                        long long p_rs, void *dst_base);
 // Dropout with keep-masks from a counter-based hash (definition in parle.h).  `count` elements per replica;

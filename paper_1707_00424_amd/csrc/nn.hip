@@ -638,6 +638,48 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose_all(const Transpo
   }
 }
 
+// Same transposition for layers whose channel counts fill whole 16-byte vectors: one workgroup per tile (found
+// by a scan of the table's running tile counts), 16-byte loads along Cin and 16-byte stores along Cout; only
+// the column reads from LDS are element-wise.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_weight_transpose_vec(const TransposeTable tab, const T *__restrict__ params,
+                                                                   long long p_rs, char *__restrict__ dst_base) {
+  constexpr int VW = 16 / sizeof(T), VPR = 64 / VW;  // vectors per tile row
+  __shared__ __attribute__((aligned(16))) T tile[64][64 + VW];
+  int layer = 0;
+  while (layer + 1 < tab.count && (int)blockIdx.x >= tab.tile_begin[layer + 1]) ++layer;
+  const int rep = blockIdx.y;
+  const int Cout = tab.cout[layer], RS = tab.rs[layer], Cin = tab.cin[layer];
+  const long long total = (long long)Cout * RS * Cin;
+  const T *src = params + rep * p_rs + tab.src_off[layer];
+  T *dst = (T *)(dst_base + tab.dst_off[layer]) + (long long)rep * total;
+  const int tci = (Cin + 63) / 64;
+  const int t = blockIdx.x - tab.tile_begin[layer];
+  const int rs = t % RS, tt = t / RS;
+  const int co0 = (tt / tci) * 64, ci0 = (tt % tci) * 64;
+#pragma unroll
+  for (int v = threadIdx.x; v < 64 * VPR; v += kThreads) {
+    const int r = v / VPR, c = (v % VPR) * VW;
+    const int co = co0 + r, ci = ci0 + c;
+    if (co < Cout && ci < Cin) *(uint4 *)&tile[r][c] = *(const uint4 *)&src[((long long)co * RS + rs) * Cin + ci];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int v = threadIdx.x; v < 64 * VPR; v += kThreads) {
+    const int r = v / VPR, c = (v % VPR) * VW;  // r: input channel of the row, c: first of VW output channels
+    const int ci = ci0 + r, co = co0 + c;
+    if (ci < Cin && co < Cout) {
+      union {
+        T e[VW];
+        uint4 q;
+      } out;
+#pragma unroll
+      for (int e = 0; e < VW; ++e) out.e[e] = tile[c + e][r];
+      *(uint4 *)&dst[((long long)ci * RS + rs) * Cout + co] = out.q;
+    }
+  }
+}
+
 __device__ __forceinline__ unsigned mix32(unsigned x) {
   x ^= x >> 16;
   x *= 0x7FEB352Du;
@@ -919,9 +961,32 @@ hipError_t launch_weight_transpose(hipStream_t st, int dtype, int n, int Cout, i
   return hipGetLastError();
 }
 
+bool transpose_vector_ok(int dtype, int cout, int cin, long long src_off) {
+  const int vw = dtype ? 8 : 4;
+  return cout % vw == 0 && cin % vw == 0 && src_off % vw == 0;
+}
+
+void transpose_table_finish(TransposeTable &tab) {
+  tab.tile_begin[0] = 0;
+  for (int i = 0; i < tab.count; ++i)
+    tab.tile_begin[i + 1] = tab.tile_begin[i] + ((tab.cout[i] + 63) / 64) * ((tab.cin[i] + 63) / 64) * tab.rs[i];
+}
+
 hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
                                        long long p_rs, void *dst_base) {
   if (tab.count < 1) return hipSuccess;
+  if (tab.vec) {
+    const int vw = dtype ? 8 : 4;
+    if (p_rs % vw || !aligned_to(params, 16) || !aligned_to(dst_base, 16) || tab.tile_begin[tab.count] < 1)
+      return hipErrorInvalidValue;
+    dim3 vgrid(tab.tile_begin[tab.count], n);
+    DISPATCH_T(dtype,
+               hipLaunchKernelGGL(k_weight_transpose_vec<float>, vgrid, dim3(kThreads), 0, st, tab, (const float *)params,
+                                  p_rs, (char *)dst_base),
+               hipLaunchKernelGGL(k_weight_transpose_vec<bf16_t>, vgrid, dim3(kThreads), 0, st, tab,
+                                  (const bf16_t *)params, p_rs, (char *)dst_base));
+    return hipGetLastError();
+  }
   dim3 grid(256, tab.count, n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_weight_transpose_all<float>, grid, dim3(kThreads), 0, st, tab, (const float *)params, p_rs,
