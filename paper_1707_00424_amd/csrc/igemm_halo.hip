@@ -12,6 +12,8 @@
 // Step order: channel chunk outer, tap inner (the contraction order is free).  The weight tile of
 // each step is double-buffered in LDS with a two-step register prefetch; the next chunk's patch
 // is prefetched into registers during the R*S steps of the current one.
+#include <stdlib.h>
+
 #include "igemm_dev.h"
 
 namespace {
@@ -28,25 +30,33 @@ struct HaloGeom {
   int slots;       // nimg * HR * HC
   int omin_h, omin_w;  // smallest tap offset (input row = output row + offset)
   FastDiv dImg, dHC, dRows;  // by HR*HC, HC and TH*Q (no integer division on the device)
+  int tiles, nb, bn;  // pixel tiles, column blocks and their width in channels (set with the grid)
 };
 
+// LDS of a workgroup with TN column tiles: patch + a ring of three weight tiles; the epilogue reuses the same
+// bytes as its staging strips
 template <int TN>
-__device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &io, const HaloGeom &hg) {
+constexpr int halo_lds_bytes() {
+  constexpr int pipe = (kHaloSlots + 3 * TN * 32) * (32 + 8) * 2;
+  constexpr int stage = 4 * kStageFloats<TN> * (int)sizeof(float);
+  return pipe > stage ? pipe : stage;
+}
+
+// `tile`, `col`: pixel tile and column block of this workgroup; column blocks before it are hg.bn wide.
+template <int TN>
+__device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &io, const HaloGeom &hg, char *smem,
+                                               int tile, int col) {
   typedef bf16_t T;
   constexpr int VW = 8, BK = 32, LK = BK + VW;
   constexpr int TM = 2, BM = 256, BN = TN * 32;  // four wavefronts stacked along the pixel axis
   constexpr int B_IT = (BN + 63) / 64;
   constexpr int H_IT = (kHaloSlots * 4 + kThreads - 1) / kThreads;
-  // patch + a ring of three weight tiles; the epilogue reuses the same LDS as its staging strips
-  constexpr int kPipeBytes = (kHaloSlots + 3 * BN) * LK * (int)sizeof(T);
-  constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
-  __shared__ __attribute__((aligned(16))) char smem[kPipeBytes > kStageBytes ? kPipeBytes : kStageBytes];
   T *Hs = reinterpret_cast<T *>(smem);
   T *Bs = reinterpret_cast<T *>(smem + kHaloSlots * LK * sizeof(T));  // tile i of the ring at Bs + i * BN * LK
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int m0 = tile * BM, n0 = col * hg.bn;
   const int lrow = tid >> 2, lkv = tid & 3;
   const int PQ = g.P * g.Q;
   const int RS = g.R * g.S;
@@ -232,22 +242,52 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
                                    reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
 }
 
-template <int TN>
+// Workgroups are handed to the eight XCDs in turn, so ids that differ by 8 share an L2: the column blocks
+// of one pixel tile get such ids.  They run at the same time on the same XCD, the patch is fetched into
+// that L2 once, and their partial output rows meet there before they are written back.
+__device__ __forceinline__ bool halo_block(const HaloGeom &hg, int &tile, int &col) {
+  const int per_group = 8 * hg.nb;
+  const int group = blockIdx.x / per_group, within = blockIdx.x - group * per_group;
+  tile = group * 8 + (within & 7), col = within >> 3;
+  return tile < hg.tiles;  // the grid is padded to whole groups
+}
+
+// Column blocks 0 .. nb-2 are TN tiles wide, the last one TL <= TN tiles (160 channels = 96 + 64,
+// 320 = 128 + 128 + 64): a narrower last block multiplies no padding.
+template <int TN, int TL>
 __global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const GemmIO io, const HaloGeom hg) {
-  conv_halo_body<TN>(g, io, hg);
+  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<TN>()];
+  int tile, col;
+  if (!halo_block(hg, tile, col)) return;
+  if (TL != TN && col == hg.nb - 1)
+    conv_halo_body<TL>(g, io, hg, smem, tile, col);
+  else
+    conv_halo_body<TN>(g, io, hg, smem, tile, col);
 }
 // 64 output channels: few enough registers for three workgroups per compute unit, which hides more of
 // the prologue and epilogue of one workgroup behind the matrix work of the others
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void k_conv_halo_n64(const ConvGeom g,
                                                                                                    const GemmIO io,
                                                                                                    const HaloGeom hg) {
-  conv_halo_body<2>(g, io, hg);
+  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<2>()];
+  int tile, col;
+  if (!halo_block(hg, tile, col)) return;
+  conv_halo_body<2>(g, io, hg, smem, tile, col);
 }
 
-template <int TN>
-hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, const HaloGeom &hg) {
-  dim3 grid((g.M + 255) / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
-  hipLaunchKernelGGL((k_conv_halo<TN>), grid, dim3(kThreads), 0, st, g, io, hg);
+// grid of `tiles` pixel tiles x `nb` column blocks of `bn` channels (the last may be narrower), laid out in
+// groups of 8 tiles (see halo_block)
+dim3 halo_grid(const ConvGeom &g, int bn, int replicas, HaloGeom &hg) {
+  hg.tiles = (g.M + 255) / 256;
+  hg.bn = bn;
+  hg.nb = (g.N + bn - 1) / bn;
+  return dim3((hg.tiles + 7) / 8 * 8 * hg.nb, 1, replicas);
+}
+
+template <int TN, int TL>
+hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, HaloGeom hg) {
+  const dim3 grid = halo_grid(g, TN * 32, replicas, hg);
+  hipLaunchKernelGGL((k_conv_halo<TN, TL>), grid, dim3(kThreads), 0, st, g, io, hg);
   return hipGetLastError();
 }
 
@@ -287,10 +327,17 @@ hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, con
   if (!make_halo_geom(g, hg)) return hipErrorInvalidValue;
   const int n = g.N;
   if (n <= 64) {
-    dim3 grid((g.M + 255) / 256, (g.N + 63) / 64, replicas);
+    const dim3 grid = halo_grid(g, 64, replicas, hg);
     hipLaunchKernelGGL(k_conv_halo_n64, grid, dim3(kThreads), 0, st, g, io, hg);
     return hipGetLastError();
   }
-  if (n <= 96 || n % 96 == 0) return run_halo<3>(st, replicas, g, io, hg);
-  return run_halo<4>(st, replicas, g, io, hg);
+  // 96- or 128-wide column blocks, whichever pads the output channels least (ties go to the wider tile);
+  // a last block of at most 64 channels runs two tiles wide
+  const int pad3 = (n + 95) / 96 * 96, pad4 = (n + 127) / 128 * 128;
+  if (pad3 < pad4) {
+    const int last = n - (pad3 - 96);
+    return last <= 64 ? run_halo<3, 2>(st, replicas, g, io, hg) : run_halo<3, 3>(st, replicas, g, io, hg);
+  }
+  const int last = n - (pad4 - 128);
+  return last <= 64 ? run_halo<4, 2>(st, replicas, g, io, hg) : run_halo<4, 4>(st, replicas, g, io, hg);
 }

@@ -83,6 +83,7 @@ CASES = [
     (1, 5, 16, 16, 3, 96, 3, 2, 1),     # same, stride 2, three 32-channel tiles
     (2, 4, 12, 12, 20, 50, 5, 1, 0),    # LeNet's second conv: backward-data over 50 channels (8-byte gathers in fp32)
     (1, 3, 8, 8, 6, 40, 3, 1, 1),       # forward over 6 channels: 8-byte gathers, 64-wide tile with a ragged edge
+    (1, 2, 16, 16, 160, 320, 3, 1, 1),  # WRN-28-10 widths: 320 outputs = 2 x 128 + 64, 160 (backward-data) = 96 + 64
 ]
 
 
