@@ -83,7 +83,7 @@ MODEL_WORKLOADS = {
 MFMA_PEAK_TFLOPS = {0: 157.3, 1: 2500.0}
 
 
-def bench_model(name, torch, pb, blocks=2, graph=True):
+def bench_model(name, torch, pb, blocks=2, graph=True, progress=False):
     """Replica-images/s of the whole step (forward, loss, backward, fused update; outer step every
     L = 25) on synthetic class-conditional Gaussian images, batch 128 per replica."""
     from paper_1707_00424_amd import synth
@@ -102,14 +102,21 @@ def bench_model(name, torch, pb, blocks=2, graph=True):
     dX, dY = torch.as_tensor(X).cuda(), torch.as_tensor(Y).cuda()
     loss = torch.zeros((Lm, n), dtype=torch.float32, device="cuda")
     # warm-up: the first block call runs step by step, the second records the HIP graph and replays it
-    for _ in range(2):
+    def say(what):                      # profiler runs with counters are slow: show that blocks complete
+        if progress:
+            torch.cuda.synchronize()
+            print(f"bench.py: {name}: {what}", file=sys.stderr, flush=True)
+
+    for w in range(2):
         P.parle_inner_block(dX, dY, loss)
         P.parle_outer_step()
+        say(f"warm-up block {w + 1} of 2 done")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for blk in range(blocks):
         P.parle_inner_block(dX, dY, loss)
         P.parle_outer_step()
+        say(f"timed block {blk + 1} of {blocks} done")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     steps = blocks * Lm
@@ -166,6 +173,9 @@ def main():
                                                             "a HIP graph of L inner steps")
     ap.add_argument("--no-stream-reference", action="store_true",
                     help="skip the plain-stream kernels that show what HBM gives the update's access mix")
+    ap.add_argument("--progress", action="store_true",
+                    help="model workloads: report every finished block of 25 steps on stderr (synchronises: "
+                         "for profiler runs, not for timing)")
     ap.add_argument("--only-models", action="store_true",
                     help="profiling aid: skip the headline workload and print only the model timings")
     args = ap.parse_args()
@@ -183,7 +193,7 @@ def main():
     torch.cuda.set_device(0)
     names = list(MODEL_WORKLOADS) if args.models == "all" else [m for m in args.models.split(",") if m and m != "none"]
     if args.only_models:
-        print(json.dumps({"models": {nm: bench_model(nm, torch, pb, graph=not args.no_graph) for nm in names}}))
+        print(json.dumps({"models": {nm: bench_model(nm, torch, pb, graph=not args.no_graph, progress=args.progress) for nm in names}}))
         return
     n, N = N_REPLICAS, N_PARAMS
     cfg = pb.make_config(model=pb.MODEL_FLAT, n_replicas=n, n_params=N, L=L, eta_inner=0.1, eta_outer=0.1,
@@ -249,7 +259,7 @@ def main():
         ref["inner_update_vs_read5_write3"] = round(achieved / ref["read5_write3"], 4)
         out["stream_reference"] = ref
     if names:
-        out["models"] = {nm: bench_model(nm, torch, pb, graph=not args.no_graph) for nm in names}
+        out["models"] = {nm: bench_model(nm, torch, pb, graph=not args.no_graph, progress=args.progress) for nm in names}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
