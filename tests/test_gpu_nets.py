@@ -512,3 +512,26 @@ def test_split_data_between_replicas(gpu, n, fraction, alg):
     else:
         check("xa", got["y"], O.st.xa, 1e-5)
         check("x", got["x_ref"], O.st.x, 1e-5)
+
+
+@pytest.mark.parametrize("name,bf16", [("allcnn_vec", 1), ("wrn_vec", 0)])
+def test_second_stream_changes_nothing(gpu, name, bf16, monkeypatch):
+    """Weight and bias gradients run on a second stream beside the input-gradient chain; switching that off
+    (one stream) must give the same bits: same kernels, same fixed-order reductions, only their timing differs."""
+    torch, pb = gpu
+    a, n, B, L = SMALL[name], 3, 16, 3
+    X, Y = synth.image_batches(2, L, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    states = []
+    for overlap in ("1", "0"):
+        monkeypatch.setenv("PARLE_OVERLAP_WGRAD", overlap)      # read when the context is created
+        P, _ = make(pb, a, n, B, bf16=bf16, seed=4, distinct_init=True, L=L)
+        loss = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+        for k in range(L):
+            P.parle_inner_step(dX[k], dY[k], loss[k])
+        P.parle_outer_step()
+        got = P.state()
+        states.append((loss.cpu().numpy(), got["grad"], got["y"], got["x"]))
+        P.close()
+    for u, v in zip(*states):
+        np.testing.assert_array_equal(u, v)
