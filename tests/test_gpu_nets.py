@@ -535,3 +535,39 @@ def test_second_stream_changes_nothing(gpu, name, bf16, monkeypatch):
         P.close()
     for u, v in zip(*states):
         np.testing.assert_array_equal(u, v)
+
+
+@pytest.mark.parametrize("model", ["allcnn", "wrn"])
+def test_full_size_blocks_from_the_graph_equal_step_by_step(gpu, model):
+    """The launch configuration that bench.py times (n = 3, batch 128, 3x32x32, bf16 compute, blocks of L = 25
+    inner steps replayed from a HIP graph, fused outer step, scoping on for WRN) against a second context that
+    enqueues every step: bit for bit, over a step-by-step block, the recording block and a replayed one.
+    (The step-by-step path is the one test_config4_config5_full_size_step holds against the oracle.)"""
+    torch, pb = gpu
+    a, n, B, L, blocks = onets.arch(model), 3, 128, 25, 3
+    mdl, arch = model_pair(pb, a)
+    mk = lambda graph: pb.make_config(model=mdl, n_replicas=n, batch=B, L=L, compute_bf16=1, in_h=a["H"], in_w=a["W"],
+                                      in_c=a["C"], n_classes=a["classes"], arch=arch, eta_inner=0.01, eta_outer=0.01,
+                                      gamma0=0.03, rho0=1.0, fuse_outer=1, scoping_B=390 if model == "wrn" else 0,
+                                      graph_block=graph)
+    x0 = np.tile(synth.init_params(pb.parle_query_layout(mk(0)), 0, "he_normal"), (n, 1))
+    Pg, Ps = pb.Parle(mk(1), x0), pb.Parle(mk(0), x0)
+    X, Y = synth.image_batches(0, L, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    loss_g = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+    loss_s = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+    for b in range(blocks):
+        Pg.parle_inner_block(dX, dY, loss_g)
+        for k in range(L):
+            Ps.parle_inner_step(dX[k], dY[k], loss_s[k])
+        assert torch.equal(loss_g, loss_s), b
+        assert np.isfinite(loss_g.cpu().numpy()).all()
+        Pg.parle_outer_step()
+        Ps.parle_outer_step()
+        for t in ("x", "y", "z", "vy", "vx", "x_ref", "grad"):
+            assert torch.equal(getattr(Pg, t), getattr(Ps, t)), (b, t)
+        if model == "wrn":
+            assert torch.equal(Pg.bn_stats, Ps.bn_stats), b
+        loss_g.zero_()
+    assert Pg.parle_get_state() == Ps.parle_get_state()
+    assert Pg.parle_get_state()[0] == blocks * L
