@@ -4,6 +4,8 @@
 // receives which gradient, written or accumulated) fixed at plan time.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "net.h"
 
 #include "igemm.h"
@@ -34,6 +36,7 @@ struct Op {
   bool dx_accumulate = false;
   int dy = -1;             // tensor whose gradient is this op's output gradient (default: out)
   int64_t wt_off = -1;     // transposed weights (bytes)
+  int64_t col_off = -1;    // per-tap products of the two-pass backward-data (bytes), -1 = direct kernel
   // pool
   bool pool_relu_mask = false;
   // bn
@@ -263,7 +266,7 @@ bool build_plan(Net &N, std::string &err) {
       return false;
   }
   // gradients, transposed weights, scratch
-  int64_t wpartial = 0;
+  int64_t wpartial = 0, col_bytes = 0;
   for (Op &op : N.ops) {
     if (op.wseg < 0 && op.type == OP_CONV) {
       err = "internal: weight segment not found";
@@ -279,6 +282,12 @@ bool build_plan(Net &N, std::string &err) {
       if (op.need_dx) {
         N.want_grad(op.in);
         op.wt_off = N.alloc((int64_t)N.n * wsize * N.esize);
+        // few input channels under a wide window (LeNet's second convolution: 20 channels, 25 taps): as a
+        // direct implicit GEMM the pass has 20 output columns on 32-wide fp32 MFMA tiles and a contraction
+        // of 1250; as dy x W (500 columns, contraction 50) plus a gather over the window it is a fraction
+        if (N.dtype == 0 && op.stride == 1 && op.R > 1 && op.Cin <= 32 && op.R * op.R * op.Cin >= 128 &&
+            (int64_t)N.B * op.Ho * op.Wo * op.Cin * op.R * op.R < (1LL << 31))
+          col_bytes = std::max(col_bytes, (int64_t)N.n * N.B * op.Ho * op.Wo * op.Cin * op.R * op.R * 4), op.col_off = 0;
       }
       // the complete forward geometry: the split plan depends on which kernel variant will run
       const ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
@@ -310,11 +319,17 @@ bool build_plan(Net &N, std::string &err) {
       const int i = t.count++;
       t.cout[i] = op.Cout, t.rs[i] = op.R * op.R, t.cin[i] = op.Cin;
       t.src_off[i] = N.segs[op.wseg].offset, t.dst_off[i] = op.wt_off;
+      t.tap_major[i] = op.col_off >= 0;
     }
   }
   for (TransposeTable &t : N.transposes) transpose_table_finish(t);
   N.wpartial_bytes = wpartial > 0 ? wpartial : 256;
   N.off_wpartial = N.alloc(N.wpartial_bytes);
+  if (col_bytes > 0) {  // one buffer for all layers that take the two-pass route (they run one after the other)
+    const int64_t off = N.alloc(col_bytes);
+    for (Op &op : N.ops)
+      if (op.col_off == 0) op.col_off = off;
+  }
   int maxc = N.max_bn_c;
   for (const Op &op : N.ops)
     if (op.type == OP_CONV && op.bseg >= 0 && op.Cout > maxc) maxc = op.Cout;
@@ -464,6 +479,24 @@ hipError_t backward(const Run &r, float *grad) {
         if (op.need_dx) {
           void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
+          if (op.col_off > 0) {
+            // col = dy x W: the transposed weights, here ordered [RS][Cin][Cout], are the [N][K] operand as they lie
+            const int RS = op.R * op.R, M = r.B * op.Ho * op.Wo, Ncol = op.Cin * RS;
+            const ConvGeom gc = conv_fwd_geom(ConvShape{M, 1, 1, op.Cout, Ncol, 1, 1, 0});
+            float *col = (float *)(r.ws + op.col_off);
+            GemmIO io{};
+            io.in = dy, io.in_rs = dy_rs;
+            io.w = wt, io.w_rs = wsize;
+            io.out = col, io.out_rs = (int64_t)M * Ncol, io.ldc = Ncol;
+            io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
+            io.vecB = io.vecA;
+            io.in_bytes = io.in_rs * N.esize;
+            HIP_TRY(launch_igemm(r.st, N.dtype, true, r.n, gc, io));
+            HIP_TRY(launch_col2im(r.st, r.n, r.B, op.Hin, op.Win, op.Cin, op.R, op.pad, col, io.out_rs,
+                                  op.mask_in ? (const float *)r.tptr(op.in) : nullptr, r.trs(op.in), op.dx_accumulate,
+                                  (float *)r.gptr(op.in), r.trs(op.in)));
+            break;
+          }
           const ConvGeom gb = bwd_geom(op, r.B);
           GemmIO io{};
           io.in = dy, io.in_rs = dy_rs;

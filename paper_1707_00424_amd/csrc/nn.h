@@ -60,6 +60,7 @@ struct TransposeTable {
   int count;
   int cout[kMax], rs[kMax], cin[kMax];
   long long src_off[kMax], dst_off[kMax];
+  int tap_major[kMax];  // != 0: rows of the result ordered [RS][Cin] instead of [Cin][RS] (two-pass backward-data)
   // vec != 0: every entry has Cout, Cin and src_off that are multiples of the 16-byte vector width of the
   // dtype, one workgroup per 64 x 64 tile, tiles of entry i are workgroups tile_begin[i] .. tile_begin[i+1]-1
   int vec;
@@ -71,6 +72,11 @@ bool transpose_vector_ok(int dtype, int cout, int cin, long long src_off);
 void transpose_table_finish(TransposeTable &tab);
 hipError_t launch_weight_transpose_all(hipStream_t st, int dtype, int n, const TransposeTable &tab, const void *params,
                                        long long p_rs, void *dst_base);
+// fp32, stride 1: dx[b, h, w, ci] (+)= sum over the window taps of col[(b, h+pad-r, w+pad-s)][(r*R + s)*Cin + ci],
+// zeroed where mask <= 0 (mask like dx, may be NULL).  col: [n][B*P*Q][Cin*R*R], P = H + 2 pad - R + 1.
+hipError_t launch_col2im(hipStream_t st, int n, int B, int H, int W, int Cin, int R, int pad, const float *col,
+                         long long col_rs, const float *mask, long long mask_rs, int accumulate, float *dx,
+                         long long dx_rs);
 // Dropout with keep-masks from a counter-based hash (definition in parle.h).  `count` elements per replica;
 // step_dev holds the inner-step counter.  out = keep ? in * scale : 0; with relu_src the result is also
 // zeroed where relu_src <= 0 (backward through a ReLU that the dropout followed).  thresh = 0 copies.

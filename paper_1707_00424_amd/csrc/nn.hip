@@ -632,9 +632,47 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose_all(const Transpo
 #pragma unroll 4
     for (int r = ty; r < 64; r += 4) {
       const int ci = ci0 + r, co = co0 + tx;
-      if (ci < Cin && co < Cout) dst[((long long)ci * RS + rs) * Cout + co] = tile[tx][r];
+      if (ci < Cin && co < Cout)
+        dst[(tab.tap_major[layer] ? (long long)rs * Cin + ci : (long long)ci * RS + rs) * Cout + co] = tile[tx][r];
     }
     __syncthreads();
+  }
+}
+
+// Second half of a backward-data pass that goes through per-tap products: col[m][(r*S + s)*Cin + ci] holds
+// dy[m] . w[:, r, s, ci] for every output pixel m = (b, p, q) (a plain matrix product over the output
+// channels); the input gradient of pixel (h, w) is the sum of the entries whose window covers it,
+//   dx[b, h, w, ci] = sum_{r, s} col[(b, h + pad - r, w + pad - s)][(r*S + s)*Cin + ci]   (stride 1),
+// taken in tap order.  One thread per (pixel, channel): neighbouring threads read neighbouring channels of
+// one tap; a row of col is read by the R*S pixels around it.
+__global__ __launch_bounds__(kThreads) void k_col2im(int B, int H, int W, int Cin, int R, int pad, int P, int Q,
+                                                     const float *__restrict__ col, long long col_rs,
+                                                     const float *__restrict__ mask, long long mask_rs, int accumulate,
+                                                     float *__restrict__ dx, long long dx_rs) {
+  const int rep = blockIdx.y;
+  const long long total = (long long)B * H * W * Cin;
+  const int RS = R * R, ldc = Cin * RS;
+  const float *cp = col + rep * col_rs;
+  const float *mp = mask ? mask + rep * mask_rs : nullptr;
+  float *op = dx + rep * dx_rs;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int ci = (int)(i % Cin);
+    long long pix = i / Cin;
+    const int w = (int)(pix % W);
+    pix /= W;
+    const int h = (int)(pix % H), b = (int)(pix / H);
+    float sum = 0.f;
+    for (int r = 0; r < R; ++r) {
+      const int p = h + pad - r;
+      if (p < 0 || p >= P) continue;
+      for (int s2 = 0; s2 < R; ++s2) {
+        const int q = w + pad - s2;
+        if (q < 0 || q >= Q) continue;
+        sum += cp[((long long)(b * P + p) * Q + q) * ldc + (r * R + s2) * Cin + ci];
+      }
+    }
+    if (mp && !(mp[i] > 0.f)) sum = 0.f;
+    op[i] = accumulate ? op[i] + sum : sum;
   }
 }
 
@@ -675,7 +713,7 @@ __global__ __launch_bounds__(kThreads) void k_weight_transpose_vec(const Transpo
       } out;
 #pragma unroll
       for (int e = 0; e < VW; ++e) out.e[e] = tile[c + e][r];
-      *(uint4 *)&dst[((long long)ci * RS + rs) * Cout + co] = out.q;
+      *(uint4 *)&dst[(tab.tap_major[layer] ? (long long)rs * Cin + ci : (long long)ci * RS + rs) * Cout + co] = out.q;
     }
   }
 }
@@ -805,6 +843,17 @@ hipError_t launch_maxpool_bwd(hipStream_t st, int dtype, int n, int B, int H, in
                                 (const float *)dout, dout_rs, (float *)din, din_rs, relu_mask),
              hipLaunchKernelGGL(k_maxpool_bwd<bf16_t>, grid, dim3(kThreads), 0, st, B, H, W, C, (const bf16_t *)in,
                                 in_rs, (const bf16_t *)dout, dout_rs, (bf16_t *)din, din_rs, relu_mask));
+  return hipGetLastError();
+}
+
+hipError_t launch_col2im(hipStream_t st, int n, int B, int H, int W, int Cin, int R, int pad, const float *col,
+                         long long col_rs, const float *mask, long long mask_rs, int accumulate, float *dx,
+                         long long dx_rs) {
+  const int P = H + 2 * pad - R + 1, Q = W + 2 * pad - R + 1;
+  if (P < 1 || Q < 1) return hipErrorInvalidValue;
+  dim3 grid(blocks_for((long long)B * H * W * Cin, 65535), n);
+  hipLaunchKernelGGL(k_col2im, grid, dim3(kThreads), 0, st, B, H, W, Cin, R, pad, P, Q, col, col_rs, mask, mask_rs,
+                     accumulate, dx, dx_rs);
   return hipGetLastError();
 }
 
