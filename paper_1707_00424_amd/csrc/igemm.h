@@ -35,6 +35,10 @@ struct ConvGeom {
   // tile share the taps that a stride-2 backward-data gather can reach.  Only kernels that say so
   // honour it; the launchers set it, not the callers.
   int plp, plq;
+  // With plp, plq >= 4 and pblk != 0 the order inside an image is instead: block of 16 x 16 pixels
+  // (row-major over the blocks), parity class, position (i, j) of the 8 x 8 grid inside the block, i.e.
+  // pixel (16*bi + 2*i + class/2, 16*bj + 2*j + class%2): a 256-row tile is one block, 64 rows per class.
+  int pblk;
 };
 
 struct GemmIO {
@@ -114,5 +118,8 @@ hipError_t launch_wgrad_smallk(hipStream_t st, int replicas, const ConvGeom &g, 
 bool wgrad9_applicable(int dtype, const ConvGeom &g);
 int wgrad9_plan(int replicas, const ConvGeom &g, int *chunk_out);
 hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
+// Backward-data of stride-2 3x3 pad-1 layers, four parity classes per workgroup (igemm_dgrad2.hip).
+bool dgrad_s2_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
+hipError_t launch_dgrad_s2(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);
 // Rows of M per split so that the launch has enough workgroups; returns the split count.
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out);

@@ -77,6 +77,11 @@ __device__ __forceinline__ uint32_t row_pixel(const ConvGeom &g, uint32_t m) {
   if (g.plq == 0) return m;
   const int lpq = g.plp + g.plq;
   const uint32_t b = m >> lpq, mi = m & ((1u << lpq) - 1u);
+  if (g.pblk) {
+    const uint32_t blk = mi >> 8, cls = (mi >> 6) & 3u, i = (mi >> 3) & 7u, j = mi & 7u;
+    const uint32_t bi = blk >> (g.plq - 4), bj = blk & ((1u << (g.plq - 4)) - 1u);
+    return (b << lpq) | ((16u * bi + 2u * i + (cls >> 1)) << g.plq) | (16u * bj + 2u * j + (cls & 1u));
+  }
   const uint32_t cls = mi >> (lpq - 2), rem = mi & ((1u << (lpq - 2)) - 1u);
   const uint32_t ph = rem >> (g.plq - 1), qh = rem & ((1u << (g.plq - 1)) - 1u);
   return (b << lpq) | ((2u * ph + (cls >> 1)) << g.plq) | (2u * qh + (cls & 1u));

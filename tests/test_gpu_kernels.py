@@ -84,6 +84,9 @@ CASES = [
     (2, 4, 12, 12, 20, 50, 5, 1, 0),    # LeNet's second conv: backward-data over 50 channels (8-byte gathers in fp32)
     (1, 3, 8, 8, 6, 40, 3, 1, 1),       # forward over 6 channels: 8-byte gathers, 64-wide tile with a ragged edge
     (1, 2, 16, 16, 160, 320, 3, 1, 1),  # WRN-28-10 widths: 320 outputs = 2 x 128 + 64, 160 (backward-data) = 96 + 64
+    (2, 2, 32, 32, 64, 96, 3, 2, 1),    # stride-2 backward-data, four parity classes per workgroup: 2 x 2 blocks per image
+    (1, 3, 16, 32, 96, 64, 3, 2, 1),    # same, image not square, 96-wide column block
+    (1, 2, 16, 16, 160, 32, 3, 2, 1),   # same, 160 channels = 96 + a ragged second block
 ]
 
 
