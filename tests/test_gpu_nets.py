@@ -4,8 +4,9 @@ The device path (C ABI) and the CPU oracle (float64) get the same seeded images,
 parameters.  Bars:
   * fp32 compute: every state tensor within 1e-5 (relative 2-norm and max-abs relative to the largest
     entry) after L inner steps and the outer step -- the bound the workload definition states;
-    raw gradients of one step within 1e-4 (their rounding error is attenuated by eta and by the
-    size of the parameters before it reaches the state, see DESIGN.md);
+    raw gradients of one step within 1e-4 (fp32 rounding of a gradient is a few 1e-5 of its size; on its
+    way into the state it is multiplied by eta <= 0.1 and set against parameters that are larger than one
+    step of them, which is what keeps the state inside 1e-5);
   * bf16 compute (fp32 master weights): losses and state tensors within 2e-2.
 """
 import numpy as np
