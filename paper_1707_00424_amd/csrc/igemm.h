@@ -118,6 +118,9 @@ hipError_t launch_wgrad_smallk(hipStream_t st, int replicas, const ConvGeom &g, 
 bool wgrad9_applicable(int dtype, const ConvGeom &g);
 int wgrad9_plan(int replicas, const ConvGeom &g, int *chunk_out);
 hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
+// Plain products with few output tiles: the contraction split over the wavefronts of a workgroup (igemm_ksplit.hip).
+bool gemm_ksplit_applicable(int dtype, int replicas, const ConvGeom &g, const GemmIO &io);
+hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
 // Backward-data of stride-2 3x3 pad-1 layers, four parity classes per workgroup (igemm_dgrad2.hip).
 bool dgrad_s2_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
 hipError_t launch_dgrad_s2(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);

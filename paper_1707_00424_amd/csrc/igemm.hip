@@ -375,6 +375,7 @@ hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, c
   if (conv_smallk_applicable(dtype, g, io)) return launch_conv_smallk(st, dtype, out_f32, replicas, g, io);
   if (conv_halo_applicable(dtype, g, io, out_f32)) return launch_conv_halo(st, replicas, g, io);
   if (dgrad_s2_applicable(dtype, g, io, out_f32)) return launch_dgrad_s2(st, replicas, g, io);
+  if (gemm_ksplit_applicable(dtype, replicas, g, io)) return launch_gemm_ksplit(st, dtype, out_f32, replicas, g, io);
   if (igemm_fast_applicable(dtype, g, io)) return launch_igemm_fast(st, dtype, out_f32, replicas, g, io);
   if (dtype == 0) return run_igemm<float, 2, 2, 1, 1>(st, out_f32, replicas, g, io);
   switch (bf16_ntile(g.N)) {
