@@ -88,14 +88,14 @@ hipError_t run_ksplit(hipStream_t st, bool out_f32, int replicas, const ConvGeom
 }  // namespace
 
 // A plain product (1 x 1 window, stride 1, no padding: row m of the product reads row m of `in`) whose 64 x 64
-// tiles would not fill half the chip, with a contraction long enough to split.
+// tiles would leave the chip at one workgroup per compute unit or less, with a contraction long enough to split.
 bool gemm_ksplit_applicable(int dtype, int replicas, const ConvGeom &g, const GemmIO &io) {
   const int vw = dtype ? 8 : 4;
   if (g.R != 1 || g.S != 1 || g.sp != 1 || g.off != 0 || g.dshift != 0 || g.Hin != g.P || g.Win != g.Q) return false;
   if (!io.vecA || !io.vecB || g.K % vw != 0 || g.K < 8 * vw) return false;
   if (io.in_bytes <= 0 || io.in_bytes >= (1LL << 31) || (long long)g.N * g.K * (dtype ? 2 : 4) >= (1LL << 31)) return false;
   const long long tiles64 = (long long)((g.M + 63) / 64) * ((g.N + 63) / 64) * replicas;
-  return tiles64 <= 128;
+  return tiles64 <= 256;
 }
 
 hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
