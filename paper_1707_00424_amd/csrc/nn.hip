@@ -130,38 +130,42 @@ __global__ __launch_bounds__(kThreads) void k_maxpool_fwd(int B, int H, int W, i
   }
 }
 
+// One thread per pooled element: it reads its 2 x 2 window once, finds the first maximum (row-major window
+// order, as the forward pass) and writes all four input gradients; the last row / column of an odd-sized
+// image belongs to no window and gets zeros from the threads of the neighbouring windows.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_maxpool_bwd(int B, int H, int W, int C, const T *__restrict__ in,
                                                           long long in_rs, const T *__restrict__ dout,
                                                           long long dout_rs, T *__restrict__ din, long long din_rs,
                                                           int relu_mask) {
   const int Ho = H / 2, Wo = W / 2;
-  const long long total = (long long)B * H * W * C;
+  const long long total = (long long)B * Ho * Wo * C;
   const T *x = in + blockIdx.y * in_rs;
   const T *dy = dout + blockIdx.y * dout_rs;
   T *dx = din + blockIdx.y * din_rs;
+  const long long rowC = (long long)W * C;
   for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
-    const int c = i % C;
+    const int c = (int)(i % C);
     long long t = i / C;
-    const int w = t % W;
-    t /= W;
-    const int h = t % H;
-    const int b = t / H;
-    const int ho = h >> 1, wo = w >> 1;
-    float g = 0.f;
-    if (ho < Ho && wo < Wo) {
-      const long long base = (((long long)b * H + 2 * ho) * W + 2 * wo) * C + c;
-      const float v0 = ldf<T>(x, base), v1 = ldf<T>(x, base + C), v2 = ldf<T>(x, base + (long long)W * C),
-                  v3 = ldf<T>(x, base + (long long)W * C + C);
-      int arg = 0;
-      float m = v0;
-      if (v1 > m) m = v1, arg = 1;
-      if (v2 > m) m = v2, arg = 2;
-      if (v3 > m) m = v3, arg = 3;
-      const int mine = (h & 1) * 2 + (w & 1);
-      if (mine == arg && (!relu_mask || m > 0.f)) g = ldf<T>(dy, (((long long)b * Ho + ho) * Wo + wo) * C + c);
-    }
-    stf<T>(dx, i, g);
+    const int wo = (int)(t % Wo);
+    t /= Wo;
+    const int ho = (int)(t % Ho), b = (int)(t / Ho);
+    const long long base = (((long long)b * H + 2 * ho) * W + 2 * wo) * C + c;
+    const float v0 = ldf<T>(x, base), v1 = ldf<T>(x, base + C), v2 = ldf<T>(x, base + rowC), v3 = ldf<T>(x, base + rowC + C);
+    int arg = 0;
+    float m = v0;
+    if (v1 > m) m = v1, arg = 1;
+    if (v2 > m) m = v2, arg = 2;
+    if (v3 > m) m = v3, arg = 3;
+    const float g = (!relu_mask || m > 0.f) ? ldf<T>(dy, i) : 0.f;
+    stf<T>(dx, base, arg == 0 ? g : 0.f);
+    stf<T>(dx, base + C, arg == 1 ? g : 0.f);
+    stf<T>(dx, base + rowC, arg == 2 ? g : 0.f);
+    stf<T>(dx, base + rowC + C, arg == 3 ? g : 0.f);
+    const bool last_w = (W & 1) && wo == Wo - 1, last_h = (H & 1) && ho == Ho - 1;
+    if (last_w) stf<T>(dx, base + 2 * C, 0.f), stf<T>(dx, base + rowC + 2 * C, 0.f);
+    if (last_h) stf<T>(dx, base + 2 * rowC, 0.f), stf<T>(dx, base + 2 * rowC + C, 0.f);
+    if (last_w && last_h) stf<T>(dx, base + 2 * rowC + 2 * C, 0.f);
   }
 }
 
@@ -837,7 +841,8 @@ hipError_t launch_maxpool_fwd(hipStream_t st, int dtype, int n, int B, int H, in
 hipError_t launch_maxpool_bwd(hipStream_t st, int dtype, int n, int B, int H, int W, int C, const void *in,
                               long long in_rs, const void *dout, long long dout_rs, void *din, long long din_rs,
                               int relu_mask) {
-  dim3 grid(blocks_for((long long)B * H * W * C, 65535), n);
+  if (H < 2 || W < 2) return hipErrorInvalidValue;  // no window: the plans never pool such a tensor
+  dim3 grid(blocks_for((long long)B * (H / 2) * (W / 2) * C, 65535), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_maxpool_bwd<float>, grid, dim3(kThreads), 0, st, B, H, W, C, (const float *)in, in_rs,
                                 (const float *)dout, dout_rs, (float *)din, din_rs, relu_mask),
