@@ -101,7 +101,8 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   u4 hreg[H_IT];
   auto load_halo = [&](int chunk) {
     const uint32_t cb = (uint32_t)(chunk * BK * (int)sizeof(T));
-    const bool live = chunk * BK < g.Cc;
+    // channel counts that are no multiple of 32: the vectors of the last chunk beyond the row are zeros
+    const bool live = chunk * BK + (tid & 3) * VW < g.Cc;
 #pragma unroll
     for (int it = 0; it < H_IT; ++it)
       hreg[it] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (live && h_off[it] != kOob) ? h_off[it] + cb : kOob, 0, 0);
@@ -115,10 +116,10 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   };
   // weight tile of step t: channels of chunk t / RS at tap t % RS
   int ld_chunk = 0, ld_tap = 0, ld_t = 0;
-  const int KT = (g.Cc / BK) * RS;
+  const int KT = ((g.Cc + BK - 1) / BK) * RS;
   auto load_b = [&](u4 (&breg)[B_IT]) {
     const uint32_t kb = (uint32_t)((ld_tap * g.Cc + ld_chunk * BK) * (int)sizeof(T));
-    const bool live = ld_t < KT;
+    const bool live = ld_t < KT && ld_chunk * BK + lkv * VW < g.Cc;  // not into the next tap's weights
 #pragma unroll
     for (int i = 0; i < B_IT; ++i)
       breg[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (live && b_off[i] != kOob) ? b_off[i] + kb : kOob, 0, 0);
@@ -317,7 +318,7 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
 
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32) {
   HaloGeom hg;
-  return dtype == 1 && !out_f32 && io.vecA && io.vecB && g.R * g.S > 1 && g.Cc % 32 == 0 && g.N % 4 == 0 &&
+  return dtype == 1 && !out_f32 && io.vecA && io.vecB && g.R * g.S > 1 && g.Cc % 8 == 0 && g.Cc >= 16 && g.N % 4 == 0 &&
          io.ldc % 4 == 0 && io.in_bytes > 0 && io.in_bytes < (1LL << 31) && (long long)g.M * io.ldc * 4 < (1LL << 31) && (long long)g.N * g.K * 2 < (1LL << 31) &&
          g.M >= 256 && make_halo_geom(g, hg);
 }

@@ -87,6 +87,8 @@ CASES = [
     (2, 2, 32, 32, 64, 96, 3, 2, 1),    # stride-2 backward-data, four parity classes per workgroup: 2 x 2 blocks per image
     (1, 3, 16, 32, 96, 64, 3, 2, 1),    # same, image not square, 96-wide column block
     (1, 2, 16, 16, 160, 32, 3, 2, 1),   # same, 160 channels = 96 + a ragged second block
+    (2, 2, 16, 16, 16, 64, 3, 1, 1),    # patch path with half a channel chunk (the first block of the residual networks)
+    (1, 2, 16, 16, 40, 48, 3, 1, 1),    # same, one full chunk and a ragged one, in both directions
     (3, 128, 1, 1, 784, 128, 1, 1, 0),  # the MLP's first layer: contraction split over the wavefronts of a workgroup
     (2, 20, 1, 1, 504, 10, 1, 1, 0),    # same, ten outputs, contraction not a multiple of the four quarters
 ]
