@@ -121,6 +121,9 @@ hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const 
 // Plain products with few output tiles: the contraction split over the wavefronts of a workgroup (igemm_ksplit.hip).
 bool gemm_ksplit_applicable(int dtype, int replicas, const ConvGeom &g, const GemmIO &io);
 hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+// fp32 backward-weight with at most 32 output channels and a window of at most 32 values (igemm_ksplit.hip).
+bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g);
+hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Backward-data of stride-2 3x3 pad-1 layers, four parity classes per workgroup (igemm_dgrad2.hip).
 bool dgrad_s2_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
 hipError_t launch_dgrad_s2(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);

@@ -101,3 +101,95 @@ bool gemm_ksplit_applicable(int dtype, int replicas, const ConvGeom &g, const Ge
 hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   return dtype ? run_ksplit<bf16_t>(st, out_f32, replicas, g, io) : run_ksplit<float>(st, out_f32, replicas, g, io);
 }
+
+// ---------------------------------------------------------------------------------------------
+// fp32 backward-weight of a first layer: at most 32 output channels and a whole window of at most 32 values
+// (LeNet's first convolution: 20 x 25).  The result is one 32 x 32 MFMA tile; the generic kernel would multiply
+// a 64 x 64 tile of mostly padding.  A workgroup takes the rows of one split, its four wavefronts a quarter
+// each; an MFMA (32 x 32 x 2) contracts two rows, whose operands are one float of dy and one gathered float of
+// the input per lane, loaded straight into registers (the window position of a lane is fixed, its pixel
+// advances by two per MFMA).  The four partial tiles are added in wavefront order.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+__global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, const WgradIO io) {
+  __shared__ __attribute__((aligned(16))) float part[3][64 * 16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rep = blockIdx.z / io.splits, split = blockIdx.z % io.splits;
+  const int col = lane & 31, h = lane >> 5;  // output channel n (operand dy) and window value k (operand x)
+  const float *dy = (const float *)io.dy + rep * io.dy_rs;
+  const float *x = (const float *)io.x + rep * io.x_rs;
+  // rows of this wavefront: a quarter of the split, in pairs
+  const int r_begin = split * io.chunk, r_end = min(g.M, r_begin + io.chunk);
+  const int quarter = ((r_end - r_begin + 7) / 8) * 2;  // even
+  const int m0 = r_begin + wave * quarter, m1 = min(r_end, m0 + quarter);
+  // window position of this lane
+  const bool k_ok = col < g.K, n_ok = col < g.N;
+  const int kk = k_ok ? col : 0;
+  const int rs = (int)fdiv((uint32_t)kk, g.dCc), kc = kk - rs * g.Cc;
+  const int kr = (int)fdiv((uint32_t)rs, g.dS), ks = rs - kr * g.S;
+  // pixel of row m0 + h
+  const int PQ = g.P * g.Q;
+  int m = m0 + h;
+  const uint32_t mm = m < g.M ? m : 0;
+  int b = (int)fdiv(mm, g.dPQ), rem = (int)mm - b * PQ;
+  int p = (int)fdiv((uint32_t)rem, g.dQ), q = rem - p * g.Q;
+
+  f16v acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  constexpr int U = 8;
+  for (int mj = m0; mj < m1; mj += 2 * U) {
+    float av[U], bv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool live = m < m1;
+      const int ih = p * g.sp + g.off + kr, iw = q * g.sp + g.off + ks;
+      const bool tap_ok = ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win;
+      av[u] = (live && n_ok) ? dy[(long long)m * g.N + col] : 0.f;
+      bv[u] = (live && k_ok && tap_ok) ? x[((long long)(b * g.Hin + ih) * g.Win + iw) * g.Cc + kc] : 0.f;
+      m += 2, q += 2;
+      while (q >= g.Q) {
+        q -= g.Q;
+        if (++p == g.P) p = 0, ++b;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], acc, 0, 0, 0);
+  }
+  if (wave) {
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd)
+      *(f4 *)&part[wave - 1][lane * 16 + qd * 4] = f4{acc[qd * 4], acc[qd * 4 + 1], acc[qd * 4 + 2], acc[qd * 4 + 3]};
+  }
+  __syncthreads();
+  if (wave) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      const f4 t = *(const f4 *)&part[w][lane * 16 + qd * 4];
+      acc[qd * 4] += t.x, acc[qd * 4 + 1] += t.y, acc[qd * 4 + 2] += t.z, acc[qd * 4 + 3] += t.w;
+    }
+  // register v of a lane: output channel n = 8*(v/4) + 4*h + v%4, window value k = col
+  float *out = io.out + rep * io.out_rs + split * io.split_stride;
+  if (k_ok) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int n = 8 * (v >> 2) + 4 * h + (v & 3);
+      if (n < g.N) out[(long long)n * g.K + col] = acc[v];
+    }
+  }
+}
+
+}  // namespace
+
+bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g) {
+  return dtype == 0 && g.K <= 32 && g.N <= 32 && g.dshift == 0 && g.sr == 1 && g.M >= 1 && g.Q >= 1;
+}
+
+hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
+  dim3 grid(1, 1, replicas * io.splits);
+  hipLaunchKernelGGL(k_wgrad_small_f32, grid, dim3(kThreads), 0, st, g, io);
+  return hipGetLastError();
+}
