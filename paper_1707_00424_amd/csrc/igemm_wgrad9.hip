@@ -241,7 +241,10 @@ __global__ __launch_bounds__(NT * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 }
 
 int wg9_tiles(int nt32) {  // dy tiles per workgroup for N/32 tiles in all
-  for (int nt = 5; nt >= 2; --nt)
+  // four first: two workgroups of four wavefronts fill a compute unit's eight wavefront slots (two per SIMD at
+  // this kernel's register count), one of five leaves three of them empty
+  static const int order[4] = {4, 5, 3, 2};
+  for (int nt : order)
     if (nt32 % nt == 0) return nt;
   return nt32 == 1 ? 1 : 0;
 }
