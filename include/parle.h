@@ -20,9 +20,12 @@
  * GENERAL RULES.  Plain C types only.  Every function returns a parle_status and never throws.
  * Pointers named "dev" are DEVICE pointers owned by the caller (any allocator; PyTorch tensors in
  * the bundled binding); pointers named "host" are host pointers.  The library allocates no
- * device memory and frees none.  All device work is enqueued on the HIP stream given at init
- * and is asynchronous unless stated.  Buffers must not alias.  Calls on one context must not
- * overlap in time.  Non-finite values are not trapped by the step calls (parle_eval reports them).
+ * device memory and frees none.  All device work is ordered on the HIP stream given at init and is
+ * asynchronous unless stated: a context of a network model owns up to two more streams of default priority
+ * (weight- and bias-gradient kernels run beside the rest of the backward pass; blocks of inner steps are
+ * replayed from a graph), tied to the init stream by events on both sides, so the caller sees the usual
+ * stream order and needs no synchronisation of its own.  Buffers must not alias.  Calls on one context must
+ * not overlap in time.  Non-finite values are not trapped by the step calls (parle_eval reports them).
  * Arguments are checked before anything is enqueued: EINVAL, EALIGN, ESIZE and ESTATE leave the
  * context and the device state as they were.  After EHIP from a step call part of the step may have
  * been enqueued: the state tensors are then to be restored from the caller's last copy.
