@@ -327,7 +327,15 @@ hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, con
   HaloGeom hg;
   if (!make_halo_geom(g, hg)) return hipErrorInvalidValue;
   const int n = g.N;
-  if (n <= 64) {
+  // A launch that wide blocks leave below two workgroups per compute unit runs 64-wide ones when those fill
+  // the chip in one round at more than two and at most three per unit: every SIMD then holds three wavefronts
+  // instead of one or two, which overlap each other's LDS reads and MFMAs (128 channels on 16 x 16 images,
+  // three replicas of 128: -8 %).  With fewer narrow workgroups than that the wide ones are as fast or faster.
+  constexpr int kCus = 256;
+  const long long tiles = (g.M + 255) / 256, wide = tiles * ((n + 127) / 128) * replicas,
+                  narrow_wgs = tiles * (n / 64) * replicas;
+  const bool narrow = n % 64 == 0 && wide < 2 * kCus && narrow_wgs > 2 * kCus && narrow_wgs <= 3 * kCus;
+  if (n <= 64 || narrow) {
     const dim3 grid = halo_grid(g, 64, replicas, hg);
     hipLaunchKernelGGL(k_conv_halo_n64, grid, dim3(kThreads), 0, st, g, io, hg);
     return hipGetLastError();

@@ -163,6 +163,7 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
     (3, 128, 32, 32, 96, 96, 3, 1, 1),      # All-CNN-C conv2
     (3, 128, 16, 16, 192, 192, 3, 2, 1),    # All-CNN-C conv6 (stride 2)
     (3, 128, 32, 32, 16, 64, 3, 1, 1),      # WRN-16-4 group 1
+    (3, 128, 16, 16, 128, 128, 3, 1, 1),    # WRN-16-4 group 2: 64-wide column blocks, two per pixel tile
     (3, 128, 8, 8, 256, 256, 3, 1, 1),      # WRN-16-4 group 3
 ])
 def test_full_size_layers_sampled(gpu, layer):
