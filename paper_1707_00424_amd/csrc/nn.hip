@@ -342,22 +342,40 @@ __global__ __launch_bounds__(kThreads) void k_colreduce_vec(int M, int C, int ch
   }
 }
 
-// Sum over the row-splits of one channel's two partial sums: one wavefront per (channel, replica),
-// lane l takes splits l, l+64, ... in order, then a fixed shuffle tree (deterministic).
+// Sum over the row-splits of one channel's two partial sums: one workgroup of kFinThreads per (channel,
+// replica).  These kernels sit between two passes over the activations and last as long as their chain of
+// dependent L2 round trips, so a thread takes splits t, t + kFinThreads, ... four at a time with all eight
+// loads issued together (one round trip for up to 1024 splits); then a fixed shuffle tree and the wavefronts'
+// sums in order (deterministic).  Every thread returns the totals.
+constexpr int kFinThreads = 256;
 __device__ __forceinline__ void sum_splits(const double *__restrict__ partial, int rep, int S, int C, int c, double &s1,
                                            double &s2) {
-  s1 = 0.0, s2 = 0.0;
-  for (int sp = threadIdx.x; sp < S; sp += PARLE_WAVE) {
-    const double *p = partial + ((long long)rep * S + sp) * 2 * C;
-    s1 += p[c];
-    s2 += p[C + c];
+  __shared__ double red[2][kFinThreads / PARLE_WAVE];
+  const double *p = partial + (long long)rep * S * 2 * C + c;
+  double a1 = 0.0, a2 = 0.0;
+  for (int s0 = threadIdx.x; s0 < S; s0 += 4 * kFinThreads) {
+    double v1[4], v2[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int sp = s0 + u * kFinThreads;
+      const bool ok = sp < S;
+      v1[u] = ok ? p[(long long)sp * 2 * C] : 0.0;
+      v2[u] = ok ? p[(long long)sp * 2 * C + C] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a1 += v1[u], a2 += v2[u];
   }
-  s1 = wave_sum(s1);
-  s2 = wave_sum(s2);
+  a1 = wave_sum(a1);
+  a2 = wave_sum(a2);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) red[0][threadIdx.x / PARLE_WAVE] = a1, red[1][threadIdx.x / PARLE_WAVE] = a2;
+  __syncthreads();
+  s1 = 0.0, s2 = 0.0;
+#pragma unroll
+  for (int w = 0; w < kFinThreads / PARLE_WAVE; ++w) s1 += red[0][w], s2 += red[1][w];
 }
 
 // bias gradient: grad[c] = sum over splits of s1
-__global__ __launch_bounds__(PARLE_WAVE) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
+__global__ __launch_bounds__(kFinThreads) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
                                                               float *__restrict__ grad, long long grad_rs) {
   const int rep = blockIdx.y, c = blockIdx.x;
   double s1, s2;
@@ -365,7 +383,7 @@ __global__ __launch_bounds__(PARLE_WAVE) void k_bias_finalize(int C, int S, cons
   if (threadIdx.x == 0) grad[rep * grad_rs + c] = (float)s1;
 }
 
-__global__ __launch_bounds__(PARLE_WAVE) void k_bn_stats_finalize(int M, int C, int S,
+__global__ __launch_bounds__(kFinThreads) void k_bn_stats_finalize(int M, int C, int S,
                                                                   const double *__restrict__ partial,
                                                                   float *__restrict__ saved, float *__restrict__ running,
                                                                   long long run_rs) {
@@ -509,7 +527,7 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply_vec(int M, int C, con
   }
 }
 
-__global__ __launch_bounds__(PARLE_WAVE) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
+__global__ __launch_bounds__(kFinThreads) void k_bn_bwd_finalize(int C, int S, const double *__restrict__ partial,
                                                                 float *__restrict__ sums, float *__restrict__ dgamma,
                                                                 float *__restrict__ dbeta, long long p_rs) {
   const int rep = blockIdx.y, c = blockIdx.x;
@@ -908,7 +926,7 @@ hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, cons
                                       partial)),
              (run_colreduce<bf16_t, 0>(st, grid, M, C, chunk, ct, dy, dy_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
                                        partial)));
-  hipLaunchKernelGGL(k_bias_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, grad, grad_rs);
+  hipLaunchKernelGGL(k_bias_finalize, dim3(C, n), dim3(kFinThreads), 0, st, C, S, partial, grad, grad_rs);
   return hipGetLastError();
 }
 
@@ -934,7 +952,7 @@ hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, c
                                       partial)),
              (run_colreduce<bf16_t, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
                                        partial)));
-  hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, M, C, S, partial, saved, running,
+  hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(kFinThreads), 0, st, M, C, S, partial, saved, running,
                      run_rs);
   const int vw = dtype ? 8 : 4;
   if (C % vw == 0 && x_rs % vw == 0 && out_rs % vw == 0 && aligned_to(x, 16) && aligned_to(out, 16)) {
@@ -979,7 +997,7 @@ hipError_t launch_bn_bwd(hipStream_t st, int dtype, int n, int M, int C, const v
                                       partial)),
              (run_colreduce<bf16_t, 2>(st, grid, M, C, chunk, ct, x, x_rs, dout, dout_rs, saved, gamma, beta, p_rs,
                                        partial)));
-  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(C, n), dim3(PARLE_WAVE), 0, st, C, S, partial, sums, dgamma, dbeta, p_rs);
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(C, n), dim3(kFinThreads), 0, st, C, S, partial, sums, dgamma, dbeta, p_rs);
   const int vw = dtype ? 8 : 4;
   if (C % vw == 0 && x_rs % vw == 0 && dout_rs % vw == 0 && dx_rs % vw == 0 && add_rs % vw == 0 && aligned_to(x, 16) &&
       aligned_to(dout, 16) && aligned_to(dx, 16) && aligned_to(add, 16)) {
