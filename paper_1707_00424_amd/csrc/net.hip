@@ -35,6 +35,13 @@ struct Op {
   bool mask_in = false;    // the input is a ReLU output: its gradient is masked by (in > 0)
   bool dx_accumulate = false;
   int dy = -1;             // tensor whose gradient is this op's output gradient (default: out)
+  // A shortcut convolution is a branch beside the block's chain of convolutions: it runs on the second stream
+  // (forward), and its input gradient, which needs only the block output's gradient, is written there as soon
+  // as that gradient is final; the block's first convolution, whose input is the same tensor, then
+  // accumulates its own input gradient onto it.
+  bool branch = false;     // this op is such a shortcut
+  int join = -1;           // index of the shortcut op whose output this op reads (resid) and whose backward it starts
+  int dx_after = -1;       // index of the shortcut op whose input gradient this op's accumulates onto
   int64_t wt_off = -1;     // transposed weights (bytes)
   int64_t col_off = -1;    // per-tap products of the two-pass backward-data (bytes), -1 = direct kernel
   // pool
@@ -67,10 +74,14 @@ struct Net {
   bool overlap = true;
   hipStream_t side = nullptr;
   std::vector<hipEvent_t> dy_ready;  // one per op: its output gradient is final
+  // per op, used by shortcut ops only: input ready (forward fork), output ready (forward join), input gradient
+  // ready (backward join)
+  std::vector<hipEvent_t> br_fork, br_out, br_dx;
   hipEvent_t side_done = nullptr;
   ~Net() {
-    for (hipEvent_t e : dy_ready)
-      if (e) (void)hipEventDestroy(e);
+    for (const std::vector<hipEvent_t> *v : {&dy_ready, &br_fork, &br_out, &br_dx})
+      for (hipEvent_t e : *v)
+        if (e) (void)hipEventDestroy(e);
     if (side_done) (void)hipEventDestroy(side_done);
     if (side) (void)hipStreamDestroy(side);
   }
@@ -224,16 +235,17 @@ bool build_plan(Net &N, std::string &err) {
       for (const WrnBlock &b : wrn_block_list(a)) {
         const int bn1 = N.add_bn(h, b.name + ".bn1");
         const int o = N.ops[bn1].out;
-        int s = -1;
+        int s = -1, sc = -1;
         if (b.has_sc) {
-          const int sc = N.add_conv(o, H, W, b.cin, b.name + ".sc", b.cout, 1, b.stride, 0, false, false);
-          N.ops[sc].need_dx = true, N.ops[sc].dx_accumulate = true;
+          sc = N.add_conv(o, H, W, b.cin, b.name + ".sc", b.cout, 1, b.stride, 0, false, false);
+          N.ops[sc].need_dx = true, N.ops[sc].branch = true;
           s = N.ops[sc].out;
         } else {
           N.ops[bn1].bn_add = -2;  // resolved below to the block output
         }
         const int cv1 = N.add_conv(o, H, W, b.cin, b.name + ".conv1", b.cout, 3, b.stride, 1, false, false);
         N.ops[cv1].need_dx = true;
+        if (b.has_sc) N.ops[cv1].dx_accumulate = true, N.ops[cv1].dx_after = sc;
         const int bn2 = N.add_bn(N.ops[cv1].out, b.name + ".bn2");
         const int cv1_ho = N.ops[cv1].Ho, cv1_wo = N.ops[cv1].Wo;
         const int mid = N.add_drop(N.ops[bn2].out, false);
@@ -242,10 +254,8 @@ bool build_plan(Net &N, std::string &err) {
         N.ops[cv2].resid = b.has_sc ? s : h;
         const int v = N.ops[cv2].out;
         if (b.has_sc) {
-          // the shortcut conv's output gradient is the block output's gradient; it runs (in reverse
-          // order) after conv1's backward-data has written the gradient of o, hence accumulates
-          for (Op &op : N.ops)
-            if (op.type == OP_CONV && op.out == s) op.dy = v;
+          // the shortcut conv's output gradient is the block output's gradient
+          N.ops[sc].dy = v, N.ops[cv2].join = sc;
         } else {
           N.ops[bn1].bn_add = v;
         }
@@ -372,10 +382,19 @@ ConvGeom bwd_geom(const Op &op, int B) { return conv_bwd_geom(shape_of(op, B)); 
 hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_eval_row) {
   Net &N = *r.N;
   const int vw = 16 / N.esize;
-  for (const Op &op : N.ops) {
+  const bool branches = train && N.side != nullptr;  // shortcut convolutions beside the chain
+  for (int oi = 0; oi < (int)N.ops.size(); ++oi) {
+    const Op &op = N.ops[oi];
     switch (op.type) {
       case OP_CONV: {
         const ConvGeom g = fwd_geom(op, r.B);
+        hipStream_t cst = r.st;
+        if (branches && op.branch) {
+          HIP_TRY(hipEventRecord(N.br_fork[oi], r.st));
+          HIP_TRY(hipStreamWaitEvent(N.side, N.br_fork[oi], 0));
+          cst = N.side;
+        }
+        if (branches && op.join >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_out[op.join], 0));
         GemmIO io{};
         io.in = r.tptr(op.in), io.in_rs = r.trs(op.in);
         io.w = r.wptr(op.wseg), io.w_rs = r.p_rs;
@@ -389,7 +408,8 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         io.vecB = (g.K % vw == 0) && (N.dtype == 0 || ((N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) &&
                                                        aligned_to(io.w, 16)));
         io.in_bytes = io.in_rs * N.esize;
-        HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, io));
+        HIP_TRY(launch_igemm(cst, N.dtype, N.tensors[op.out].f32, r.n, g, io));
+        if (cst != r.st) HIP_TRY(hipEventRecord(N.br_out[oi], N.side));
         break;
       }
       case OP_POOL: {
@@ -437,6 +457,23 @@ hipError_t backward(const Run &r, float *grad) {
   const int vw = 16 / N.esize;
   for (const TransposeTable &t : N.transposes)
     HIP_TRY(launch_weight_transpose_all(r.st, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
+  // input gradient of a convolution (direct kernels) on stream `s`
+  auto launch_dgrad = [&](const Op &op, hipStream_t s) -> hipError_t {
+    const void *dy = r.gptr(op.dy);
+    const int64_t dy_rs = r.trs(op.dy);
+    const int64_t wsize = N.segs[op.wseg].size;
+    const ConvGeom gb = bwd_geom(op, r.B);
+    GemmIO io{};
+    io.in = dy, io.in_rs = dy_rs;
+    io.w = r.ws + op.wt_off, io.w_rs = wsize;  // transposed at the start of the backward pass, all layers in one launch
+    io.out = r.gptr(op.in), io.out_rs = r.trs(op.in), io.ldc = op.Cin;
+    io.mask = op.mask_in ? r.tptr(op.in) : nullptr, io.mask_rs = r.trs(op.in);
+    io.accumulate = op.dx_accumulate;
+    io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
+    io.vecB = (gb.K % vw == 0) && (wsize % vw == 0);
+    io.in_bytes = io.in_rs * N.esize;
+    return launch_igemm(s, N.dtype, false, r.n, gb, io);
+  };
   for (int oi = (int)N.ops.size() - 1; oi >= 0; --oi) {
     const Op &op = N.ops[oi];
     switch (op.type) {
@@ -451,6 +488,12 @@ hipError_t backward(const Run &r, float *grad) {
           HIP_TRY(hipEventRecord(N.dy_ready[oi], r.st));
           HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
           lst = N.side, colpartial = N.off_colpartial_side;
+        }
+        // the block's shortcut shares this op's output gradient: its input gradient goes first on the second
+        // stream (the block's first convolution waits for it), ahead of the weight gradients
+        if (op.join >= 0) {
+          HIP_TRY(launch_dgrad(N.ops[op.join], lst));
+          if (N.side) HIP_TRY(hipEventRecord(N.br_dx[op.join], N.side));
         }
         if (op.bseg >= 0)
           HIP_TRY(launch_bias_grad(lst, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + colpartial),
@@ -476,7 +519,8 @@ hipError_t backward(const Run &r, float *grad) {
             HIP_TRY(launch_reduce_partials(lst, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
           }
         }
-        if (op.need_dx) {
+        if (op.need_dx && !op.branch) {
+          if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
           void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
           if (op.col_off > 0) {
@@ -497,17 +541,7 @@ hipError_t backward(const Run &r, float *grad) {
                                   (float *)r.gptr(op.in), r.trs(op.in)));
             break;
           }
-          const ConvGeom gb = bwd_geom(op, r.B);
-          GemmIO io{};
-          io.in = dy, io.in_rs = dy_rs;
-          io.w = wt, io.w_rs = wsize;
-          io.out = r.gptr(op.in), io.out_rs = r.trs(op.in), io.ldc = op.Cin;
-          io.mask = op.mask_in ? r.tptr(op.in) : nullptr, io.mask_rs = r.trs(op.in);
-          io.accumulate = op.dx_accumulate;
-          io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
-          io.vecB = (gb.K % vw == 0) && (wsize % vw == 0);
-          io.in_bytes = io.in_rs * N.esize;
-          HIP_TRY(launch_igemm(r.st, N.dtype, false, r.n, gb, io));
+          HIP_TRY(launch_dgrad(op, r.st));
         }
         break;
       }
@@ -560,7 +594,10 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   if (cs != hipStreamCaptureStatusNone) return hipSuccess;  // this step runs on one stream
   hipStream_t side = nullptr;
   HIP_TRY(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
-  std::vector<hipEvent_t> ev(N.ops.size() + 1, nullptr);
+  // per op: output gradient final; per shortcut op three more (see Net); one for the join at the end
+  size_t n_branch = 0;
+  for (const Op &op : N.ops) n_branch += op.branch ? 1 : 0;
+  std::vector<hipEvent_t> ev(N.ops.size() + 3 * n_branch + 1, nullptr);
   for (hipEvent_t &e : ev) {
     if (hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming)) {
       for (hipEvent_t d : ev)
@@ -571,6 +608,13 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   }
   N.side_done = ev.back();
   ev.pop_back();
+  N.br_fork.assign(N.ops.size(), nullptr), N.br_out.assign(N.ops.size(), nullptr), N.br_dx.assign(N.ops.size(), nullptr);
+  for (size_t oi = 0; oi < N.ops.size(); ++oi) {
+    if (!N.ops[oi].branch) continue;
+    N.br_fork[oi] = ev.back(), ev.pop_back();
+    N.br_out[oi] = ev.back(), ev.pop_back();
+    N.br_dx[oi] = ev.back(), ev.pop_back();
+  }
   N.dy_ready = ev;
   N.side = side;
   return hipSuccess;
