@@ -67,10 +67,13 @@ struct Net {
   std::vector<Op> ops;
   int t_images = -1, t_logits = -1;
   int64_t ws_bytes = 0;
-  int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0, wpartial_bytes = 0;
+  int64_t off_colpartial = 0, off_wpartial = 0, off_rowcopy = 0, wpartial_bytes = 0, wpartial_main_bytes = 0;
   // Weight and bias gradients are leaves of the backward pass: they run on a second stream beside the
   // chain of input gradients (own column-partial scratch; the weight partials are used there only).
   int64_t off_colpartial_side = 0;
+  // A layer without input gradient (the first one) is the last the backward pass reaches: nothing follows it on
+  // the first stream, so its leaves run there, beside whatever the second stream still has queued (own scratch).
+  int64_t off_wpartial_main = 0;
   bool overlap = true;
   hipStream_t side = nullptr;
   std::vector<hipEvent_t> dy_ready;  // one per op: its output gradient is final
@@ -276,7 +279,7 @@ bool build_plan(Net &N, std::string &err) {
       return false;
   }
   // gradients, transposed weights, scratch
-  int64_t wpartial = 0, col_bytes = 0;
+  int64_t wpartial = 0, wpartial_main = 0, col_bytes = 0;
   for (Op &op : N.ops) {
     if (op.wseg < 0 && op.type == OP_CONV) {
       err = "internal: weight segment not found";
@@ -303,7 +306,8 @@ bool build_plan(Net &N, std::string &err) {
       const ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
       int chunk = 0;
       const int S = wgrad_plan(N.dtype, N.n, g, &chunk);
-      if (S > 1 && (int64_t)N.n * S * wsize * 4 > wpartial) wpartial = (int64_t)N.n * S * wsize * 4;
+      if (S > 1 && (int64_t)N.n * S * wsize * 4 > (op.need_dx ? wpartial : wpartial_main))
+        (op.need_dx ? wpartial : wpartial_main) = (int64_t)N.n * S * wsize * 4;
       if ((int64_t)N.B * op.Hin * op.Win * op.Cin >= (1LL << 31) || (int64_t)g.M * op.Cout >= (1LL << 31) ||
           wsize >= (1LL << 31)) {
         err = "a layer exceeds 2^31 elements per replica";
@@ -335,6 +339,8 @@ bool build_plan(Net &N, std::string &err) {
   for (TransposeTable &t : N.transposes) transpose_table_finish(t);
   N.wpartial_bytes = wpartial > 0 ? wpartial : 256;
   N.off_wpartial = N.alloc(N.wpartial_bytes);
+  N.off_wpartial_main = N.alloc(wpartial_main > 0 ? wpartial_main : 256);
+  N.wpartial_main_bytes = wpartial_main;
   if (col_bytes > 0) {  // one buffer for all layers that take the two-pass route (they run one after the other)
     const int64_t off = N.alloc(col_bytes);
     for (Op &op : N.ops)
@@ -481,13 +487,18 @@ hipError_t backward(const Run &r, float *grad) {
         const void *dy = r.gptr(op.dy);
         const int64_t dy_rs = r.trs(op.dy);
         const ConvGeom gf = fwd_geom(op, r.B);
-        // leaves: on the second stream once this op's output gradient is final
+        // leaves: on the second stream once this op's output gradient is final.  A layer without input
+        // gradient (the first one) leaves the first stream idle: its leaves run there, beside whatever the
+        // second stream still has queued.
         hipStream_t lst = r.st;
         int64_t colpartial = N.off_colpartial;
-        if (N.side) {
+        int64_t wpart = N.off_wpartial, wpart_bytes = N.wpartial_bytes;
+        if (N.side && op.need_dx) {
           HIP_TRY(hipEventRecord(N.dy_ready[oi], r.st));
           HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
           lst = N.side, colpartial = N.off_colpartial_side;
+        } else if (!op.need_dx) {
+          wpart = N.off_wpartial_main, wpart_bytes = N.wpartial_main_bytes;
         }
         // the block's shortcut shares this op's output gradient: its input gradient goes first on the second
         // stream (the block's first convolution waits for it), ahead of the weight gradients
@@ -513,8 +524,8 @@ hipError_t backward(const Run &r, float *grad) {
             HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));
           } else {
             // never launch with more partials than the plan reserved room for
-            if ((int64_t)r.n * S * wsize * 4 > N.wpartial_bytes) return hipErrorInvalidValue;
-            io.out = (float *)(r.ws + N.off_wpartial), io.out_rs = (int64_t)S * wsize, io.split_stride = wsize;
+            if ((int64_t)r.n * S * wsize * 4 > wpart_bytes) return hipErrorInvalidValue;
+            io.out = (float *)(r.ws + wpart), io.out_rs = (int64_t)S * wsize, io.split_stride = wsize;
             HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));
             HIP_TRY(launch_reduce_partials(lst, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
           }

@@ -89,6 +89,8 @@ CASES = [
     (1, 2, 16, 16, 160, 32, 3, 2, 1),   # same, 160 channels = 96 + a ragged second block
     (2, 2, 16, 16, 16, 64, 3, 1, 1),    # patch path with half a channel chunk (the first block of the residual networks)
     (1, 2, 16, 16, 40, 48, 3, 1, 1),    # same, one full chunk and a ragged one, in both directions
+    (2, 3, 6, 7, 8, 12, 5, 1, 2),       # padded 5x5 window on 6 x 7 pixels, 8 channels
+    (1, 2, 8, 8, 32, 10, 2, 1, 0),      # 2x2 window, no padding
     (3, 128, 1, 1, 784, 128, 1, 1, 0),  # the MLP's first layer: contraction split over the wavefronts of a workgroup
     (2, 20, 1, 1, 504, 10, 1, 1, 0),    # same, ten outputs, contraction not a multiple of the four quarters
 ]
