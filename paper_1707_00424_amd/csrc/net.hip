@@ -493,13 +493,41 @@ hipError_t backward(const Run &r, float *grad) {
         hipStream_t lst = r.st;
         int64_t colpartial = N.off_colpartial;
         int64_t wpart = N.off_wpartial, wpart_bytes = N.wpartial_bytes;
-        if (N.side && op.need_dx) {
+        const bool fork = N.side && op.need_dx;
+        if (fork) {
           HIP_TRY(hipEventRecord(N.dy_ready[oi], r.st));
-          HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
           lst = N.side, colpartial = N.off_colpartial_side;
         } else if (!op.need_dx) {
           wpart = N.off_wpartial_main, wpart_bytes = N.wpartial_main_bytes;
         }
+        // The input gradient is enqueued before the leaves.  The order matters when the step is recorded into a
+        // graph: the runtime keeps the first successor of a node on the node's own queue, and a chain that
+        // lands behind a branch of leaves waits for them although nothing ties the two.
+        if (op.need_dx && !op.branch) {
+          if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
+          void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
+          const int64_t wsize = N.segs[op.wseg].size;
+          if (op.col_off > 0) {
+            // col = dy x W: the transposed weights, here ordered [RS][Cin][Cout], are the [N][K] operand as they lie
+            const int RS = op.R * op.R, M = r.B * op.Ho * op.Wo, Ncol = op.Cin * RS;
+            const ConvGeom gc = conv_fwd_geom(ConvShape{M, 1, 1, op.Cout, Ncol, 1, 1, 0});
+            float *col = (float *)(r.ws + op.col_off);
+            GemmIO io{};
+            io.in = dy, io.in_rs = dy_rs;
+            io.w = wt, io.w_rs = wsize;
+            io.out = col, io.out_rs = (int64_t)M * Ncol, io.ldc = Ncol;
+            io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
+            io.vecB = io.vecA;
+            io.in_bytes = io.in_rs * N.esize;
+            HIP_TRY(launch_igemm(r.st, N.dtype, true, r.n, gc, io));
+            HIP_TRY(launch_col2im(r.st, r.n, r.B, op.Hin, op.Win, op.Cin, op.R, op.pad, col, io.out_rs,
+                                  op.mask_in ? (const float *)r.tptr(op.in) : nullptr, r.trs(op.in), op.dx_accumulate,
+                                  (float *)r.gptr(op.in), r.trs(op.in)));
+          } else {
+            HIP_TRY(launch_dgrad(op, r.st));
+          }
+        }
+        if (fork) HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
         // the block's shortcut shares this op's output gradient: its input gradient goes first on the second
         // stream (the block's first convolution waits for it), ahead of the weight gradients
         if (op.join >= 0) {
@@ -529,30 +557,6 @@ hipError_t backward(const Run &r, float *grad) {
             HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));
             HIP_TRY(launch_reduce_partials(lst, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
           }
-        }
-        if (op.need_dx && !op.branch) {
-          if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
-          void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
-          const int64_t wsize = N.segs[op.wseg].size;
-          if (op.col_off > 0) {
-            // col = dy x W: the transposed weights, here ordered [RS][Cin][Cout], are the [N][K] operand as they lie
-            const int RS = op.R * op.R, M = r.B * op.Ho * op.Wo, Ncol = op.Cin * RS;
-            const ConvGeom gc = conv_fwd_geom(ConvShape{M, 1, 1, op.Cout, Ncol, 1, 1, 0});
-            float *col = (float *)(r.ws + op.col_off);
-            GemmIO io{};
-            io.in = dy, io.in_rs = dy_rs;
-            io.w = wt, io.w_rs = wsize;
-            io.out = col, io.out_rs = (int64_t)M * Ncol, io.ldc = Ncol;
-            io.vecA = (op.Cout % vw == 0) && aligned_to(dy, 16);
-            io.vecB = io.vecA;
-            io.in_bytes = io.in_rs * N.esize;
-            HIP_TRY(launch_igemm(r.st, N.dtype, true, r.n, gc, io));
-            HIP_TRY(launch_col2im(r.st, r.n, r.B, op.Hin, op.Win, op.Cin, op.R, op.pad, col, io.out_rs,
-                                  op.mask_in ? (const float *)r.tptr(op.in) : nullptr, r.trs(op.in), op.dx_accumulate,
-                                  (float *)r.gptr(op.in), r.trs(op.in)));
-            break;
-          }
-          HIP_TRY(launch_dgrad(op, r.st));
         }
         break;
       }
