@@ -389,33 +389,51 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
   Net &N = *r.N;
   const int vw = 16 / N.esize;
   const bool branches = train && N.side != nullptr;  // shortcut convolutions beside the chain
+  // a shortcut waits until the chain's next convolution has been enqueued (see the note on order in backward())
+  int pending = -1;
+  auto conv_io = [&](const Op &op, const ConvGeom &g) {
+    GemmIO io{};
+    io.in = r.tptr(op.in), io.in_rs = r.trs(op.in);
+    io.w = r.wptr(op.wseg), io.w_rs = r.p_rs;
+    io.out = r.tptr(op.out), io.out_rs = r.trs(op.out), io.ldc = op.Cout;
+    io.bias = op.bseg >= 0 ? r.fptr(op.bseg) : nullptr, io.bias_rs = r.p_rs;
+    io.resid = op.resid >= 0 ? r.tptr(op.resid) : nullptr, io.resid_rs = op.resid >= 0 ? r.trs(op.resid) : 0;
+    io.relu = op.relu;
+    io.vecA = (op.Cin % vw == 0) && aligned_to(io.in, 16);
+    // 16-byte loads of weight rows.  Global and buffer loads need 4-byte alignment only, which fp32 rows
+    // always have; bf16 rows must start on a 16-byte boundary (two-byte offsets would misalign them).
+    io.vecB = (g.K % vw == 0) && (N.dtype == 0 || ((N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) &&
+                                                   aligned_to(io.w, 16)));
+    io.in_bytes = io.in_rs * N.esize;
+    return io;
+  };
+  auto launch_pending = [&]() -> hipError_t {
+    if (pending < 0) return hipSuccess;
+    const int pi = pending;
+    pending = -1;
+    const Op &op = N.ops[pi];
+    const ConvGeom g = fwd_geom(op, r.B);
+    HIP_TRY(hipStreamWaitEvent(N.side, N.br_fork[pi], 0));
+    HIP_TRY(launch_igemm(N.side, N.dtype, N.tensors[op.out].f32, r.n, g, conv_io(op, g)));
+    return hipEventRecord(N.br_out[pi], N.side);
+  };
   for (int oi = 0; oi < (int)N.ops.size(); ++oi) {
     const Op &op = N.ops[oi];
     switch (op.type) {
       case OP_CONV: {
         const ConvGeom g = fwd_geom(op, r.B);
-        hipStream_t cst = r.st;
         if (branches && op.branch) {
+          HIP_TRY(launch_pending());
           HIP_TRY(hipEventRecord(N.br_fork[oi], r.st));
-          HIP_TRY(hipStreamWaitEvent(N.side, N.br_fork[oi], 0));
-          cst = N.side;
+          pending = oi;
+          break;
         }
-        if (branches && op.join >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_out[op.join], 0));
-        GemmIO io{};
-        io.in = r.tptr(op.in), io.in_rs = r.trs(op.in);
-        io.w = r.wptr(op.wseg), io.w_rs = r.p_rs;
-        io.out = r.tptr(op.out), io.out_rs = r.trs(op.out), io.ldc = op.Cout;
-        io.bias = op.bseg >= 0 ? r.fptr(op.bseg) : nullptr, io.bias_rs = r.p_rs;
-        io.resid = op.resid >= 0 ? r.tptr(op.resid) : nullptr, io.resid_rs = op.resid >= 0 ? r.trs(op.resid) : 0;
-        io.relu = op.relu;
-        io.vecA = (op.Cin % vw == 0) && aligned_to(io.in, 16);
-        // 16-byte loads of weight rows.  Global and buffer loads need 4-byte alignment only, which fp32 rows
-        // always have; bf16 rows must start on a 16-byte boundary (two-byte offsets would misalign them).
-        io.vecB = (g.K % vw == 0) && (N.dtype == 0 || ((N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) &&
-                                                       aligned_to(io.w, 16)));
-        io.in_bytes = io.in_rs * N.esize;
-        HIP_TRY(launch_igemm(cst, N.dtype, N.tensors[op.out].f32, r.n, g, io));
-        if (cst != r.st) HIP_TRY(hipEventRecord(N.br_out[oi], N.side));
+        if (branches && op.join >= 0) {
+          HIP_TRY(launch_pending());
+          HIP_TRY(hipStreamWaitEvent(r.st, N.br_out[op.join], 0));
+        }
+        HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, conv_io(op, g)));
+        HIP_TRY(launch_pending());
         break;
       }
       case OP_POOL: {
@@ -455,7 +473,7 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
       }
     }
   }
-  return hipSuccess;
+  return launch_pending();
 }
 
 hipError_t backward(const Run &r, float *grad) {
