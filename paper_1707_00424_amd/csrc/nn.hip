@@ -303,27 +303,46 @@ __global__ __launch_bounds__(kThreads) void k_colreduce_vec(int M, int C, int ch
       }
     }
   };
-  if (active) {
-    for (int r = r0 + lr; r < r1; r += tr) {
-      float xv[VW];
-      unpack(*(const u4v *)(xp + (long long)r * C + lc * VW), xv);
-      if (MODE == 0) {
+  auto add_row = [&](const u4v &xq, const u4v &dq) {
+    float xv[VW];
+    unpack(xq, xv);
+    if (MODE == 0) {
 #pragma unroll
-        for (int e = 0; e < VW; ++e) s1[e] += xv[e];
-      } else if (MODE == 1) {
+      for (int e = 0; e < VW; ++e) s1[e] += xv[e];
+    } else if (MODE == 1) {
 #pragma unroll
-        for (int e = 0; e < VW; ++e) s1[e] += xv[e], s2[e] += xv[e] * xv[e];
-      } else {
-        float dv[VW];
-        unpack(*(const u4v *)(dp + (long long)r * C + lc * VW), dv);
+      for (int e = 0; e < VW; ++e) s1[e] += xv[e], s2[e] += xv[e] * xv[e];
+    } else {
+      float dv[VW];
+      unpack(dq, dv);
 #pragma unroll
-        for (int e = 0; e < VW; ++e) {
-          const float xh = (xv[e] - mean[e]) * rstd[e];
-          const float d = (xh * gm[e] + bt[e]) > 0.f ? dv[e] : 0.f;
-          s1[e] += d;
-          s2[e] += d * xh;
-        }
+      for (int e = 0; e < VW; ++e) {
+        const float xh = (xv[e] - mean[e]) * rstd[e];
+        const float d = (xh * gm[e] + bt[e]) > 0.f ? dv[e] : 0.f;
+        s1[e] += d;
+        s2[e] += d * xh;
       }
+    }
+  };
+  if (active) {
+    // U rows per trip, their loads issued together: a thread's trips are few (tens of rows), and with one load
+    // in flight per thread the pass runs at the latency of memory, not at its bandwidth
+    constexpr int U = 4;
+    int r = r0 + lr;
+    for (; r + (U - 1) * tr < r1; r += U * tr) {
+      u4v xq[U], dq[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        xq[u] = *(const u4v *)(xp + (long long)(r + u * tr) * C + lc * VW);
+        if (MODE == 2) dq[u] = *(const u4v *)(dp + (long long)(r + u * tr) * C + lc * VW);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) add_row(xq[u], dq[u]);
+    }
+    for (; r < r1; r += tr) {
+      u4v dq = {0u, 0u, 0u, 0u};
+      if (MODE == 2) dq = *(const u4v *)(dp + (long long)r * C + lc * VW);
+      add_row(*(const u4v *)(xp + (long long)r * C + lc * VW), dq);
     }
   }
 #pragma unroll
