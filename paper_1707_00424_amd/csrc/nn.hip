@@ -480,6 +480,58 @@ __device__ __forceinline__ u4e pack16(const float *f) {
   return v;
 }
 
+// bf16, C a multiple of 8: 16-byte accesses.  Forward: one workgroup per image; a thread owns 8 channels of the
+// pixels pl, pl + PL, ... (PL = 256 / (C / 8) pixel lanes, several loads in flight), the lanes' sums are added
+// through LDS in lane order.  Backward: one thread per 16-byte vector of the input gradient.
+template <bool OUT_F32>
+__global__ __launch_bounds__(kThreads) void k_gap_fwd_vec(int HW, int C, const bf16_t *__restrict__ in, long long in_rs,
+                                                          void *__restrict__ out, long long out_rs) {
+  __shared__ float red[kThreads * 8];
+  const int b = blockIdx.x, rep = blockIdx.y;
+  const int CV = C >> 3, PL = kThreads / CV;
+  const int cv = threadIdx.x % CV, pl = threadIdx.x / CV;
+  const bf16_t *x = in + rep * in_rs + (long long)b * HW * C + cv * 8;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (pl < PL) {
+#pragma unroll 4
+    for (int p = pl; p < HW; p += PL) {
+      float v[8];
+      unpack16<bf16_t>(*(const u4e *)(x + (long long)p * C), v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += v[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[pl * C + cv * 8 + e] = s[e];
+  }
+  __syncthreads();
+  const float inv = 1.0f / (float)HW;
+  for (int c = threadIdx.x; c < C; c += kThreads) {
+    float t = 0.f;
+    for (int l = 0; l < PL; ++l) t += red[l * C + c];
+    const long long o = rep * out_rs + (long long)b * C + c;
+    if (OUT_F32)
+      ((float *)out)[o] = t * inv;
+    else
+      ((bf16_t *)out)[o] = f32_to_bf16(t * inv);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_gap_bwd_vec(long long total, int HW, int CV, const bf16_t *__restrict__ dout,
+                                                          long long dout_rs, bf16_t *__restrict__ din, long long din_rs) {
+  const bf16_t *dy = dout + blockIdx.y * dout_rs;
+  bf16_t *dx = din + blockIdx.y * din_rs;
+  const float inv = 1.0f / (float)HW;
+  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += (long long)gridDim.x * kThreads) {
+    const int cv = (int)(i % CV);
+    const long long b = i / ((long long)HW * CV);
+    float v[8];
+    unpack16<bf16_t>(*(const u4e *)(dy + (b * CV + cv) * 8), v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= inv;
+    *(u4e *)(dx + i * 8) = pack16<bf16_t>(v);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_bn_apply_relu_vec(int M, int C, const T *__restrict__ x, long long x_rs,
                                                                 const float *__restrict__ gamma,
@@ -901,6 +953,14 @@ hipError_t launch_col2im(hipStream_t st, int n, int B, int H, int W, int Cin, in
 
 hipError_t launch_gap_fwd(hipStream_t st, int dtype, bool out_f32, int n, int B, int HW, int C, const void *in,
                           long long in_rs, void *out, long long out_rs) {
+  if (dtype == 1 && C % 8 == 0 && C / 8 <= kThreads && in_rs % 8 == 0 && aligned_to(in, 16)) {
+    dim3 vgrid(B, n);
+    if (out_f32)
+      hipLaunchKernelGGL(k_gap_fwd_vec<true>, vgrid, dim3(kThreads), 0, st, HW, C, (const bf16_t *)in, in_rs, out, out_rs);
+    else
+      hipLaunchKernelGGL(k_gap_fwd_vec<false>, vgrid, dim3(kThreads), 0, st, HW, C, (const bf16_t *)in, in_rs, out, out_rs);
+    return hipGetLastError();
+  }
   dim3 grid(blocks_for((long long)B * C, 65535), n);
   if (dtype == 0) {
     hipLaunchKernelGGL((k_gap_fwd<float, true>), grid, dim3(kThreads), 0, st, B, HW, C, (const float *)in, in_rs, out,
@@ -917,6 +977,12 @@ hipError_t launch_gap_fwd(hipStream_t st, int dtype, bool out_f32, int n, int B,
 
 hipError_t launch_gap_bwd(hipStream_t st, int dtype, int n, int B, int HW, int C, const void *dout, long long dout_rs,
                           void *din, long long din_rs) {
+  if (dtype == 1 && C % 8 == 0 && dout_rs % 8 == 0 && din_rs % 8 == 0 && aligned_to(dout, 16) && aligned_to(din, 16)) {
+    const long long total = (long long)B * HW * (C / 8);
+    hipLaunchKernelGGL(k_gap_bwd_vec, dim3(blocks_for(total, 65535), n), dim3(kThreads), 0, st, total, HW, C / 8,
+                       (const bf16_t *)dout, dout_rs, (bf16_t *)din, din_rs);
+    return hipGetLastError();
+  }
   dim3 grid(blocks_for((long long)B * HW * C, 65535), n);
   DISPATCH_T(dtype,
              hipLaunchKernelGGL(k_gap_bwd<float>, grid, dim3(kThreads), 0, st, B, HW, C, (const float *)dout, dout_rs,
