@@ -71,6 +71,13 @@ struct Net {
   // Weight and bias gradients are leaves of the backward pass: they run on a second stream beside the
   // chain of input gradients (own column-partial scratch; the weight partials are used there only).
   int64_t off_colpartial_side = 0;
+  // Bias gradients (two small kernels per layer) on a third stream: they would otherwise sit in the second
+  // stream's queue in front of every weight gradient.
+  hipStream_t side2 = nullptr;
+  hipEvent_t side2_done = nullptr;
+  // All of a network's bias gradients or none: networks of small layers (LeNet, the MLP) lose more to the extra
+  // events than the stream hides (+4 %), and a mix of both placements measured worst of all.
+  bool bias_stream = false;
   // A layer without input gradient (the first one) is the last the backward pass reaches: nothing follows it on
   // the first stream, so its leaves run there, beside whatever the second stream still has queued (own scratch).
   int64_t off_wpartial_main = 0;
@@ -86,7 +93,9 @@ struct Net {
       for (hipEvent_t e : *v)
         if (e) (void)hipEventDestroy(e);
     if (side_done) (void)hipEventDestroy(side_done);
+    if (side2_done) (void)hipEventDestroy(side2_done);
     if (side) (void)hipStreamDestroy(side);
+    if (side2) (void)hipStreamDestroy(side2);
   }
   int64_t bn_floats = 0;
   int max_bn_c = 0;
@@ -317,6 +326,13 @@ bool build_plan(Net &N, std::string &err) {
       N.want_grad(op.in);
     }
   }
+  {
+    int with_bias = 0, large = 0;
+    for (const Op &op : N.ops)
+      if (op.type == OP_CONV && op.bseg >= 0 && op.need_dx)
+        ++with_bias, large += (int64_t)N.B * op.Ho * op.Wo * op.Cout >= (1LL << 20) ? 1 : 0;
+    N.bias_stream = with_bias >= 2 && 2 * large > with_bias;
+  }
   // two kinds of tables: layers whose rows fill whole 16-byte vectors (tiled, vector kernel) and the rest
   for (int vec = 1; vec >= 0; --vec) {
     bool open = false;
@@ -481,6 +497,7 @@ hipError_t backward(const Run &r, float *grad) {
   const int vw = 16 / N.esize;
   for (const TransposeTable &t : N.transposes)
     HIP_TRY(launch_weight_transpose_all(r.st, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
+  bool used_side2 = false;
   // input gradient of a convolution (direct kernels) on stream `s`
   auto launch_dgrad = [&](const Op &op, hipStream_t s) -> hipError_t {
     const void *dy = r.gptr(op.dy);
@@ -552,9 +569,15 @@ hipError_t backward(const Run &r, float *grad) {
           HIP_TRY(launch_dgrad(N.ops[op.join], lst));
           if (N.side) HIP_TRY(hipEventRecord(N.br_dx[op.join], N.side));
         }
-        if (op.bseg >= 0)
-          HIP_TRY(launch_bias_grad(lst, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + colpartial),
+        if (op.bseg >= 0) {
+          hipStream_t bst = lst;
+          if (fork && N.side2 && N.bias_stream) {
+            HIP_TRY(hipStreamWaitEvent(N.side2, N.dy_ready[oi], 0));
+            bst = N.side2, used_side2 = true;
+          }
+          HIP_TRY(launch_bias_grad(bst, N.dtype, r.n, gf.M, op.Cout, dy, dy_rs, (double *)(r.ws + colpartial),
                                    grad + N.segs[op.bseg].offset, r.p_rs));
+        }
         {
           WgradIO io{};
           io.dy = dy, io.dy_rs = dy_rs;
@@ -616,6 +639,10 @@ hipError_t backward(const Run &r, float *grad) {
     HIP_TRY(hipEventRecord(N.side_done, N.side));
     HIP_TRY(hipStreamWaitEvent(r.st, N.side_done, 0));
   }
+  if (used_side2) {
+    HIP_TRY(hipEventRecord(N.side2_done, N.side2));
+    HIP_TRY(hipStreamWaitEvent(r.st, N.side2_done, 0));
+  }
   return hipSuccess;
 }
 
@@ -625,22 +652,27 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   HIP_TRY(hipStreamIsCapturing(st, &cs));
   if (cs != hipStreamCaptureStatusNone) return hipSuccess;  // this step runs on one stream
-  hipStream_t side = nullptr;
+  hipStream_t side = nullptr, side2 = nullptr;
   HIP_TRY(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
+  if (hipError_t rc = hipStreamCreateWithFlags(&side2, hipStreamNonBlocking)) {
+    (void)hipStreamDestroy(side);
+    return rc;
+  }
   // per op: output gradient final; per shortcut op three more (see Net); one for the join at the end
   size_t n_branch = 0;
   for (const Op &op : N.ops) n_branch += op.branch ? 1 : 0;
-  std::vector<hipEvent_t> ev(N.ops.size() + 3 * n_branch + 1, nullptr);
+  std::vector<hipEvent_t> ev(N.ops.size() + 3 * n_branch + 2, nullptr);
   for (hipEvent_t &e : ev) {
     if (hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming)) {
       for (hipEvent_t d : ev)
         if (d) (void)hipEventDestroy(d);
       (void)hipStreamDestroy(side);
+      (void)hipStreamDestroy(side2);
       return rc;
     }
   }
-  N.side_done = ev.back();
-  ev.pop_back();
+  N.side_done = ev.back(), ev.pop_back();
+  N.side2_done = ev.back(), ev.pop_back();
   N.br_fork.assign(N.ops.size(), nullptr), N.br_out.assign(N.ops.size(), nullptr), N.br_dx.assign(N.ops.size(), nullptr);
   for (size_t oi = 0; oi < N.ops.size(); ++oi) {
     if (!N.ops[oi].branch) continue;
@@ -650,6 +682,7 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   }
   N.dy_ready = ev;
   N.side = side;
+  N.side2 = side2;
   return hipSuccess;
 }
 
