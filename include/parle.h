@@ -21,9 +21,9 @@
  * Pointers named "dev" are DEVICE pointers owned by the caller (any allocator; PyTorch tensors in
  * the bundled binding); pointers named "host" are host pointers.  The library allocates no
  * device memory and frees none.  All device work is ordered on the HIP stream given at init and is
- * asynchronous unless stated: a context of a network model owns up to two more streams of default priority
- * (weight- and bias-gradient kernels run beside the rest of the backward pass; blocks of inner steps are
- * replayed from a graph), tied to the init stream by events on both sides, so the caller sees the usual
+ * asynchronous unless stated: a context of a network model owns up to three more streams of default priority
+ * (weight-gradient, bias-gradient and shortcut kernels run beside the chain of the forward and backward pass;
+ * blocks of inner steps are replayed from a graph), tied to the init stream by events on both sides, so the caller sees the usual
  * stream order and needs no synchronisation of its own.  Buffers must not alias.  Calls on one context must
  * not overlap in time.  Non-finite values are not trapped by the step calls (parle_eval reports them).
  * Arguments are checked before anything is enqueued: EINVAL, EALIGN, ESIZE and ESTATE leave the
