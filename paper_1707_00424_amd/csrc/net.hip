@@ -88,7 +88,10 @@ struct Net {
   // ready (backward join)
   std::vector<hipEvent_t> br_fork, br_out, br_dx;
   hipEvent_t side_done = nullptr;
+  hipEvent_t step_begin = nullptr, wt_ready = nullptr;  // the weight transposes of a step run beside its forward pass
   ~Net() {
+    if (step_begin) (void)hipEventDestroy(step_begin);
+    if (wt_ready) (void)hipEventDestroy(wt_ready);
     for (const std::vector<hipEvent_t> *v : {&dy_ready, &br_fork, &br_out, &br_dx})
       for (hipEvent_t e : *v)
         if (e) (void)hipEventDestroy(e);
@@ -495,8 +498,12 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
 hipError_t backward(const Run &r, float *grad) {
   Net &N = *r.N;
   const int vw = 16 / N.esize;
-  for (const TransposeTable &t : N.transposes)
-    HIP_TRY(launch_weight_transpose_all(r.st, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
+  if (N.side) {
+    HIP_TRY(hipStreamWaitEvent(r.st, N.wt_ready, 0));  // transposed on the second stream beside the forward pass
+  } else {
+    for (const TransposeTable &t : N.transposes)
+      HIP_TRY(launch_weight_transpose_all(r.st, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
+  }
   bool used_side2 = false;
   // input gradient of a convolution (direct kernels) on stream `s`
   auto launch_dgrad = [&](const Op &op, hipStream_t s) -> hipError_t {
@@ -661,7 +668,7 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   // per op: output gradient final; per shortcut op three more (see Net); one for the join at the end
   size_t n_branch = 0;
   for (const Op &op : N.ops) n_branch += op.branch ? 1 : 0;
-  std::vector<hipEvent_t> ev(N.ops.size() + 3 * n_branch + 2, nullptr);
+  std::vector<hipEvent_t> ev(N.ops.size() + 3 * n_branch + 4, nullptr);
   for (hipEvent_t &e : ev) {
     if (hipError_t rc = hipEventCreateWithFlags(&e, hipEventDisableTiming)) {
       for (hipEvent_t d : ev)
@@ -673,6 +680,8 @@ hipError_t make_side_stream(Net &N, hipStream_t st) {
   }
   N.side_done = ev.back(), ev.pop_back();
   N.side2_done = ev.back(), ev.pop_back();
+  N.step_begin = ev.back(), ev.pop_back();
+  N.wt_ready = ev.back(), ev.pop_back();
   N.br_fork.assign(N.ops.size(), nullptr), N.br_out.assign(N.ops.size(), nullptr), N.br_dx.assign(N.ops.size(), nullptr);
   for (size_t oi = 0; oi < N.ops.size(); ++oi) {
     if (!N.ops[oi].branch) continue;
@@ -728,7 +737,16 @@ hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const v
     const Tensor &ti = N.tensors[N.t_images];
     HIP_TRY(launch_convert(st, 1, images, r.ws + ti.off, (long long)N.n * N.B * ti.H * ti.W * ti.C));
   }
+  if (N.side) HIP_TRY(hipEventRecord(N.step_begin, st));
   HIP_TRY(forward(r, true, bn_stats, nullptr));
+  if (N.side) {
+    // the transposed weights are read by the backward pass only: the second stream makes them beside the forward
+    // pass (enqueued after it, see the note on order in backward(); they wait for the start of the step only)
+    HIP_TRY(hipStreamWaitEvent(N.side, N.step_begin, 0));
+    for (const TransposeTable &t : N.transposes)
+      HIP_TRY(launch_weight_transpose_all(N.side, N.dtype, r.n, t, r.params_t, r.p_rs, r.ws));
+    HIP_TRY(hipEventRecord(N.wt_ready, N.side));
+  }
   const Tensor &tl = N.tensors[N.t_logits];
   HIP_TRY(launch_softmax_xent_train(st, N.dtype, N.n, N.B, tl.C, (const float *)r.tptr(N.t_logits), r.trs(N.t_logits),
                                     labels, loss_dev, r.gptr(N.t_logits), r.trs(N.t_logits)));
