@@ -133,6 +133,27 @@ def test_one_step_loss_and_gradient(gpu, name, bf16):
         check(f"{name} {t}", got[t], getattr(O.st, t), 1e-5)
 
 
+@pytest.mark.parametrize("name", ["mlp_odd", "lenet_odd", "allcnn_odd", "wrn_odd"])
+def test_one_replica_one_image(gpu, name):
+    """Degenerate sizes: n = 1 replica, a mini-batch of one image (the batch-norm statistics of the residual
+    network are then over the pixels of that image alone); one inner step and an outer step, fp32."""
+    torch, pb = gpu
+    a = SMALL[name]
+    P, O = make(pb, a, 1, 1, bf16=0, seed=11, L=1)
+    X, Y = synth.image_batches(8, 1, 1, 1, a["H"], a["W"], a["C"], a["classes"])
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    P.parle_inner_step(dev(torch, X[0]), dev(torch, Y[0]), loss)
+    ref_loss = O.inner_step(X[0], Y[0])
+    assert O.relu_margin > 2e-6, O.relu_margin   # no pre-activation within float32 rounding of the kink
+    np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=1e-5)
+    check(f"{name} grad", P.state()["grad"], O.last_grad, 1e-4)
+    P.parle_outer_step()
+    O.outer_step()
+    got = P.state()
+    for t in ("x", "y", "z", "vx", "x_ref"):
+        check(f"{name} {t}", got[t], getattr(O.st, t), 1e-5)
+
+
 def _cycle(pb, torch, a, n, B, L, bf16, seed, outer=1, **kw):
     P, O = make(pb, a, n, B, bf16=bf16, seed=seed, L=L, **kw)
     X, Y = synth.image_batches(seed, L * outer, n, B, a["H"], a["W"], a["C"], a["classes"])
