@@ -407,6 +407,10 @@ __global__ __launch_bounds__(kFinThreads) void k_bn_stats_finalize(int M, int C,
                                                                   float *__restrict__ saved, float *__restrict__ running,
                                                                   long long run_rs) {
   const int rep = blockIdx.y, c = blockIdx.x;
+  // the running statistics are fetched beside the partial sums, not in a round trip of their own after them
+  float *rm = running ? running + rep * run_rs : nullptr, *rv = running ? rm + C : nullptr;
+  float rm_old = 0.f, rv_old = 0.f;
+  if (running && threadIdx.x == 0) rm_old = rm[c], rv_old = rv[c];
   double s1, s2;
   sum_splits(partial, rep, S, C, c, s1, s2);
   if (threadIdx.x != 0) return;
@@ -416,10 +420,9 @@ __global__ __launch_bounds__(kFinThreads) void k_bn_stats_finalize(int M, int C,
   saved[(long long)rep * 2 * C + c] = (float)mean;
   saved[(long long)rep * 2 * C + C + c] = (float)(1.0 / sqrt(var + (double)kBnEps));
   if (running) {
-    float *rm = running + rep * run_rs, *rv = rm + C;
     const double unbiased = M > 1 ? var * ((double)M / (M - 1)) : var;
-    rm[c] = (1.f - kBnMomentum) * rm[c] + kBnMomentum * (float)mean;
-    rv[c] = (1.f - kBnMomentum) * rv[c] + kBnMomentum * (float)unbiased;
+    rm[c] = (1.f - kBnMomentum) * rm_old + kBnMomentum * (float)mean;
+    rv[c] = (1.f - kBnMomentum) * rv_old + kBnMomentum * (float)unbiased;
   }
 }
 
