@@ -513,7 +513,7 @@ hipError_t backward(const Run &r, float *grad) {
     const ConvGeom gb = bwd_geom(op, r.B);
     GemmIO io{};
     io.in = dy, io.in_rs = dy_rs;
-    io.w = r.ws + op.wt_off, io.w_rs = wsize;  // transposed at the start of the backward pass, all layers in one launch
+    io.w = r.ws + op.wt_off, io.w_rs = wsize;  // transposed once per step, all layers in one launch
     io.out = r.gptr(op.in), io.out_rs = r.trs(op.in), io.ldc = op.Cin;
     io.mask = op.mask_in ? r.tptr(op.in) : nullptr, io.mask_rs = r.trs(op.in);
     io.accumulate = op.dx_accumulate;
@@ -547,7 +547,7 @@ hipError_t backward(const Run &r, float *grad) {
         // lands behind a branch of leaves waits for them although nothing ties the two.
         if (op.need_dx && !op.branch) {
           if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
-          void *wt = r.ws + op.wt_off;  // transposed at the start of the backward pass, all layers in one launch
+          void *wt = r.ws + op.wt_off;  // transposed once per step, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
           if (op.col_off > 0) {
             // col = dy x W: the transposed weights, here ordered [RS][Cin][Cout], are the [N][K] operand as they lie
