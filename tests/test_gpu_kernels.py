@@ -76,6 +76,7 @@ CASES = [
     (2, 3, 16, 8, 16, 32, 1, 2, 0),     # strided 1x1: three of four parity classes reach no tap
     (1, 2, 32, 32, 32, 128, 3, 1, 1),   # backward-weight with nine taps per wavefront: two column blocks, 4 dy tiles
     (1, 3, 16, 16, 64, 160, 3, 1, 1),   # same, 5 dy tiles per workgroup
+    (1, 2, 16, 16, 32, 224, 3, 1, 1),   # 7 tiles of 32 output channels: no whole grouping of dy tiles, the transpose-read kernel
     (2, 3, 8, 8, 32, 128, 3, 1, 1),     # same, two 8 x 8 images per block, odd batch
     (1, 2, 24, 16, 32, 192, 3, 1, 1),   # same, two groups of 3 dy tiles, three row blocks per image
     (2, 4, 12, 12, 3, 16, 3, 1, 1),     # whole contraction in one tile (K = 27): first-layer kernel, ragged last tile
