@@ -39,6 +39,9 @@ struct ConvGeom {
   // (row-major over the blocks), parity class, position (i, j) of the 8 x 8 grid inside the block, i.e.
   // pixel (16*bi + 2*i + class/2, 16*bj + 2*j + class%2): a 256-row tile is one block, 64 rows per class.
   int pblk;
+  // Backward-weight only: wavefronts a launch of the nine-tap kernel should put in flight (0 = one per SIMD of
+  // the chip); the contraction is split over workgroups accordingly.
+  int leaf_waves;
 };
 
 struct GemmIO {

@@ -290,7 +290,8 @@ int wgrad9_plan(int replicas, const ConvGeom &g, int *chunk_out) {
     const int v = e ? atoi(e) : 0;
     return v > 0 ? v : 1024;
   }();
-  long long want = (waves / nt + tiles - 1) / tiles;
+  const int target = g.leaf_waves > 0 ? g.leaf_waves : waves;
+  long long want = (target / nt + tiles - 1) / tiles;
   if (want > wg.total_blocks / 4) want = wg.total_blocks / 4;
   if (want < 1) want = 1;
   const long long cap = 65535 / replicas;

@@ -78,6 +78,11 @@ struct Net {
   // All of a network's bias gradients or none: networks of small layers (LeNet, the MLP) lose more to the extra
   // events than the stream hides (+4 %), and a mix of both placements measured worst of all.
   bool bias_stream = false;
+  // Wavefronts a weight-gradient launch of the nine-tap kernel puts in flight.  Where batch-norm passes share
+  // the chain of input gradients, that chain is the longer one and the leaves have slack: they take half the
+  // chip's SIMDs and leave the rest to the chain (WRN-16-4 -3 %); without batch-norm the leaves are the longer
+  // side and take all of them (All-CNN-C: +3.7 % with half).
+  int leaf_waves = 0;
   // A layer without input gradient (the first one) is the last the backward pass reaches: nothing follows it on
   // the first stream, so its leaves run there, beside whatever the second stream still has queued (own scratch).
   int64_t off_wpartial_main = 0;
@@ -291,6 +296,7 @@ bool build_plan(Net &N, std::string &err) {
       return false;
   }
   // gradients, transposed weights, scratch
+  N.leaf_waves = N.max_bn_c > 0 ? 512 : 0;
   int64_t wpartial = 0, wpartial_main = 0, col_bytes = 0;
   for (Op &op : N.ops) {
     if (op.wseg < 0 && op.type == OP_CONV) {
@@ -315,7 +321,8 @@ bool build_plan(Net &N, std::string &err) {
           col_bytes = std::max(col_bytes, (int64_t)N.n * N.B * op.Ho * op.Wo * op.Cin * op.R * op.R * 4), op.col_off = 0;
       }
       // the complete forward geometry: the split plan depends on which kernel variant will run
-      const ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
+      ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
+      g.leaf_waves = N.leaf_waves;
       int chunk = 0;
       const int S = wgrad_plan(N.dtype, N.n, g, &chunk);
       if (S > 1 && (int64_t)N.n * S * wsize * 4 > (op.need_dx ? wpartial : wpartial_main))
@@ -528,7 +535,8 @@ hipError_t backward(const Run &r, float *grad) {
       case OP_CONV: {
         const void *dy = r.gptr(op.dy);
         const int64_t dy_rs = r.trs(op.dy);
-        const ConvGeom gf = fwd_geom(op, r.B);
+        ConvGeom gf = fwd_geom(op, r.B);
+        gf.leaf_waves = N.leaf_waves;
         // leaves: on the second stream once this op's output gradient is final.  A layer without input
         // gradient (the first one) leaves the first stream idle: its leaves run there, beside whatever the
         // second stream still has queued.
