@@ -996,8 +996,9 @@ hipError_t launch_gap_bwd(hipStream_t st, int dtype, int n, int B, int HW, int C
 }
 
 int colreduce_splits(int n, int M) {
-  // enough workgroups to fill the chip, at least 64 rows per split
-  int want = (1024 + n - 1) / n;
+  // two workgroups per compute unit (more splits cost the finalize kernel more than they gain the reduction:
+  // measured 256 .. 2048), at least 64 rows per split
+  int want = (512 + n - 1) / n;
   int maxs = (M + 63) / 64;
   if (want > maxs) want = maxs;
   if (want < 1) want = 1;
