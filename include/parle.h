@@ -98,6 +98,11 @@ typedef enum {
  *   key = mix(mix(seed + 0x9E3779B9*k) ^ (a*0x85EBCA6B + s*0xC2B2AE35 + 1)),   all modulo 2^32,
  *   mix(x): x ^= x >> 16; x *= 0x7FEB352D; x ^= x >> 15; x *= 0x846CA68B; x ^= x >> 16,
  * kept elements are multiplied by 1 / (1 - dropout); parle_eval applies no dropout.
+ * The multipliers are public-domain integer-hash constants, not the paper's: 0x7FEB352D / 0x846CA68B
+ * with shifts 16-15-16 are the "lowbias32" finaliser found by C. Wellons' hash-prospector search,
+ * 0x9E3779B9 is 2^32 / golden ratio (Knuth's multiplicative hashing), 0x85EBCA6B / 0xC2B2AE35 are the
+ * two multipliers of MurmurHash3's 32-bit finaliser (A. Appleby); here the last three only decorrelate
+ * the counters that enter the key.
  * Loss: mean over the replica's mini-batch of the softmax cross-entropy (Section 1.1).
  * ReLU'(0) = 0.  maxpool2 = 2x2 window, stride 2, floor; gradient to the first maximum in
  * row-major window order.

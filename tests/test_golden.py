@@ -1,4 +1,4 @@
-"""The values Section 3.2 prints (tests/golden/hyperparameters_section_3_2.txt) against the oracle.
+"""The values Section 3.1 prints (tests/golden/hyperparameters_section_3_1.txt) against the oracle.
 
 The fixture is in the paper's notation (gamma, rho); the oracle computes with the multipliers g = 1/gamma and
 r = 1/rho, so the test converts on its own side and evaluates rule (9) in the paper's form.
@@ -10,7 +10,7 @@ import numpy as np
 
 from oracle import parle
 
-GOLDEN = pathlib.Path(__file__).parent / "golden" / "hyperparameters_section_3_2.txt"
+GOLDEN = pathlib.Path(__file__).parent / "golden" / "hyperparameters_section_3_1.txt"
 
 
 def _read():

@@ -332,3 +332,161 @@ def test_dropout_off_in_evaluation_and_lenet_bn_layout():
     nets.loss_and_grad(a, flat, X, Y, bn_state=bn, drop=dict(p=0.5, seed=1, step=0, replica=0))
     assert not np.allclose(bn["bn3"][0], 0)                # running statistics moved
     assert nets.evaluate(a, flat, X, Y, bn_state=bn) == nets.evaluate(a, flat, X, Y, bn_state=bn)
+
+
+# ---- wiring of the networks, written out layer by layer from their definitions on tiny inputs ----------------
+def _bn_train_bruteforce(x, gam, bet):
+    C = x.shape[-1]
+    out = np.empty_like(x)
+    for c in range(C):
+        v = x[..., c]
+        m = v.sum() / v.size
+        var = ((v - m) ** 2).sum() / v.size
+        out[..., c] = (v - m) / np.sqrt(var + 1e-5) * gam[c] + bet[c]
+    return out
+
+
+def _allcnn_bruteforce(a, P, x):
+    """All-CNN-C as its layer list reads: seven 3x3 convolutions with padding 1 (the third and the sixth with
+    stride 2), two 1x1 convolutions, a ReLU after every convolution but the last, then the spatial mean."""
+    spec = [(1, 1), (1, 1), (2, 1), (1, 1), (1, 1), (2, 1), (1, 1), (1, 0), (1, 0)]
+    h = x
+    for i, (stride, pad) in enumerate(spec):
+        h = _conv_bruteforce(h, P[f"conv{i + 1}.w"], P[f"conv{i + 1}.b"], stride, pad)
+        if i != len(spec) - 1:
+            h = np.where(h > 0, h, 0.0)
+    return h.sum(axis=(1, 2)) / (h.shape[1] * h.shape[2])
+
+
+def _wrn_bruteforce(a, P, x, zero_block=None):
+    """Pre-activation wide residual network: conv, then blocks BN-ReLU-conv-BN-ReLU-conv; an identity block
+    adds its input, a block that changes width or resolution adds a strided 1x1 convolution of its BN-ReLU
+    output; BN-ReLU, spatial mean, linear classifier.  ``zero_block`` returns after that block the tensor
+    a block with both 3x3 convolutions at zero must produce (its shortcut branch alone)."""
+    h = _conv_bruteforce(x, P["conv1.w"], None, 1, 1)
+    widths = [a["base"] * a["widen"] * m for m in (1, 2, 4)]
+    cin = a["base"]
+    for gi, cout in enumerate(widths):
+        for bi in range(a["nb"]):
+            name = f"g{gi + 1}b{bi + 1}"
+            stride = 2 if (gi > 0 and bi == 0) else 1
+            o = np.maximum(_bn_train_bruteforce(h, P[name + ".bn1.g"], P[name + ".bn1.b"]), 0.0)
+            u = _conv_bruteforce(o, P[name + ".conv1.w"], None, stride, 1)
+            u = np.maximum(_bn_train_bruteforce(u, P[name + ".bn2.g"], P[name + ".bn2.b"]), 0.0)
+            u = _conv_bruteforce(u, P[name + ".conv2.w"], None, 1, 1)
+            if cin != cout or stride != 1:
+                branch = _conv_bruteforce(o, P[name + ".sc.w"], None, stride, 0)
+            else:
+                branch = h
+            if name == zero_block:
+                assert not u.any()
+                return branch
+            h = u + branch
+            cin = cout
+    h = np.maximum(_bn_train_bruteforce(h, P["bn_out.g"], P["bn_out.b"]), 0.0)
+    pooled = h.sum(axis=(1, 2)) / (h.shape[1] * h.shape[2])
+    return pooled @ P["fc.w"].T + P["fc.b"]
+
+
+def test_allcnn_wiring_bruteforce():
+    a = TINY["allcnn"]
+    p = synth.init_params(nets.layout(a), seed=31).astype(np.float64)
+    x, _ = _data(a, 2, 32)
+    ref = _allcnn_bruteforce(a, nets.unpack(a, p), x)
+    assert np.allclose(nets.logits_only(a, p, x), ref, rtol=0, atol=1e-12)
+
+
+def test_allcnn_last_convolution_has_no_relu():
+    """A last convolution with weights -1 and bias 0 on non-negative inputs gives negative logits; a ReLU
+    behind it would return zeros."""
+    a = TINY["allcnn"]
+    p = synth.init_params(nets.layout(a), seed=33).astype(np.float64)
+    P = nets.unpack(a, p)                                  # views into p
+    for i in range(1, 9):
+        P[f"conv{i}.b"][...] = 0.25                        # keeps every hidden layer alive
+    P["conv9.w"][...] = -1.0
+    P["conv9.b"][...] = 0.0
+    x, _ = _data(a, 3, 34)
+    logits = nets.logits_only(a, p, x)
+    assert (logits < 0).all()
+
+
+def test_wrn_wiring_bruteforce():
+    a = TINY["wrn"]
+    p = synth.init_params(nets.layout(a), seed=35).astype(np.float64)
+    x, _ = _data(a, 3, 36)
+    ref = _wrn_bruteforce(a, nets.unpack(a, p), x)
+    assert np.allclose(nets.logits_only(a, p, x, bn_state=nets.new_bn_state(a)), ref, rtol=0, atol=1e-10)
+
+
+def test_wrn_block_with_zero_convolutions_is_its_shortcut():
+    """Zero both 3x3 convolutions of a block: what the block hands on is the strided 1x1 convolution of its
+    BN-ReLU output.  That tensor is computed by hand (brute force) and pushed through a brute-force copy of
+    the remaining blocks and the head; the oracle, run end to end with the zeroed weights, must give the
+    same logits."""
+    a = nets.arch("wrn", H=8, W=8, C=2, base=2, widen=2, nb=1, classes=3)
+    x, _ = _data(a, 3, 38)
+    names = [b[0] for b in nets.wrn_blocks(a)]
+    for name in names:
+        p = synth.init_params(nets.layout(a), seed=37).astype(np.float64)
+        P = nets.unpack(a, p)                               # views into p
+        P[name + ".conv1.w"][...] = 0.0
+        P[name + ".conv2.w"][...] = 0.0
+        h = _wrn_bruteforce(a, P, x, zero_block=name)       # the shortcut branch alone
+        assert h.shape[-1] == P[name + ".sc.w"].shape[0]
+        for nm in names[names.index(name) + 1:]:            # every later block halves the resolution (nb = 1)
+            o = np.maximum(_bn_train_bruteforce(h, P[nm + ".bn1.g"], P[nm + ".bn1.b"]), 0.0)
+            u = _conv_bruteforce(o, P[nm + ".conv1.w"], None, 2, 1)
+            u = np.maximum(_bn_train_bruteforce(u, P[nm + ".bn2.g"], P[nm + ".bn2.b"]), 0.0)
+            h = _conv_bruteforce(u, P[nm + ".conv2.w"], None, 1, 1) + _conv_bruteforce(o, P[nm + ".sc.w"], None, 2, 0)
+        h = np.maximum(_bn_train_bruteforce(h, P["bn_out.g"], P["bn_out.b"]), 0.0)
+        want = (h.sum(axis=(1, 2)) / (h.shape[1] * h.shape[2])) @ P["fc.w"].T + P["fc.b"]
+        got = nets.logits_only(a, p, x, bn_state=nets.new_bn_state(a))
+        assert np.allclose(got, want, rtol=0, atol=1e-10), name
+
+
+def test_dropout_layer_keeps_the_mean_of_a_constant_tensor():
+    """Inverted dropout: kept units are scaled by 1 / (1 - p), so a constant tensor keeps its mean up to the
+    binomial fluctuation of the keep count (4 sigma) and the 2^-24 grid of the threshold."""
+    n, c = 400_000, 3.0
+    for p in (0.25, 0.3, 0.4, 0.5):
+        keep = nets.dropout_keep(seed=11, step=5, replica=2, site=1, count=n, p=p)
+        t = nets.Tape()
+        xv = nets.Var(np.full((n,), c))
+        o = nets.dropout(t, xv, keep, p)
+        sigma = c * np.sqrt(p / ((1 - p) * n))
+        assert abs(o.v.mean() - c) < 4 * sigma + c * 2.0 ** -20, p
+        kept = o.v[o.v != 0]
+        assert np.allclose(kept, c / (1 - float(np.float32(p))), rtol=1e-12)      # the scale itself, p taken in float32
+        o.g = np.ones(n)
+        t.backward()
+        assert np.array_equal(xv.g != 0, keep) and np.allclose(xv.g[keep], 1 / (1 - float(np.float32(p))), rtol=1e-12)
+
+
+def test_reference_is_evaluated_with_replica_averaged_running_statistics():
+    """The averaged model has no batch of its own: evaluation at the reference uses the mean over replicas of
+    the running batch-norm statistics.  Two replicas, different batches, hand average."""
+    from oracle import parle, trainer
+    a = TINY["wrn"]
+    p0 = synth.init_params(nets.layout(a), seed=41).astype(np.float64)
+    cfg = parle.ParleConfig(n_replicas=2, gamma0=0.03, rho0=1.0, eta_inner=0.05, eta_outer=0.05)
+    net = trainer.ParleNet(a, cfg, np.tile(p0, (2, 1)))
+    rng = np.random.default_rng(42)
+    for s in range(2):
+        X = rng.standard_normal((2, 4, a["H"], a["W"], a["C"])) * (1.0 + np.arange(2)[:, None, None, None, None])
+        Y = rng.integers(0, a["classes"], (2, 4))
+        net.inner_step(X, Y)
+    net.outer_step()
+    Xe, Ye = _data(a, 6, 43)
+    hand = {k: [0.5 * (net.bn[0][k][0] + net.bn[1][k][0]), 0.5 * (net.bn[0][k][1] + net.bn[1][k][1])]
+            for k in net.bn[0]}
+    want = nets.evaluate(a, net.st.x_ref, Xe, Ye, bn_state=hand)
+    got = net.eval(-1, Xe, Ye)
+    assert np.isclose(got[0], want[0], rtol=1e-13) and got[1] == want[1]
+    for one in (0, 1):                                      # and not with one replica's statistics
+        other = nets.evaluate(a, net.st.x_ref, Xe, Ye, bn_state=net.bn[one])
+        assert abs(other[0] - got[0]) > 1e-6
+    # a replica is evaluated with its own parameters and statistics
+    assert net.eval(1, Xe, Ye)[:2] == nets.evaluate(a, net.st.x[1], Xe, Ye, bn_state=net.bn[1])
+    e0, e1 = net.st.x[0] - net.st.x_ref, net.st.x[1] - net.st.x_ref
+    assert np.isclose(got[2], e0 @ e0 + e1 @ e1, rtol=1e-12)

@@ -259,3 +259,132 @@ def test_weight_decay_is_gradient_of_l2_term():
     st = parle.init_state(x0, cfg)
     parle.inner_update(st, np.zeros_like(x0), cfg)
     assert np.allclose(st.y, x0 * (1 - 0.05))
+
+
+# ---- (8c) in its default form: the unscaled gradient of local entropy, g (x^a - z^a) ------------------------
+def test_outer_step_default_mode_hand_computed_numbers():
+    """Two scalar replicas, momentum 0, z != x, g = 0.5, r = 1, eta = 0.1; numbers worked by hand:
+    mean = 2;  replica 0: d = 0.5 (1 - 0.5) + 1 (1 - 2) = -0.75  ->  x = 1.075;
+               replica 1: d = 0.5 (3 - 3.5) + 1 (3 - 2) =  0.75  ->  x = 2.925."""
+    cfg = _cfg(2, gamma0=0.5, rho0=1.0, momentum=0.0, eta_outer=0.1, xa_mode=0)
+    st = parle.init_state(np.array([[1.0], [3.0]]), cfg)
+    st.z = np.array([[0.5], [3.5]])
+    st.inner_since_outer = 1
+    parle.outer_step(st, cfg)
+    assert np.allclose(st.x[:, 0], [1.075, 2.925], rtol=0, atol=1e-15)
+    assert np.allclose(st.x_ref, [2.0]) and np.array_equal(st.y, st.x) and np.array_equal(st.z, st.x)
+    # the printed form of (8c) (coefficient 1 on x - z) from the same state: d = 0.5 - 1, -0.5 + 1
+    cfg1 = _cfg(2, gamma0=0.5, rho0=1.0, momentum=0.0, eta_outer=0.1, xa_mode=1)
+    st = parle.init_state(np.array([[1.0], [3.0]]), cfg1)
+    st.z = np.array([[0.5], [3.5]])
+    st.inner_since_outer = 1
+    parle.outer_step(st, cfg1)
+    assert np.allclose(st.x[:, 0], [1.05, 2.95], rtol=0, atol=1e-15)
+
+
+def test_outer_step_default_mode_with_momentum_two_steps_hand_computed():
+    """One replica (so the elastic term vanishes), g = 0.5, eta = 0.1, momentum 0.9, z held at 0 by hand:
+    step 1: d = 0.5 * 2 = 1, v = 1, x = 2 - 0.1 (1 + 0.9) = 1.81;
+    step 2: d = 0.905, v = 0.9 + 0.905 = 1.805, x = 1.81 - 0.1 (0.905 + 1.6245) = 1.55705."""
+    cfg = _cfg(1, gamma0=0.5, rho0=1.0, momentum=0.9, eta_outer=0.1, xa_mode=0)
+    st = parle.init_state(np.array([[2.0]]), cfg)
+    for want in (1.81, 1.55705):
+        st.z = np.zeros((1, 1))
+        st.inner_since_outer = 1
+        parle.outer_step(st, cfg)
+        assert np.allclose(st.x, want, rtol=0, atol=1e-14)
+
+
+def test_default_outer_step_is_gradient_descent_on_local_entropy_of_a_quadratic():
+    """Remark "Scoping and learning rate annealing": grad f_gamma(x) = (x - <y>) / gamma.  For
+    f(y) = c y^2 / 2 the Gibbs measure of (3) is Gaussian with mean x / (1 + gamma c), so
+    grad f_gamma(x) = c x / (1 + gamma c) in closed form.  With exact gradients the y-chain of (8a)
+    settles at that mean and z follows it, so one default-mode outer step (no elastic term, no momentum)
+    must be x <- x - eta c x / (1 + gamma c)."""
+    c, gamma, eta = 3.0, 0.25, 0.2
+    cfg = _cfg(1, L=400, gamma0=1.0 / gamma, rho0=0.0, momentum=0.0, eta_inner=0.05, eta_outer=eta, alpha=0.75,
+               xa_mode=0)
+    st = parle.init_state(np.array([[1.5, -0.7]]), cfg)
+    x = np.array([1.5, -0.7])
+    for _ in range(3):
+        for _ in range(cfg.L):
+            parle.inner_update(st, c * st.y, cfg)
+        assert np.allclose(st.z[0], x / (1 + gamma * c), atol=1e-12)
+        parle.outer_step(st, cfg)
+        x = x - eta * c * x / (1 + gamma * c)
+        assert np.allclose(st.x[0], x, atol=1e-12)
+
+
+def test_first_outer_step_uses_the_initial_couplings():
+    """Rule (9) with exponent floor(k/L) counted in completed outer steps: the outer step that closes the
+    first block still sees gamma_0 and rho_0.  g0 = 0.5 doubles to 1 (B = 1) only afterwards:
+    d = 0.5 (1 - 0) + 1 (1 - 0) with the mean of +-1 at 0 -> x = 1 - 0.1 * 1.5 = 0.85."""
+    cfg = _cfg(2, gamma0=0.5, rho0=1.0, gamma_max=4.0, rho_max=10.0, scoping_B=1, momentum=0.0, eta_outer=0.1)
+    st = parle.init_state(np.array([[1.0], [-1.0]]), cfg)
+    st.z = np.zeros((2, 1))
+    st.inner_since_outer = 1
+    parle.outer_step(st, cfg)
+    assert np.allclose(st.x[:, 0], [0.85, -0.85], rtol=0, atol=1e-15)
+    assert st.g == 1.0 and st.r == 2.0
+    # the next inner step is pulled with the doubled g = 1: from y = x + 1, d = 1, y - x = 1 - 0.1 = 0.9
+    st.y = st.x + 1.0
+    parle.inner_update(st, np.zeros((2, 1)), cfg)
+    assert np.allclose(st.y - st.x, 0.9, rtol=0, atol=1e-15)
+
+
+# ---- the reset after the outer step (y^a <- x^a is stated; z^a and the y-momentum are readings) ---------------
+def test_reset_clears_the_y_momentum_and_the_flag_that_keeps_it():
+    """Constant gradient 1, no couplings (x never moves), eta' = 0.1, mu = 0.9.  By hand:
+    block 1: v = 1, y = -0.19; v = 1.9, y = -0.19 - 0.1 (1 + 1.71) = -0.461.
+    fresh chain after the reset: v = 1, y = -0.19.
+    momentum carried over instead: v = 0.9 * 1.9 + 1 = 2.71, y = 0 - 0.1 (1 + 2.439) = -0.3439."""
+    for flags, first in ((3, -0.19), (1, -0.3439)):
+        cfg = _cfg(1, gamma0=0.0, rho0=0.0, momentum=0.9, eta_inner=0.1, reset_flags=flags)
+        st = parle.init_state(np.zeros((1, 1)), cfg)
+        parle.inner_update(st, np.ones((1, 1)), cfg)
+        assert np.allclose(st.y, -0.19, atol=1e-15)
+        parle.inner_update(st, np.ones((1, 1)), cfg)
+        assert np.allclose(st.y, -0.461, atol=1e-15)
+        parle.outer_step(st, cfg)
+        assert st.x[0, 0] == 0.0 and st.y[0, 0] == 0.0
+        parle.inner_update(st, np.ones((1, 1)), cfg)
+        assert np.allclose(st.y, first, atol=1e-15), flags
+
+
+def test_reset_of_z_and_the_flag_that_keeps_it():
+    """alpha = 0.5, constant gradient -1, eta' = 1, no momentum: y = 1, z = 0.5 after one step.  The outer step
+    (no couplings) leaves x = 0; bit 0 of reset_flags restarts z at x, without it z stays 0.5."""
+    for flags, want in ((3, 0.0), (2, 0.5)):
+        cfg = _cfg(1, gamma0=0.0, rho0=0.0, momentum=0.0, eta_inner=1.0, alpha=0.5, reset_flags=flags)
+        st = parle.init_state(np.zeros((1, 1)), cfg)
+        parle.inner_update(st, -np.ones((1, 1)), cfg)
+        assert st.y[0, 0] == 1.0 and st.z[0, 0] == 0.5
+        parle.outer_step(st, cfg)
+        assert st.z[0, 0] == want and st.y[0, 0] == 0.0
+
+
+def test_weight_decay_acts_on_y_not_on_x():
+    """f contains the regulariser (Section 1.1), so its gradient in (8a) is taken where the data gradient
+    is: at y.  With zero data gradient and no coupling y_k = (1 - eta' wd)^k y_0; by hand 2 -> 1.9 -> 1.805
+    (the decay of the anchor x instead would give 1.8).  With the proximal term on, by hand:
+    step 1: d = 0.5 * 2 = 1, y = 1.9;  step 2: d = 0.5 * 1.9 + 0.3 (1.9 - 2) = 0.92, y = 1.808."""
+    cfg = _cfg(1, gamma0=0.0, rho0=0.0, momentum=0.0, weight_decay=0.5, eta_inner=0.1)
+    st = parle.init_state(np.array([[2.0]]), cfg)
+    for k in range(1, 6):
+        parle.inner_update(st, np.zeros((1, 1)), cfg)
+        assert np.allclose(st.y, 2.0 * 0.95 ** k, atol=1e-15)
+    cfg = _cfg(1, gamma0=0.3, rho0=0.0, momentum=0.0, weight_decay=0.5, eta_inner=0.1)
+    st = parle.init_state(np.array([[2.0]]), cfg)
+    parle.inner_update(st, np.zeros((1, 1)), cfg)
+    parle.inner_update(st, np.zeros((1, 1)), cfg)
+    assert np.allclose(st.y, 1.808, atol=1e-15)
+
+
+def test_spread_closed_form():
+    """Two replicas at +-e around a reference at their mean: sum_a ||x^a - x||^2 = 2 ||e||^2."""
+    e = np.array([3.0, -4.0, 12.0])                       # ||e||^2 = 169
+    cfg = _cfg(2)
+    st = parle.init_state(np.stack([5.0 + e, 5.0 - e]), cfg)
+    assert np.allclose(st.x_ref, 5.0) and parle.spread(st) == 338.0
+    st = parle.init_state(np.tile(e, (4, 1)), _cfg(4))    # collapsed ensemble
+    assert parle.spread(st) == 0.0
