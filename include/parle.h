@@ -281,6 +281,20 @@ parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, fl
 parle_status parle_k_spread(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
                             double *partial_dev, float *out_dev);
 
+/* parle_k_spread for callers that cannot allocate device memory or pass a scratch buffer along: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same result, same
+ * kernels; the per-workgroup partial sums live in a 32 KiB array that is part of the library's device
+ * image (one copy per GPU, held until the process ends), and the call allocates and frees nothing.
+ * x, x_ref, out_dev as for parle_k_spread (device pointers, 16-byte aligned, caller-owned; out_dev[0]
+ * receives the fp32 sum).  n * n_pad <= PARLE_SPREAD_STATIC_MAX_ELEMS, else PARLE_ESIZE; EINVAL / EALIGN /
+ * EHIP as usual, with a text behind parle_last_error(NULL).  Every call on a GPU uses that GPU's one
+ * array: calls that overlap on one GPU (different streams, different threads) race on it and must be
+ * ordered by the caller; calls on one stream are safe.  Nothing in the array needs clearing between
+ * calls: the second kernel reads only the slots the first kernel of the same call wrote. */
+#define PARLE_SPREAD_STATIC_MAX_ELEMS (1LL << 34)
+parle_status parle_k_spread_static(void *hip_stream, int32_t n, int64_t n_pad, const float *x, const float *x_ref,
+                                   float *out_dev);
+
 /* Measurement aid, not a step of the method: `reads` arrays of `count` floats are read from src_dev
  * (laid out one after the other) and `writes` arrays of `count` floats written to dst_dev, with the
  * access shape of the update kernels (16 bytes per lane, non-temporal) and no arithmetic that matters.

@@ -79,6 +79,7 @@ _SIGNATURES = {
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_float,
                              C.c_int32, C.c_int32, C.c_int32],
     "parle_k_spread": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_k_spread_static": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p],
     "parle_k_stream_reference": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
     "parle_k_conv_forward": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int32, C.c_void_p],
@@ -197,6 +198,11 @@ def parle_k_stream_reference(reads, writes, count, src, dst, stream=None):
 def parle_k_spread(x, x_ref, partial, out, stream=None):
     n, n_pad = x.shape
     _check(lib().parle_k_spread(_stream_handle(stream), n, n_pad, _ptr(x), _ptr(x_ref), _ptr(partial), _ptr(out)))
+
+
+def parle_k_spread_static(x, x_ref, out, stream=None):
+    n, n_pad = x.shape
+    _check(lib().parle_k_spread_static(_stream_handle(stream), n, n_pad, _ptr(x), _ptr(x_ref), _ptr(out)))
 
 
 def parle_k_conv_forward(desc, x, w, bias, resid, relu, y, stream=None):

@@ -28,6 +28,8 @@ struct parle_ctx {
   int32_t gk_steps = 0;
 };
 
+void parle_internal_set_error(const std::string &msg);
+
 namespace {
 
 constexpr int64_t kRowAlign = 1024;      // elements: every replica row starts 4 KiB aligned
@@ -45,6 +47,12 @@ parle_status fail(parle_ctx *ctx, parle_status s, const std::string &msg) {
     g_init_err = msg;
   return s;
 }
+
+}  // namespace
+
+void parle_internal_set_error(const std::string &msg) { g_init_err = msg; }
+
+namespace {
 
 parle_status check_config(const parle_config *cfg, Arch &arch, std::string &msg) {
   if (!cfg) {

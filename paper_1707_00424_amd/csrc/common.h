@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <string>
+
 #include "../../include/parle.h"
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -43,6 +45,9 @@ __device__ __forceinline__ float wave_sum(float v) {
   for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) v += __shfl_down(v, off, PARLE_WAVE);
   return v;
 }
+
+// Text behind parle_last_error(NULL) for entry points that have no context (calling thread only).
+void parle_internal_set_error(const std::string &msg);
 
 static inline bool aligned_to(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 

@@ -3,6 +3,9 @@
 // accesses; nothing is reused, so loads and stores are non-temporal.
 #include <stdlib.h>
 
+#include <mutex>
+#include <string>
+
 #include "common.h"
 
 namespace {
@@ -261,6 +264,12 @@ __global__ void k_set_coupling(float *dst, float g, float r) {
 // reduction on; per-block partials are summed by one block in a fixed order (deterministic).
 // ---------------------------------------------------------------------------------------------
 constexpr int kSpreadBlocks = 4096;
+
+// Scratch of the entry point that allocates nothing: the per-workgroup partial sums of one spread launch,
+// 32 KiB per GPU, held until the process ends.  In host code this name is only a stand-in for the symbol:
+// the device address is fetched once per device (static_spread_scratch below) and that pointer is what
+// kernels receive.
+static __device__ __align__(256) double scratch[kSpreadBlocks];
 
 __global__ __launch_bounds__(kThreads) void k_spread_partial(const f4 *__restrict__ X, const f4 *__restrict__ XR,
                                                              int n, int64_t np4, double *__restrict__ partial) {
@@ -566,3 +575,51 @@ parle_status parle_k_stream_reference(void *hip_stream, int32_t reads, int32_t w
 }
 
 }  // extern "C"
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+double *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (every GPU holds its own copy of the array).
+parle_status static_spread_scratch(double **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    parle_internal_set_error("parle_k_spread_static: no current HIP device (or device index >= 64)");
+    return PARLE_EHIP;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      parle_internal_set_error(std::string("parle_k_spread_static: hipGetSymbolAddress failed: ") + hipGetErrorString(e));
+      return PARLE_EHIP;
+    }
+    g_scratch_ptr[dev] = (double *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PARLE_OK;
+}
+}  // namespace
+
+extern "C" parle_status parle_k_spread_static(void *hip_stream, int32_t n, int64_t n_pad, const float *x,
+                                              const float *x_ref, float *out_dev) {
+  if (n < 1 || n_pad < 4 || (n_pad & 3) || !x || !x_ref || !out_dev) {
+    parle_internal_set_error("parle_k_spread_static: n >= 1, n_pad a positive multiple of 4 and non-null pointers needed");
+    return PARLE_EINVAL;
+  }
+  if ((double)n * (double)n_pad > (double)PARLE_SPREAD_STATIC_MAX_ELEMS) {
+    parle_internal_set_error("parle_k_spread_static: n * n_pad exceeds PARLE_SPREAD_STATIC_MAX_ELEMS (2^34); use "
+                             "parle_k_spread with a scratch buffer of the caller's");
+    return PARLE_ESIZE;
+  }
+  if (!aligned_to(x, 16) || !aligned_to(x_ref, 16)) {
+    parle_internal_set_error("parle_k_spread_static: x and x_ref must be 16-byte aligned");
+    return PARLE_EALIGN;
+  }
+  double *partial = nullptr;
+  if (parle_status s = static_spread_scratch(&partial)) return s;
+  // every slot the second kernel reads is written by the first one of the same call: nothing to clear
+  return parle_k_spread(hip_stream, n, n_pad, x, x_ref, partial, out_dev);
+}

@@ -139,6 +139,19 @@ def test_null_arguments_do_not_crash():
     assert L.parle_init(C.byref(cfg), C.byref(bufs), None, C.byref(h)) == pb.PARLE_EALIGN
 
 
+def test_static_spread_rejects_bad_sizes_before_touching_the_device():
+    # fake, never dereferenced pointers: every rejection below happens in the host-side argument checks
+    L = pb.lib()
+    a = 4096
+    assert L.parle_k_spread_static(None, 2, (1 << 33) + 4, a, a, a) == pb.PARLE_ESIZE
+    assert b"PARLE_SPREAD_STATIC_MAX_ELEMS" in L.parle_last_error(None)
+    assert L.parle_k_spread_static(None, 0, 8, a, a, a) == pb.PARLE_EINVAL
+    assert L.parle_k_spread_static(None, 2, 6, a, a, a) == pb.PARLE_EINVAL
+    assert L.parle_k_spread_static(None, 2, 8, a, None, a) == pb.PARLE_EINVAL
+    assert L.parle_k_spread_static(None, 2, 8, a + 4, a, a) == pb.PARLE_EALIGN
+    assert b"16-byte" in L.parle_last_error(None)
+
+
 def test_struct_layouts_match_the_header(tmp_path):
     """The ctypes mirrors of the ABI structs have the size and field offsets a C compiler gives the header."""
     structs = {"parle_config": pb.parle_config, "parle_sizes": pb.parle_sizes, "parle_segment": pb.parle_segment,
