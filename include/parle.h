@@ -329,6 +329,55 @@ parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_des
                                           float *scratch, int64_t scratch_bytes, float *dw);
 int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc); /* -1 on a bad descriptor */
 
+/* ------------------------------------------------------------------------------------------
+ * The memory-bound layer kernels of the same forward / backward pass (Section 1.1's loss; the
+ * batch-norm, dropout and pooling layers of the networks of Section 4), one layer each.
+ * Tensors are DEVICE pointers, 16-byte aligned, channels-last, one block per replica:
+ *   [n][batch, h, w, c] in the activation format (dtype 0: fp32, 1: bf16 raw 16-bit; results are
+ *   computed in fp32 and rounded to nearest even once, on the store).
+ * Per-channel parameters and results are fp32 [n][c].  `scratch` holds the partial sums of the
+ * column reductions: parle_k_layer_scratch_bytes(desc) bytes (-1 on a bad descriptor), ESIZE if less.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t dtype, n, batch, h, w, c;
+} parle_act_desc;
+int64_t parle_k_layer_scratch_bytes(const parle_act_desc *desc);
+
+/* Training-mode batch-norm + ReLU: per replica and channel, mean and biased variance over the
+ * batch*h*w rows; out = max(0, gamma*(x - mean)/sqrt(var + 1e-5) + beta).  saved [n][2][c] receives
+ * mean and 1/sqrt(var + eps); running [n][2][c] (mean, variance; may be NULL) is updated with momentum 0.1
+ * and the unbiased variance. */
+parle_status parle_k_bn_forward(void *hip_stream, const parle_act_desc *desc, const void *x, const float *gamma,
+                                const float *beta, void *scratch, int64_t scratch_bytes, float *saved, float *running,
+                                void *out);
+/* Its backward: with xhat = (x - mean)*rstd and d = dout where gamma*xhat + beta > 0, else 0:
+ *   dbeta = sum d, dgamma = sum d*xhat, dx = gamma*rstd*(d - dbeta/M - xhat*dgamma/M) (+ add, like x, or NULL).
+ * sums [n][2][c] is a work buffer (the two sums in fp32). */
+parle_status parle_k_bn_backward(void *hip_stream, const parle_act_desc *desc, const void *x, const void *dout,
+                                 const float *gamma, const float *beta, const float *saved, const void *add,
+                                 void *scratch, int64_t scratch_bytes, float *sums, float *dgamma, float *dbeta, void *dx);
+/* 2x2 max-pool, stride 2, floor: in [n][batch,h,w,c] -> out [n][batch,h/2,w/2,c].  Backward: dout goes to the
+ * first maximum of each window in row-major order (times (in > 0) when relu_mask != 0), zero elsewhere. */
+parle_status parle_k_maxpool_forward(void *hip_stream, const parle_act_desc *desc, const void *in, void *out);
+parle_status parle_k_maxpool_backward(void *hip_stream, const parle_act_desc *desc, const void *in, const void *dout,
+                                      int32_t relu_mask, void *din);
+/* Global average pool over h*w: out [n][batch, c] (fp32 when out_f32 != 0, else the activation format);
+ * backward: din = dout / (h*w) at every position. */
+parle_status parle_k_gap_forward(void *hip_stream, const parle_act_desc *desc, int32_t out_f32, const void *in, void *out);
+parle_status parle_k_gap_backward(void *hip_stream, const parle_act_desc *desc, const void *dout, void *din);
+/* Dropout with the keep-mask defined at parle_config (site `site`, rate p, inner step read from step_dev[0]):
+ * out = keep ? in / (1 - p) : 0, additionally zero where relu_src <= 0 when relu_src (like in) is given.
+ * The same call applied to a gradient is the backward pass. */
+parle_status parle_k_dropout(void *hip_stream, const parle_act_desc *desc, const void *in, const void *relu_src,
+                             uint32_t seed, const int64_t *step_dev, int32_t site, float p, void *out);
+/* grad [n][c] = sum over the batch*h*w rows of dy (the bias gradient of a layer). */
+parle_status parle_k_bias_grad(void *hip_stream, const parle_act_desc *desc, const void *dy, void *scratch,
+                               int64_t scratch_bytes, float *grad);
+/* Mean softmax cross-entropy of each replica's batch: logits fp32 [n][batch, classes], labels [n][batch];
+ * loss [n] (may be NULL); dlogits (activation format) = (softmax - onehot) / batch. */
+parle_status parle_k_softmax_xent(void *hip_stream, int32_t dtype, int32_t n, int32_t batch, int32_t classes,
+                                  const float *logits, const int32_t *labels, float *loss, void *dlogits);
+
 #ifdef __cplusplus
 }
 #endif

@@ -190,6 +190,8 @@ class Tape:
     def __init__(self):
         self.back = []
         self.relu_margin = np.inf  # smallest non-zero |input| any ReLU saw (diagnostic, see relu())
+        self.pool_margin = np.inf  # smallest lead of a positive window maximum over the runner-up (see maxpool2())
+        self.decisions = []        # (kind, margin, largest |input|) of every ReLU / max-pool, in forward order
 
     def backward(self):
         for fn in reversed(self.back):
@@ -254,6 +256,7 @@ def relu(t, x):
     nz = np.abs(x.v[x.v != 0])
     if nz.size:
         t.relu_margin = min(t.relu_margin, float(nz.min()))
+    t.decisions.append(("relu", float(nz.min()) if nz.size else np.inf, float(nz.max()) if nz.size else 0.0))
     t.back.append(lambda: x.acc(o.g * (x.v > 0)))
     return o
 
@@ -265,6 +268,13 @@ def maxpool2(t, x):
     win = np.stack([x.v[:, i:2 * Ho:2, j:2 * Wo:2, :] for i in (0, 1) for j in (0, 1)], axis=0)
     idx = np.argmax(win, axis=0)          # first maximum on ties
     o = Var(np.take_along_axis(win, idx[None], axis=0)[0])
+    # diagnostic, outside the arithmetic: how close any window came to routing its gradient elsewhere.  Windows
+    # whose maximum is not positive do not count: behind a ReLU they are ties at zero that carry no gradient.
+    top2 = np.sort(win, axis=0)[-2:]
+    lead = (top2[1] - top2[0])[top2[1] > 0]
+    if lead.size:
+        t.pool_margin = min(t.pool_margin, float(lead.min()))
+    t.decisions.append(("maxpool", float(lead.min()) if lead.size else np.inf, float(np.abs(win).max())))
 
     def back():
         dx = np.zeros_like(x.v)
@@ -357,8 +367,28 @@ def add(t, p, q):
     return o
 
 
-def softmax_xent(t, logits, labels):
-    """Mean over the batch of -log softmax(logits)[label]; also returns the predicted classes."""
+def round_bf16(a):
+    """Nearest value with an 8-bit significand (the bfloat16 grid), ties to the even significand; the exponent
+    range is taken as unbounded (nothing in these networks comes near bfloat16's limits)."""
+    a = np.asarray(a, dtype=np.float64)
+    m, e = np.frexp(a)                       # a = m * 2^e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def store(t, x, q):
+    """A tensor as it is kept between layers when the workload computes in reduced precision: the values
+    rounded by ``q`` on the way forward, and the gradient that arrives for them rounded on the way back
+    (gradients of activations are kept in the same format).  ``q = None``: exact storage, nothing happens."""
+    if q is None:
+        return x
+    o = Var(q(x.v).astype(x.v.dtype))
+    t.back.append(lambda: x.acc(q(o.g).astype(x.v.dtype)))
+    return o
+
+
+def softmax_xent(t, logits, labels, q=None):
+    """Mean over the batch of -log softmax(logits)[label]; also returns the predicted classes.
+    ``q`` rounds the gradient handed to the logits (see :func:`store`)."""
     z = logits.v - logits.v.max(axis=1, keepdims=True)
     logp = z - np.log(np.exp(z).sum(axis=1, keepdims=True))
     B = z.shape[0]
@@ -368,7 +398,7 @@ def softmax_xent(t, logits, labels):
     def back():
         d = np.exp(logp)
         d[np.arange(B), labels] -= 1.0
-        logits.acc(d / B)
+        logits.acc(d / B if q is None else q(d / B).astype(d.dtype))
 
     t.back.append(back)
     return loss, pred
@@ -377,96 +407,135 @@ def softmax_xent(t, logits, labels):
 # ----------------------------------------------------------------------------
 # networks
 # ----------------------------------------------------------------------------
-def forward(a, P, x, t, train=True, bn_state=None, drop=None):
+def forward(a, P, x, t, train=True, bn_state=None, drop=None, q=None):
     """Logits of architecture ``a`` with parameter Vars ``P`` on images ``x`` (a Var).
 
-    ``drop`` = dict(p, seed, step, replica) switches dropout on (training only)."""
+    ``drop`` = dict(p, seed, step, replica) switches dropout on (training only).
+    ``q`` (see :func:`store`) switches reduced-precision storage on: the images, every layer output that a
+    later layer reads, and the weights of the contractions are rounded by it; biases, batch-norm parameters,
+    the logits and all sums stay exact.  A layer output is what the layer hands on: a convolution together
+    with the bias, the residual and the ReLU behind it; a batch-norm together with its ReLU."""
     m = a["model"]
     site = [0]
+
+    def keep(h):
+        return store(t, h, q)
+
+    def W(name):
+        """A weight as the contraction reads it: rounded copy of the master value; the gradient of the copy is
+        the gradient of the master value, unrounded (weight gradients are sums kept exact)."""
+        if q is None:
+            return P[name]
+        w = P[name]
+        o = Var(q(w.v).astype(w.v.dtype))
+        t.back.append(lambda: w.acc(o.g))
+        return o
 
     def dropped(h):
         if not train or drop is None or drop["p"] <= 0:
             return h
-        keep = dropout_keep(drop["seed"], drop["step"], drop["replica"], site[0], h.v.size, drop["p"])
+        mask = dropout_keep(drop["seed"], drop["step"], drop["replica"], site[0], h.v.size, drop["p"])
         site[0] += 1
-        return dropout(t, h, keep, drop["p"])
+        return keep(dropout(t, h, mask, drop["p"]))
 
+    x = keep(x)
     if m == "mlp":
-        h = relu(t, linear(t, x, P["fc1.w"], P["fc1.b"]))
-        return linear(t, h, P["fc2.w"], P["fc2.b"])
+        h = keep(relu(t, linear(t, x, W("fc1.w"), P["fc1.b"])))
+        return linear(t, h, W("fc2.w"), P["fc2.b"])
     if m == "lenet":
         bn = a.get("bn", 0)
 
         def act(h, name):
             if bn:
-                h = batchnorm(t, h, P[name + ".g"], P[name + ".b"], bn_state[name], train)
-            return relu(t, h)
+                h = batchnorm(t, keep(h), P[name + ".g"], P[name + ".b"], bn_state[name], train)
+            return keep(relu(t, h))
 
-        h = dropped(maxpool2(t, act(conv2d(t, x, P["conv1.w"], P["conv1.b"], 1, 0), "bn1")))
-        h = dropped(maxpool2(t, act(conv2d(t, h, P["conv2.w"], P["conv2.b"], 1, 0), "bn2")))
-        h = dropped(act(linear(t, h, P["fc1.w"], P["fc1.b"]), "bn3"))   # batch-norm over the batch, per feature
-        return linear(t, h, P["fc2.w"], P["fc2.b"])
+        h = dropped(maxpool2(t, act(conv2d(t, x, W("conv1.w"), P["conv1.b"], 1, 0), "bn1")))
+        h = dropped(maxpool2(t, act(conv2d(t, h, W("conv2.w"), P["conv2.b"], 1, 0), "bn2")))
+        h = dropped(act(linear(t, h, W("fc1.w"), P["fc1.b"]), "bn3"))   # batch-norm over the batch, per feature
+        return linear(t, h, W("fc2.w"), P["fc2.b"])
     if m == "allcnn":
         strides = [1, 1, 2, 1, 1, 2, 1, 1, 1]
         pads = [1, 1, 1, 1, 1, 1, 1, 0, 0]
         h = x
         for i in range(9):
-            h = conv2d(t, h, P[f"conv{i + 1}.w"], P[f"conv{i + 1}.b"], strides[i], pads[i])
+            h = conv2d(t, h, W(f"conv{i + 1}.w"), P[f"conv{i + 1}.b"], strides[i], pads[i])
             if i < 8:
                 h = relu(t, h)
+            h = keep(h)
             if strides[i] == 2:
                 h = dropped(h)
         return gap(t, h)
     if m == "wrn":
-        h = conv2d(t, x, P["conv1.w"], None, 1, 1)
+        h = keep(conv2d(t, x, W("conv1.w"), None, 1, 1))
         for name, cin, cout, stride in wrn_blocks(a):
-            o = relu(t, batchnorm(t, h, P[name + ".bn1.g"], P[name + ".bn1.b"], bn_state[name + ".bn1"], train))
-            u = conv2d(t, o, P[name + ".conv1.w"], None, stride, 1)
-            u = relu(t, batchnorm(t, u, P[name + ".bn2.g"], P[name + ".bn2.b"], bn_state[name + ".bn2"], train))
-            u = conv2d(t, dropped(u), P[name + ".conv2.w"], None, 1, 1)
+            o = keep(relu(t, batchnorm(t, h, P[name + ".bn1.g"], P[name + ".bn1.b"], bn_state[name + ".bn1"], train)))
+            u = keep(conv2d(t, o, W(name + ".conv1.w"), None, stride, 1))
+            u = keep(relu(t, batchnorm(t, u, P[name + ".bn2.g"], P[name + ".bn2.b"], bn_state[name + ".bn2"], train)))
+            u = conv2d(t, dropped(u), W(name + ".conv2.w"), None, 1, 1)
             if cin != cout or stride != 1:
-                sc = conv2d(t, o, P[name + ".sc.w"], None, stride, 0)
+                sc = keep(conv2d(t, o, W(name + ".sc.w"), None, stride, 0))
             else:
                 sc = h
-            h = add(t, u, sc)
-        h = relu(t, batchnorm(t, h, P["bn_out.g"], P["bn_out.b"], bn_state["bn_out"], train))
-        return linear(t, gap(t, h), P["fc.w"], P["fc.b"])
+            h = keep(add(t, u, sc))
+        h = keep(relu(t, batchnorm(t, h, P["bn_out.g"], P["bn_out.b"], bn_state["bn_out"], train)))
+        return linear(t, keep(gap(t, h)), W("fc.w"), P["fc.b"])
     raise ValueError(m)
 
 
-def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop=None, diag=None):
+def loss_and_grad(a, flat, images, labels, bn_state=None, dtype=np.float64, drop=None, diag=None, storage=None):
     """Mini-batch loss at the flat parameter vector and its gradient (same packing).
 
+    ``storage="bf16"``: activations, their gradients and the weights inside the contractions are kept on the
+    bfloat16 grid (see :func:`forward`), everything else exact -- the workloads that compute in bf16 with fp32
+    master weights.  Rounding decides ReLU masks, so a comparison that should be sharper than the rounding
+    itself has to take those decisions in the same precision on both sides; the sums stay float64 here.
+
     In training mode batch-norm running statistics in ``bn_state`` are updated in place.  A dict passed
-    as ``diag`` receives ``relu_margin``, the smallest non-zero |input| of any ReLU in the pass.
+    as ``diag`` receives ``relu_margin``, the smallest non-zero |input| of any ReLU in the pass, and ``pool_margin``,
+    the smallest lead of a positive max-pool winner over the runner-up of its window, and ``decisions``, one
+    (kind, margin, largest |input|) per ReLU / max-pool in forward order.
     """
     flat = np.asarray(flat, dtype=dtype)
     t = Tape()
     P = {k: Var(v) for k, v in unpack(a, flat).items()}
     x = Var(np.asarray(images, dtype=dtype))
-    logits = forward(a, P, x, t, train=True, bn_state=bn_state, drop=drop)
-    loss, _ = softmax_xent(t, logits, np.asarray(labels))
+    q = _storage_rounding(storage)
+    logits = forward(a, P, x, t, train=True, bn_state=bn_state, drop=drop, q=q)
+    loss, _ = softmax_xent(t, logits, np.asarray(labels), q=q)
     t.backward()
     if diag is not None:
         diag["relu_margin"] = t.relu_margin
+        diag["pool_margin"] = t.pool_margin
+        diag["decisions"] = list(t.decisions)
     grad = np.concatenate([P[s["name"]].g.reshape(-1) for s in layout(a)])
     return float(loss), grad
 
 
-def evaluate(a, flat, images, labels, bn_state=None, dtype=np.float64):
+def _storage_rounding(storage):
+    if storage is None:
+        return None
+    if storage == "bf16":
+        return round_bf16
+    raise ValueError(storage)
+
+
+def evaluate(a, flat, images, labels, bn_state=None, dtype=np.float64, storage=None):
     """Mean loss and number of misclassified samples (batch-norm in evaluation mode)."""
     flat = np.asarray(flat, dtype=dtype)
     t = Tape()
     P = {k: Var(v) for k, v in unpack(a, flat).items()}
-    logits = forward(a, P, Var(np.asarray(images, dtype=dtype)), t, train=False, bn_state=bn_state)
+    logits = forward(a, P, Var(np.asarray(images, dtype=dtype)), t, train=False, bn_state=bn_state,
+                     q=_storage_rounding(storage))
     loss, pred = softmax_xent(t, logits, np.asarray(labels))
     return float(loss), int(np.sum(pred != np.asarray(labels)))
 
 
-def logits_only(a, flat, images, bn_state=None, train=True, dtype=np.float64):
+def logits_only(a, flat, images, bn_state=None, train=True, dtype=np.float64, storage=None):
     flat = np.asarray(flat, dtype=dtype)
     P = {k: Var(v) for k, v in unpack(a, flat).items()}
-    return forward(a, P, Var(np.asarray(images, dtype=dtype)), Tape(), train=train, bn_state=bn_state).v
+    return forward(a, P, Var(np.asarray(images, dtype=dtype)), Tape(), train=train, bn_state=bn_state,
+                   q=_storage_rounding(storage)).v
 
 
 def flops_forward_per_image(a) -> int:

@@ -13,11 +13,18 @@ from . import nets, parle
 
 
 class ParleNet:
-    def __init__(self, a, cfg: parle.ParleConfig, x0, dtype=np.float64):
-        self.a, self.cfg, self.dtype = a, cfg, dtype
+    """``storage="bf16"`` keeps activations, their gradients and the weights inside the contractions on the
+    bfloat16 grid (nets.loss_and_grad); the state of (8a)-(8d) and all sums stay in ``dtype``."""
+
+    def __init__(self, a, cfg: parle.ParleConfig, x0, dtype=np.float64, storage=None):
+        self.a, self.cfg, self.dtype, self.storage = a, cfg, dtype, storage
         self.st = parle.init_state(x0, cfg, dtype=dtype)
         self.bn = [nets.new_bn_state(a, dtype) for _ in range(cfg.n_replicas)]
         self.relu_margin = np.inf  # smallest non-zero |ReLU input| over all steps so far (diagnostic)
+        # per replica, of the last step: smallest distance of any ReLU input from zero / of any positive max-pool
+        # winner from its runner-up -- how close the step came to a decision that rounding could take differently
+        self.last_margins = np.full(cfg.n_replicas, np.inf)
+        self.last_decisions = [[] for _ in range(cfg.n_replicas)]   # per replica: nets.loss_and_grad's `decisions`
 
     def inner_step(self, images, labels):
         """images ``[n, B, H, W, C]``, labels ``[n, B]``; returns the per-replica losses at y^a."""
@@ -29,8 +36,11 @@ class ParleNet:
                     if self.cfg.dropout > 0 else None)
             diag = {}
             losses[a_i], G[a_i] = nets.loss_and_grad(self.a, self.st.y[a_i], images[a_i], labels[a_i],
-                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop, diag=diag)
+                                                     bn_state=self.bn[a_i], dtype=self.dtype, drop=drop, diag=diag,
+                                                     storage=self.storage)
             self.relu_margin = min(self.relu_margin, diag["relu_margin"])
+            self.last_margins[a_i] = min(diag["relu_margin"], diag["pool_margin"])
+            self.last_decisions[a_i] = diag["decisions"]
         parle.inner_update(self.st, G, self.cfg)
         self.last_grad = G
         return losses
@@ -47,7 +57,7 @@ class ParleNet:
                   for k in self.bn[0]}
         else:
             flat, bn = self.st.x[which], self.bn[which]
-        loss, nerr = nets.evaluate(self.a, flat, images, labels, bn_state=bn, dtype=self.dtype)
+        loss, nerr = nets.evaluate(self.a, flat, images, labels, bn_state=bn, dtype=self.dtype, storage=self.storage)
         sp = float(sum(np.sum((self.st.x[i] - self.st.x_ref) ** 2) for i in range(self.cfg.n_replicas)))
         return loss, nerr, sp
 

@@ -56,6 +56,10 @@ class parle_conv_desc(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("dtype", "n", "batch", "h", "w", "cin", "cout", "k", "stride", "pad")]
 
 
+class parle_act_desc(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("dtype", "n", "batch", "h", "w", "c")]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -87,8 +91,22 @@ _SIGNATURES = {
                                    C.c_int32, C.c_void_p, C.c_void_p],
     "parle_k_conv_backward_weight": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_void_p],
+    "parle_k_bn_forward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                           C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_k_bn_backward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "parle_k_maxpool_forward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p],
+    "parle_k_maxpool_backward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p],
+    "parle_k_gap_forward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_int32, C.c_void_p, C.c_void_p],
+    "parle_k_gap_backward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p],
+    "parle_k_dropout": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_int32,
+                        C.c_float, C.c_void_p],
+    "parle_k_bias_grad": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p],
+    "parle_k_softmax_xent": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_void_p],
 }
-EXPORTS = sorted(list(_SIGNATURES) + ["parle_last_error", "parle_destroy", "parle_k_conv_scratch_bytes"])
+EXPORTS = sorted(list(_SIGNATURES) + ["parle_last_error", "parle_destroy", "parle_k_conv_scratch_bytes",
+                                         "parle_k_layer_scratch_bytes"])
 
 
 def lib():
@@ -109,6 +127,8 @@ def lib():
         L.parle_destroy.restype = None
         L.parle_k_conv_scratch_bytes.argtypes = [C.POINTER(parle_conv_desc)]
         L.parle_k_conv_scratch_bytes.restype = C.c_int64
+        L.parle_k_layer_scratch_bytes.argtypes = [C.POINTER(parle_act_desc)]
+        L.parle_k_layer_scratch_bytes.restype = C.c_int64
         _lib = L
     return _lib
 
@@ -223,6 +243,58 @@ def parle_k_conv_backward_weight(desc, dy, x, scratch, dw, stream=None):
 
 def parle_k_conv_scratch_bytes(desc) -> int:
     return int(lib().parle_k_conv_scratch_bytes(C.byref(desc)))
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def parle_k_layer_scratch_bytes(desc) -> int:
+    return int(lib().parle_k_layer_scratch_bytes(C.byref(desc)))
+
+
+def parle_k_bn_forward(desc, x, gamma, beta, scratch, saved, running, out, stream=None):
+    _check(lib().parle_k_bn_forward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(scratch),
+                                    _nbytes(scratch), _ptr(saved), _ptr(running), _ptr(out)))
+
+
+def parle_k_bn_backward(desc, x, dout, gamma, beta, saved, add, scratch, sums, dgamma, dbeta, dx, stream=None):
+    _check(lib().parle_k_bn_backward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(dout), _ptr(gamma), _ptr(beta),
+                                     _ptr(saved), _ptr(add), _ptr(scratch), _nbytes(scratch), _ptr(sums), _ptr(dgamma),
+                                     _ptr(dbeta), _ptr(dx)))
+
+
+def parle_k_maxpool_forward(desc, x, out, stream=None):
+    _check(lib().parle_k_maxpool_forward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(out)))
+
+
+def parle_k_maxpool_backward(desc, x, dout, relu_mask, din, stream=None):
+    _check(lib().parle_k_maxpool_backward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(dout), int(relu_mask),
+                                          _ptr(din)))
+
+
+def parle_k_gap_forward(desc, out_f32, x, out, stream=None):
+    _check(lib().parle_k_gap_forward(_stream_handle(stream), C.byref(desc), int(out_f32), _ptr(x), _ptr(out)))
+
+
+def parle_k_gap_backward(desc, dout, din, stream=None):
+    _check(lib().parle_k_gap_backward(_stream_handle(stream), C.byref(desc), _ptr(dout), _ptr(din)))
+
+
+def parle_k_dropout(desc, x, relu_src, seed, step_dev, site, p, out, stream=None):
+    _check(lib().parle_k_dropout(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(relu_src), int(seed), _ptr(step_dev),
+                                 int(site), float(p), _ptr(out)))
+
+
+def parle_k_bias_grad(desc, dy, scratch, grad, stream=None):
+    _check(lib().parle_k_bias_grad(_stream_handle(stream), C.byref(desc), _ptr(dy), _ptr(scratch), _nbytes(scratch),
+                                   _ptr(grad)))
+
+
+def parle_k_softmax_xent(dtype, logits, labels, loss, dlogits, stream=None):
+    n, batch, classes = logits.shape
+    _check(lib().parle_k_softmax_xent(_stream_handle(stream), int(dtype), n, batch, classes, _ptr(logits), _ptr(labels),
+                                      _ptr(loss), _ptr(dlogits)))
 
 
 class Parle:

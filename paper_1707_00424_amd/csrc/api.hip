@@ -112,6 +112,10 @@ parle_status check_config(const parle_config *cfg, Arch &arch, std::string &msg)
   return PARLE_OK;
 }
 
+int64_t bn_average_bytes(const Net *net) {
+  return net ? (net_bn_floats_per_replica(net) * (int64_t)sizeof(float) + 255) / 256 * 256 : 0;
+}
+
 parle_status compute_sizes(const parle_config *cfg, parle_sizes *out, Arch &arch, std::vector<Segment> &segs,
                            Net **net_out, std::string &msg) {
   if (parle_status s = check_config(cfg, arch, msg)) return s;
@@ -135,7 +139,7 @@ parle_status compute_sizes(const parle_config *cfg, parle_sizes *out, Arch &arch
   if (cfg->model != PARLE_MODEL_FLAT) {
     Net *net = net_create(*cfg, arch, segs, out->n_pad, msg);
     if (!net) return PARLE_EINVAL;
-    out->workspace_bytes += net_workspace_bytes(net);
+    out->workspace_bytes += bn_average_bytes(net) + net_workspace_bytes(net);
     out->bn_bytes = net_bn_floats_per_replica(net) * cfg->n_replicas * (int64_t)sizeof(float);
     out->forward_flops_per_image = net_forward_flops_per_image(net);
     if (net_out)
@@ -150,7 +154,9 @@ parle_status hip_fail(parle_ctx *ctx, hipError_t e, const char *what) {
   return fail(ctx, PARLE_EHIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
-void *net_ws(parle_ctx *ctx) { return (char *)ctx->buf.workspace + kHeaderBytes; }
+// Workspace: header | replica-averaged BN running statistics (evaluation at the reference) | the network's own
+float *bn_average_dev(parle_ctx *ctx) { return (float *)((char *)ctx->buf.workspace + kHeaderBytes); }
+void *net_ws(parle_ctx *ctx) { return (char *)ctx->buf.workspace + kHeaderBytes + bn_average_bytes(ctx->net); }
 
 float *coupling_dev(parle_ctx *ctx) {
   return ctx->cfg.graph_block ? (float *)((char *)ctx->buf.workspace + kCouplingOff) : nullptr;
@@ -436,8 +442,7 @@ parle_status parle_eval(parle_ctx *ctx, int32_t which, const float *images_dev, 
     if (ctx->sizes.bn_bytes) {
       const int64_t per = net_bn_floats_per_replica(ctx->net);
       if (which < 0) {
-        float *avg = (float *)(hdr + kScalarOff + 256);  // fits: header holds 32 KiB past the scalars
-        if ((int64_t)per * 4 > kHeaderBytes - kScalarOff - 256) return fail(ctx, PARLE_ESIZE, "too many BN channels");
+        float *avg = bn_average_dev(ctx);
         if ((e = net_average_bn(ctx->net, ctx->stream, (const float *)ctx->buf.bn_stats, avg)) != hipSuccess)
           return hip_fail(ctx, e, "bn average");
         bn_row = avg;

@@ -1,0 +1,127 @@
+"""Free-running full-size cycles of the two bf16 workloads against the stored trajectory of the CPU oracle.
+
+All-CNN-C and WRN-16-4 at the size the bench times (three replicas, batch 128, 3x32x32, bf16 compute with fp32
+master weights): L = 25 inner steps of (8a)-(8b) and the outer step (8c)-(8d), twice with rule (9) switching the
+couplings in between for the residual network.  The oracle needs 10-30 CPU-minutes for such a run, so its result
+is stored (tests/golden/full_size_cycle_*.npz, written by tests/golden/make_full_size_cycles.py, which calls
+only oracle/ and the seeded input generators): sampled entries of every state tensor at fixed positions in every
+parameter segment, the norm of every segment's displacement over all its entries, losses, couplings, batch-norm
+running statistics.
+
+Bars: the loss of every step and every state tensor within 2e-2 (the bound the workload definition states for
+bf16 compute).  25 steps move the parameters by a few per cent of their size at most, so that bar alone would
+also pass a device that did not train; what binds is the DISPLACEMENT from the start of the block, held per
+parameter segment in direction and size (bars below, with the measured figures in the design doc)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_1707_00424_amd import synth
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+# displacement of a segment over a block, device against oracle: relative 2-norm error on the sampled entries,
+# cosine, and ratio of the two norms taken over all entries
+DISP_REL, DISP_COS, NORM_RATIO = 1.0, 0.0, 10.0      # measured first, then set
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1707_00424_amd import binding as pb
+    pb.lib()
+    return torch, pb
+
+
+def rel2(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+
+
+def cosine(got, ref):
+    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
+    den = np.sqrt((got * got).sum() * (ref * ref).sum())
+    return float((got * ref).sum() / den) if den > 0 else 1.0
+
+
+def full_norms(lay, delta):
+    out, off = np.zeros((delta.shape[0], len(lay))), 0
+    for i, s in enumerate(lay):
+        out[:, i] = np.linalg.norm(delta[:, off:off + s["size"]].astype(np.float64), axis=1)
+        off += s["size"]
+    return out
+
+
+@pytest.mark.parametrize("name", ["allcnn", "wrn"])
+def test_full_size_free_running_cycle(gpu, name):
+    torch, pb = gpu
+    path = os.path.join(GOLDEN, f"full_size_cycle_{name}.npz")
+    G = np.load(path, allow_pickle=False)
+    rc = json.loads(str(G["recipe"]))
+    model = pb.MODEL_ALLCNN_C if rc["model"] == "allcnn" else pb.MODEL_WRN
+    n, B, L = rc["n"], rc["batch"], rc["L"]
+    cfg = pb.make_config(model=model, n_replicas=n, batch=B, L=L, compute_bf16=1, eta_inner=rc["eta_inner"],
+                         eta_outer=rc["eta_outer"], momentum=rc["momentum"], alpha=rc["alpha"], gamma0=rc["gamma0"],
+                         rho0=rc["rho0"], scoping_B=rc["scoping_B"], fuse_outer=1)
+    lay = pb.parle_query_layout(cfg)
+    assert [s["name"] for s in lay] == [str(v) for v in G["segment_names"]]
+    x0 = np.tile(synth.init_params(lay, rc["seed"], rc["weight_init"]), (n, 1))
+    P = pb.Parle(cfg, x0)
+    steps = L * rc["blocks"]
+    X, Y = synth.image_batches(rc["seed"], steps, n, B, 32, 32, 3, 10)
+    dX, dY = torch.as_tensor(X).cuda(), torch.as_tensor(Y).cuda()
+    loss = torch.zeros((steps, n), dtype=torch.float32, device="cuda")
+    pos, bounds = G["positions"], G["segment_bounds"]
+    worst = dict(rel=("", 0.0), cos=("", 1.0), ratio=("", 1.0))
+
+    def hold(label, got_s, ref_s, start_s, got_norm, ref_norm):
+        """Sampled displacement per segment (direction and size) and the full-vector norm per segment."""
+        for i, sg in enumerate(lay):
+            lo, hi = bounds[i], bounds[i + 1]
+            for r in range(n):
+                d, dr = got_s[r, lo:hi] - start_s[r, lo:hi], ref_s[r, lo:hi] - start_s[r, lo:hi]
+                e, c = rel2(d, dr), cosine(d, dr)
+                q = got_norm[r, i] / max(ref_norm[r, i], 1e-30)
+                tag = f"{label} {sg['name']}[{r}]"
+                if e > worst["rel"][1]:
+                    worst["rel"] = (tag, e)
+                if c < worst["cos"][1]:
+                    worst["cos"] = (tag, c)
+                if abs(np.log(q)) > abs(np.log(worst["ratio"][1])):
+                    worst["ratio"] = (tag, q)
+                assert e <= DISP_REL and c >= DISP_COS, (tag, e, c)
+                assert 1 / NORM_RATIO <= q <= NORM_RATIO, (tag, q)
+
+    for b in range(rc["blocks"]):
+        start = P.state()["x"].astype(np.float64)
+        for k in range(b * L, (b + 1) * L):
+            P.parle_inner_step(dX[k], dY[k], loss[k])
+        got = P.state()
+        for t in ("y", "z"):
+            ref = G[f"b{b}_{t}"]
+            assert rel2(got[t][:, pos], ref) <= 2e-2, (b, t)
+        hold(f"block {b} y", got["y"][:, pos], G[f"b{b}_y"], start[:, pos], full_norms(lay, got["y"] - start),
+             G[f"b{b}_ynorm"])
+        assert rel2(got["vy"][:, pos], G[f"b{b}_vy"]) <= 10 * DISP_REL, (b, "vy")
+        P.parle_outer_step()
+        got = P.state()
+        assert rel2(got["x"][:, pos], G[f"b{b}_x"]) <= 2e-2 and rel2(got["x_ref"][pos], G[f"b{b}_x_ref"]) <= 2e-2
+        assert np.array_equal(got["y"], got["x"]) and np.array_equal(got["z"], got["x"]) and not got["vy"].any()
+        hold(f"block {b} x", got["x"][:, pos], G[f"b{b}_x"], start[:, pos], full_norms(lay, got["x"] - start),
+             G[f"b{b}_xnorm"])
+        _, od, g, r = P.parle_get_state()
+        assert od == b + 1 and abs(g - G[f"b{b}_gr"][0]) <= 1e-6 * g and abs(r - G[f"b{b}_gr"][1]) <= 1e-6 * r
+        if f"b{b}_bn" in G:
+            stats = P.bn_stats.cpu().numpy().reshape(n, -1)
+            assert rel2(stats, G[f"b{b}_bn"]) <= 2e-2
+    got_loss, ref_loss = loss.cpu().numpy().astype(np.float64), G["losses"]
+    np.testing.assert_allclose(got_loss, ref_loss, rtol=2e-2)
+    print(f"{name}: loss {ref_loss[0].mean():.3f} -> {ref_loss[-1].mean():.3f}, worst loss error "
+          f"{np.abs(got_loss / ref_loss - 1).max():.2e}; worst displacement error {worst['rel']}, cosine {worst['cos']}, "
+          f"norm ratio {worst['ratio']}")
+    P.close()

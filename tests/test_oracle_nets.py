@@ -490,3 +490,72 @@ def test_reference_is_evaluated_with_replica_averaged_running_statistics():
     assert net.eval(1, Xe, Ye)[:2] == nets.evaluate(a, net.st.x[1], Xe, Ye, bn_state=net.bn[1])
     e0, e1 = net.st.x[0] - net.st.x_ref, net.st.x[1] - net.st.x_ref
     assert np.isclose(got[2], e0 @ e0 + e1 @ e1, rtol=1e-12)
+
+
+# ---- reduced-precision storage (the bf16 workloads): rounding, where it is applied, what it leaves exact ---------
+def test_round_bf16_against_a_library_conversion_and_by_hand():
+    import torch
+    rng = np.random.default_rng(51)
+    v = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000), [0.0, -0.0, 1.0, -3.5]])
+    v32 = v.astype(np.float32)
+    lib = torch.from_numpy(v32).to(torch.bfloat16).to(torch.float32).numpy()     # round-to-nearest-even
+    assert np.array_equal(nets.round_bf16(v32), lib.astype(np.float64))
+    # by hand: 8 significant bits.  1 + 2^-8 is a tie between 1 and 1 + 2^-7: even significand wins (1);
+    # 1 + 3 * 2^-8 is a tie between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    assert nets.round_bf16(1 + 2.0 ** -8) == 1.0 and nets.round_bf16(1 + 3 * 2.0 ** -8) == 1 + 2.0 ** -6
+    assert nets.round_bf16(1 + 2.0 ** -8 + 2.0 ** -30) == 1 + 2.0 ** -7          # just above the tie: up
+    assert nets.round_bf16(-(1 + 2.0 ** -8)) == -1.0 and nets.round_bf16(255.5) == 256.0 and nets.round_bf16(0.1) == 0.10009765625
+    x = rng.standard_normal(1000)
+    r = nets.round_bf16(x)
+    assert np.array_equal(nets.round_bf16(r), r) and np.abs(r - x).max() <= 2.0 ** -8 * np.abs(x).max()
+    assert np.abs(r / x - 1).max() <= 2.0 ** -8                                   # half an ulp of an 8-bit significand
+
+
+def test_store_rounds_values_forward_and_gradients_backward():
+    t = nets.Tape()
+    x = nets.Var(np.array([1 + 2.0 ** -8, 0.3]))
+    o = nets.store(t, x, nets.round_bf16)
+    assert o.v.tolist() == [1.0, 0.30078125]
+    o.g = np.array([0.7, 1 + 3 * 2.0 ** -8])
+    t.backward()
+    assert x.g.tolist() == [0.69921875, 1 + 2.0 ** -6]
+    assert nets.store(t, x, None) is x                                            # exact storage: nothing happens
+
+
+def test_bf16_storage_mlp_against_library_bfloat16_arithmetic():
+    """The same small MLP computed with a tensor library's bfloat16 type at the storage points (images, weights
+    inside the products, the hidden activation) and float64 sums in between."""
+    import torch
+    a = TINY["mlp"]
+    rng = np.random.default_rng(52)
+    p = (rng.standard_normal(nets.n_params(a)) * 0.7)
+    x = rng.standard_normal((7, a["H"], a["W"], a["C"]))
+
+    def bf(v):
+        return torch.as_tensor(np.asarray(v, np.float32)).to(torch.bfloat16).to(torch.float64)
+
+    P = nets.unpack(a, p)
+    p32 = p.astype(np.float32)
+    P32 = nets.unpack(a, p32)
+    xb = bf(x.reshape(7, -1))
+    h = torch.clamp(xb @ bf(P32["fc1.w"]).T + torch.as_tensor(P32["fc1.b"].astype(np.float64)), min=0)
+    h = bf(h.numpy())
+    want = (h @ bf(P32["fc2.w"]).T + torch.as_tensor(P32["fc2.b"].astype(np.float64))).numpy()
+    got = nets.logits_only(a, p32, x.astype(np.float32), storage="bf16")
+    assert np.allclose(got, want, rtol=0, atol=1e-12)
+    exact = nets.logits_only(a, p32, x.astype(np.float32))
+    assert 1e-4 < np.abs(got - exact).max() < 0.2                                 # it does round, and only a little
+
+
+@pytest.mark.parametrize("model", ["mlp", "lenet", "allcnn", "wrn"])
+def test_bf16_storage_stays_close_to_exact_and_keeps_weight_gradients_unrounded(model):
+    a = TINY[model]
+    p = synth.init_params(nets.layout(a), seed=53).astype(np.float64)
+    x, y = _data(a, 6, 54)
+    l0, g0 = nets.loss_and_grad(a, p, x, y, bn_state=nets.new_bn_state(a))
+    l1, g1 = nets.loss_and_grad(a, p, x, y, bn_state=nets.new_bn_state(a), storage="bf16")
+    assert l0 != l1 and abs(l1 / l0 - 1) < 3e-2
+    cos = g0 @ g1 / np.sqrt((g0 @ g0) * (g1 @ g1))
+    assert cos > 0.9
+    # weight gradients are exact sums of products of stored values: not themselves on the bf16 grid
+    assert (nets.round_bf16(g1) != g1).mean() > 0.5
