@@ -375,14 +375,29 @@ def round_bf16(a):
     return np.ldexp(np.rint(m * 256.0) / 256.0, e)
 
 
+class StoredVar(Var):
+    """A tensor kept in a reduced-precision format, and with it its gradient: every contribution that arrives
+    is added to what is stored so far and the sum is rounded again (a backward pass that keeps gradients in the
+    format adds to them in place, in the reverse of the order in which the tensor was read going forward)."""
+    __slots__ = ("q",)
+
+    def __init__(self, v, q):
+        super().__init__(v)
+        self.q = q
+
+    def acc(self, g):
+        tot = g if self.g is None else self.g + g
+        self.g = self.q(tot).astype(self.v.dtype)
+
+
 def store(t, x, q):
     """A tensor as it is kept between layers when the workload computes in reduced precision: the values
     rounded by ``q`` on the way forward, and the gradient that arrives for them rounded on the way back
     (gradients of activations are kept in the same format).  ``q = None``: exact storage, nothing happens."""
     if q is None:
         return x
-    o = Var(q(x.v).astype(x.v.dtype))
-    t.back.append(lambda: x.acc(q(o.g).astype(x.v.dtype)))
+    o = StoredVar(q(x.v).astype(x.v.dtype), q)
+    t.back.append(lambda: x.acc(o.g))
     return o
 
 

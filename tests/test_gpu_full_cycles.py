@@ -25,7 +25,9 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 # displacement of a segment over a block, device against oracle: relative 2-norm error on the sampled entries,
 # cosine, and ratio of the two norms taken over all entries
-DISP_REL, DISP_COS, NORM_RATIO = 1.0, 0.0, 10.0      # measured first, then set
+# measured worst cases: All-CNN-C 6.7e-2 / 0.9978 / 1.006 (conv1.w), WRN-16-4 0.21 / 0.979 / 1.05 (batch-norm shifts of
+# the first group, the segments that the one-step test also finds furthest apart); losses within 1.1e-3 at every step
+DISP_REL, DISP_COS, NORM_RATIO = 0.3, 0.96, 1.12
 
 
 @pytest.fixture(scope="module")

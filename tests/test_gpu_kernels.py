@@ -162,29 +162,38 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
 
 
 @pytest.mark.parametrize("layer", [
-    # full-size layers of the bf16 workloads, batch 128, n = 3 (the launch shapes the bench times)
-    (3, 128, 32, 32, 96, 96, 3, 1, 1),      # All-CNN-C conv2
-    (3, 128, 16, 16, 192, 192, 3, 2, 1),    # All-CNN-C conv6 (stride 2)
-    (3, 128, 32, 32, 16, 64, 3, 1, 1),      # WRN-16-4 group 1
-    (3, 128, 16, 16, 128, 128, 3, 1, 1),    # WRN-16-4 group 2: 64-wide column blocks, two per pixel tile
-    (3, 128, 8, 8, 256, 256, 3, 1, 1),      # WRN-16-4 group 3
+    # full-size layers of the workloads at the launch shapes the bench times (batch 128): dtype, n, B, H, W, Cin, Cout, k, stride, pad
+    (1, 3, 128, 32, 32, 96, 96, 3, 1, 1),      # All-CNN-C conv2
+    (1, 3, 128, 16, 16, 192, 192, 3, 2, 1),    # All-CNN-C conv6 (stride 2)
+    (1, 3, 128, 32, 32, 16, 64, 3, 1, 1),      # WRN-16-4 group 1
+    (1, 3, 128, 16, 16, 128, 128, 3, 1, 1),    # WRN-16-4 group 2: 64-wide column blocks, two per pixel tile
+    (1, 3, 128, 8, 8, 256, 256, 3, 1, 1),      # WRN-16-4 group 3
+    (1, 3, 128, 32, 32, 3, 96, 3, 1, 1),       # All-CNN-C conv1: the first layer (whole contraction in one tile)
+    (1, 3, 128, 32, 32, 3, 16, 3, 1, 1),       # WRN conv1
+    (1, 3, 128, 8, 8, 192, 192, 1, 1, 0),      # All-CNN-C conv8: 1x1
+    (1, 3, 128, 8, 8, 192, 10, 1, 1, 0),       # All-CNN-C conv9: 1x1, ten outputs
+    (1, 3, 128, 32, 32, 64, 128, 1, 2, 0),     # WRN-16-4 g2b1 shortcut: 1x1, stride 2
+    (1, 3, 128, 32, 32, 160, 320, 3, 2, 1),    # WRN-28-10 g2b1.conv1: 160 -> 320, stride 2
+    (1, 3, 128, 16, 16, 320, 320, 3, 1, 1),    # WRN-28-10 group 2
+    (0, 6, 128, 28, 28, 1, 20, 5, 1, 0),       # LeNet conv1, fp32, six replicas
+    (0, 6, 128, 12, 12, 20, 50, 5, 1, 0),      # LeNet conv2, fp32 (backward-data in two passes)
 ])
 def test_full_size_layers_sampled(gpu, layer):
-    """Forward and backward-data are checked on sampled images (rows are independent); the weight
-    gradient on sampled (output channel, input channel) pairs, each summed over all 128 images."""
+    """Forward and backward-data are checked on sampled images (rows are independent); the weight gradient on
+    sampled output and input channels, summed over all 128 images by the oracle's own convolution backward
+    (the gradient entry (co, i, j, ci) depends only on channel co of dy and channel ci of x)."""
     torch, pb = gpu
-    n, B, H, W, Cin, Cout, k, stride, pad = layer
-    dtype = 1
+    dtype, n, B, H, W, Cin, Cout, k, stride, pad = layer
     Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
     gen = torch.Generator(device="cuda").manual_seed(7)
-    bf = torch.bfloat16
-    x = torch.randn((n, B, H, W, Cin), generator=gen, device="cuda").to(bf)
-    w = (torch.randn((n, Cout, k, k, Cin), generator=gen, device="cuda") / np.sqrt(k * k * Cin)).to(bf)
-    dy = torch.randn((n, B, Ho, Wo, Cout), generator=gen, device="cuda").to(bf)
+    tdt = torch.bfloat16 if dtype else torch.float32
+    x = torch.randn((n, B, H, W, Cin), generator=gen, device="cuda").to(tdt)
+    w = (torch.randn((n, Cout, k, k, Cin), generator=gen, device="cuda") / np.sqrt(k * k * Cin)).to(tdt)
+    dy = torch.randn((n, B, Ho, Wo, Cout), generator=gen, device="cuda").to(tdt)
     desc = pb.parle_conv_desc(dtype, n, B, H, W, Cin, Cout, k, stride, pad)
-    y = torch.zeros((n, B, Ho, Wo, Cout), dtype=bf, device="cuda")
-    dx = torch.zeros((n, B, H, W, Cin), dtype=bf, device="cuda")
-    wt = torch.zeros(n * Cout * k * k * Cin, dtype=bf, device="cuda")
+    y = torch.zeros((n, B, Ho, Wo, Cout), dtype=tdt, device="cuda")
+    dx = torch.zeros((n, B, H, W, Cin), dtype=tdt, device="cuda")
+    wt = torch.zeros(n * Cout * k * k * Cin, dtype=tdt, device="cuda")
     gw = torch.zeros((n, Cout, k, k, Cin), dtype=torch.float32, device="cuda")
     scratch = torch.zeros(max(pb.parle_k_conv_scratch_bytes(desc) // 4, 4), dtype=torch.float32, device="cuda")
     pb.parle_k_conv_forward(desc, x, w, None, None, 0, y)
@@ -196,17 +205,14 @@ def test_full_size_layers_sampled(gpu, layer):
         wr = download(w[r])
         for b in (0, int(rng.integers(1, B - 1)), B - 1):
             ry, rdx, _ = oracle_conv(download(x[r, b:b + 1]), wr, None, None, False, stride, pad, download(dy[r, b:b + 1]))
-            assert_near("fwd", download(y[r, b:b + 1]), ry, *tolerances(1, ry))
-            assert_near("dgrad", download(dx[r, b:b + 1]), rdx, *tolerances(1, rdx))
-        xr, dyr = download(x[r]), download(dy[r])
-        xp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin))
-        xp[:, pad:pad + H, pad:pad + W] = xr
+            assert_near("fwd", download(y[r, b:b + 1]), ry, *tolerances(dtype, ry))
+            assert_near("dgrad", download(dx[r, b:b + 1]), rdx, *tolerances(dtype, rdx))
         got = download(gw[r])
         scale = np.abs(got).max()
-        for _ in range(24):
-            co, ci = int(rng.integers(Cout)), int(rng.integers(Cin))
-            for i in range(k):
-                for j in range(k):
-                    win = xp[:, i:i + stride * (Ho - 1) + 1:stride, j:j + stride * (Wo - 1) + 1:stride, ci]
-                    ref = float(np.sum(win * dyr[..., co]))
-                    assert abs(got[co, i, j, ci] - ref) <= 2e-5 * scale + 1e-5 * abs(ref), (co, i, j, ci)
+        cos = np.sort(rng.choice(Cout, size=min(Cout, 6), replace=False))
+        cis = np.sort(rng.choice(Cin, size=min(Cin, 6), replace=False))
+        xs, dys = download(x[r][..., cis]), download(dy[r][..., cos])
+        _, _, rdw = oracle_conv(xs, np.zeros((len(cos), k, k, len(cis))), None, None, False, stride, pad, dys)
+        sub = got[cos][:, :, :, cis]
+        assert np.abs(rdw).max() > 0.2 * scale                       # the sample is not a corner of small entries
+        assert_near("wgrad", sub, rdw, 1e-5, 2e-5 * scale)

@@ -30,3 +30,63 @@ def test_float32_oracle_leaves_float64_oracle_at_step_size_0p1():
 
 def test_float32_oracle_stays_with_float64_oracle_at_step_size_0p01():
     assert _gap(0.01, 25) < 1e-6
+
+
+def test_one_ulp_in_one_bf16_activation_moves_the_gradient_by_per_cents():
+    """With activations kept on the bf16 grid a single stored value that is one ulp off (which is what a different
+    summation order does to about 3e-5 of them) shifts the roundings of everything computed from it, and the
+    gradient of a small residual network moves by 1-10 %.  This is the oracle against itself; it is why bf16
+    gradients of two correct implementations are compared sharply only where no such event occurred, and by
+    direction otherwise (tests/test_gpu_nets.py)."""
+    a = nets.arch("wrn", H=8, W=12, C=3, base=3, widen=2, nb=2, classes=5)
+    p = synth.init_params(nets.layout(a), 0, "he_normal").astype(np.float64)
+    X, Y = synth.image_batches(0, 1, 1, 9, a["H"], a["W"], a["C"], a["classes"])
+    _, g0 = nets.loss_and_grad(a, p, X[0, 0], Y[0, 0], bn_state=nets.new_bn_state(a), storage="bf16")
+    plain = nets.round_bf16
+    moved = []
+    for target in (3, 10, 20):                       # which stored tensor of the forward pass gets the nudge
+        calls = [0]
+
+        def nudged(v, target=target):
+            calls[0] += 1
+            r = plain(v)
+            if calls[0] == target:
+                idx = tuple(s // 2 for s in r.shape)
+                r = r.copy()
+                r[idx] = r[idx] * (1 + 2.0 ** -7) if r[idx] != 0 else 2.0 ** -10
+            return r
+
+        t = nets.Tape()
+        P = {k: nets.Var(v) for k, v in nets.unpack(a, p).items()}
+        logits = nets.forward(a, P, nets.Var(X[0, 0].astype(np.float64)), t, bn_state=nets.new_bn_state(a), q=nudged)
+        nets.softmax_xent(t, logits, Y[0, 0], q=nudged)
+        t.backward()
+        g1 = np.concatenate([P[s["name"]].g.reshape(-1) for s in nets.layout(a)])
+        moved.append(np.linalg.norm(g1 - g0) / np.linalg.norm(g0))
+    assert min(moved) > 5e-3 and max(moved) > 5e-2, moved
+    # the same nudge with exact storage (the hook rounds nothing, it only nudges that one value)
+    exact = []
+    for target in (3, 10, 20):
+        calls = [0]
+
+        def only_nudged(v, target=target):
+            calls[0] += 1
+            r = np.asarray(v, np.float64)
+            if calls[0] == target:
+                idx = tuple(s // 2 for s in r.shape)
+                r = r.copy()
+                r[idx] = r[idx] * (1 + 2.0 ** -7) if r[idx] != 0 else 2.0 ** -10
+            return r
+
+        grads = []
+        for hook in (lambda v: np.asarray(v, np.float64), only_nudged):
+            calls[0] = 0
+            t = nets.Tape()
+            P = {k: nets.Var(v) for k, v in nets.unpack(a, p).items()}
+            logits = nets.forward(a, P, nets.Var(X[0, 0].astype(np.float64)), t, bn_state=nets.new_bn_state(a), q=hook)
+            nets.softmax_xent(t, logits, Y[0, 0], q=hook)
+            t.backward()
+            grads.append(np.concatenate([P[s["name"]].g.reshape(-1) for s in nets.layout(a)]))
+        exact.append(np.linalg.norm(grads[1] - grads[0]) / np.linalg.norm(grads[0]))
+    print("gradient moved by (bf16 storage)", moved, "(exact storage)", exact)
+    assert max(exact) < 0.2 * min(moved), (exact, moved)

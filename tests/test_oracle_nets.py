@@ -516,10 +516,19 @@ def test_store_rounds_values_forward_and_gradients_backward():
     x = nets.Var(np.array([1 + 2.0 ** -8, 0.3]))
     o = nets.store(t, x, nets.round_bf16)
     assert o.v.tolist() == [1.0, 0.30078125]
-    o.g = np.array([0.7, 1 + 3 * 2.0 ** -8])
+    o.acc(np.array([0.7, 1 + 3 * 2.0 ** -8]))         # what a reader of the stored tensor hands back
     t.backward()
     assert x.g.tolist() == [0.69921875, 1 + 2.0 ** -6]
     assert nets.store(t, x, None) is x                                            # exact storage: nothing happens
+    # two readers: the second contribution is added to the stored (rounded) first one and the sum rounded again:
+    # 1 + 2^-8 is kept as 1, then 1 + 2^-8 gives 1 + 2^-8 -> 1 again; adding them exactly first would give 1 + 2^-7
+    t = nets.Tape()
+    x = nets.Var(np.array([0.0]))
+    o = nets.store(t, x, nets.round_bf16)
+    o.acc(np.array([1 + 2.0 ** -8]))
+    o.acc(np.array([2.0 ** -8]))
+    t.backward()
+    assert x.g.tolist() == [1.0] and nets.round_bf16(1 + 2.0 ** -8 + 2.0 ** -8) == 1 + 2.0 ** -7
 
 
 def test_bf16_storage_mlp_against_library_bfloat16_arithmetic():
