@@ -131,15 +131,41 @@ __global__ __launch_bounds__(kThreads) void k_stream(const f4 *__restrict__ src,
 // ---------------------------------------------------------------------------------------------
 // (8d) with eta'' = rho/n: column mean of the stacked replicas, summed in replica order.
 // ---------------------------------------------------------------------------------------------
-template <bool NT>
+// N > 0: compile-time replica count, all N x U loads of a thread issued before the first add; a block owns U
+// adjacent 4 KiB chunks of every row.  N = 0: any n, one load at a time.
+template <int N, int U, bool NT>
 __global__ __launch_bounds__(kThreads) void k_replica_mean(const f4 *__restrict__ X, f4 *__restrict__ XR, int n,
                                                            int64_t np4) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
-  const float fn = (float)n;
-  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
-    f4 s = ld4<NT>(X + q);
-    for (int a = 1; a < n; ++a) s += ld4<NT>(X + (int64_t)a * np4 + q);
-    XR[q] = s / fn;  // kept cacheable: the outer update reads it right away
+  const float fn = (float)(N > 0 ? N : n);
+  if (N == 0) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
+      f4 s = ld4<NT>(X + q);
+      for (int a = 1; a < n; ++a) s += ld4<NT>(X + (int64_t)a * np4 + q);
+      XR[q] = s / fn;  // kept cacheable: the outer update reads it right away
+    }
+    return;
+  }
+  const int64_t trip = (int64_t)gridDim.x * kThreads * U;
+  for (int64_t q0 = (int64_t)blockIdx.x * kThreads * U + threadIdx.x; q0 < np4; q0 += trip) {
+    f4 xs[N > 0 ? N : 1][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * kThreads;
+#pragma unroll
+      for (int a = 0; a < N; ++a)
+        if (q < np4) xs[a][u] = ld4<NT>(X + (int64_t)a * np4 + q);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * kThreads;
+      if (q < np4) {
+        f4 s = xs[0][u];
+#pragma unroll
+        for (int a = 1; a < N; ++a) s += xs[a][u];   // replica order, as the one-at-a-time form
+        XR[q] = s / fn;
+      }
+    }
   }
 }
 
@@ -174,47 +200,57 @@ __global__ __launch_bounds__(kThreads) void k_outer_update(f4 *__restrict__ X, f
 
 // Same update with the replica mean formed in registers: every x^a[i] is read once, the mean is
 // written to x_ref, and no second pass over x is needed.  N > 0: compile-time replica count.
-template <int N, bool NT, bool BF>
+template <int N, int U, bool NT, bool BF>
 __global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4 *__restrict__ Z, f4 *__restrict__ VX,
                                                           f4 *__restrict__ Y, f4 *__restrict__ VY,
                                                           f4 *__restrict__ XR, us4 *__restrict__ Y16, int n_rt,
                                                           int64_t np4, float eta, float mu, float cz, float r,
                                                           int reset_flags, int lagged) {
-  const int64_t stride = (int64_t)gridDim.x * kThreads;
   const f4 zero = {0.f, 0.f, 0.f, 0.f};
   const int n = N > 0 ? N : n_rt;
   const float fn = (float)n;
-  for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < np4; q += stride) {
-    f4 xs[N > 0 ? N : 1];
-    f4 s;
-    if (N > 0) {
+  // a block owns U adjacent 4 KiB chunks of every row; all loads of a chunk are issued before its arithmetic
+  const int64_t trip = (int64_t)gridDim.x * kThreads * U;
+  for (int64_t q0 = (int64_t)blockIdx.x * kThreads * U + threadIdx.x; q0 < np4; q0 += trip) {
 #pragma unroll
-      for (int a = 0; a < N; ++a) xs[a] = ld4<NT>(X + (int64_t)a * np4 + q);
-      s = xs[0];
+    for (int u = 0; u < U; ++u) {
+      const int64_t q = q0 + u * kThreads;
+      if (q >= np4) break;
+      f4 xs[N > 0 ? N : 1], zs[N > 0 ? N : 1], vs[N > 0 ? N : 1];
+      f4 s;
+      if (N > 0) {
 #pragma unroll
-      for (int a = 1; a < N; ++a) s += xs[a];
-    } else {
-      s = X[q];
-      for (int a = 1; a < n; ++a) s += X[(int64_t)a * np4 + q];
-    }
-    const f4 mean = s / fn;
-    const f4 xr = lagged ? XR[q] : mean;
-    st4<NT>(XR + q, mean);
+        for (int a = 0; a < N; ++a) xs[a] = ld4<NT>(X + (int64_t)a * np4 + q);
 #pragma unroll
-    for (int a = 0; a < n; ++a) {
-      const int64_t o = (int64_t)a * np4 + q;
-      const f4 x = N > 0 ? xs[N > 0 ? a : 0] : X[o];
-      const f4 z = ld4<NT>(Z + o);
-      const f4 v = ld4<NT>(VX + o);
-      const f4 d = cz * (x - z) + r * (x - xr);
-      const f4 vn = mu * v + d;
-      const f4 xn = x - eta * (d + mu * vn);
-      st4<NT>(VX + o, vn);
-      st4<NT>(X + o, xn);
-      st4<NT>(Y + o, xn);
-      if (reset_flags & 1) st4<NT>(Z + o, xn);
-      if (reset_flags & 2) st4<NT>(VY + o, zero);
-      if (BF) __builtin_nontemporal_store(to_bf16x4(xn), Y16 + o);
+        for (int a = 0; a < N; ++a) zs[a] = ld4<NT>(Z + (int64_t)a * np4 + q);
+#pragma unroll
+        for (int a = 0; a < N; ++a) vs[a] = ld4<NT>(VX + (int64_t)a * np4 + q);
+        s = xs[0];
+#pragma unroll
+        for (int a = 1; a < N; ++a) s += xs[a];
+      } else {
+        s = X[q];
+        for (int a = 1; a < n; ++a) s += X[(int64_t)a * np4 + q];
+      }
+      const f4 mean = s / fn;
+      const f4 xr = lagged ? XR[q] : mean;
+      st4<NT>(XR + q, mean);
+#pragma unroll
+      for (int a = 0; a < n; ++a) {
+        const int64_t o = (int64_t)a * np4 + q;
+        const f4 x = N > 0 ? xs[N > 0 ? a : 0] : X[o];
+        const f4 z = N > 0 ? zs[N > 0 ? a : 0] : ld4<NT>(Z + o);
+        const f4 v = N > 0 ? vs[N > 0 ? a : 0] : ld4<NT>(VX + o);
+        const f4 d = cz * (x - z) + r * (x - xr);
+        const f4 vn = mu * v + d;
+        const f4 xn = x - eta * (d + mu * vn);
+        st4<NT>(VX + o, vn);
+        st4<NT>(X + o, xn);
+        st4<NT>(Y + o, xn);
+        if (reset_flags & 1) st4<NT>(Z + o, xn);
+        if (reset_flags & 2) st4<NT>(VY + o, zero);
+        if (BF) __builtin_nontemporal_store(to_bf16x4(xn), Y16 + o);
+      }
     }
   }
 }
@@ -332,6 +368,16 @@ int grid_for(int64_t items, int per_thread_trip) {
   }
   if (need > 0x7fffffff) need = 0x7fffffff;
   return (int)need;
+}
+
+// vectors per thread and row of the replica mean and the fused outer update (PARLE_OUTER_UNROLL = 1 or 2)
+int outer_unroll() {
+  static int u = [] {
+    const char *s = getenv("PARLE_OUTER_UNROLL");
+    const int v = s ? atoi(s) : 1;
+    return v == 2 ? 2 : 1;
+  }();
+  return u;
 }
 
 parle_status check_flat_args(int32_t n, int64_t n_pad) {
@@ -475,12 +521,30 @@ parle_status parle_k_replica_mean(void *hip_stream, int32_t n, int64_t n_pad, co
   if (!aligned_to(x, 16) || !aligned_to(x_ref, 16)) return PARLE_EALIGN;
   const int64_t np4 = n_pad / 4;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (tuning().nontemporal)
-    hipLaunchKernelGGL((k_replica_mean<true>), dim3(grid_for(np4, 1)), dim3(kThreads), 0, st, (const f4 *)x,
-                       (f4 *)x_ref, n, np4);
-  else
-    hipLaunchKernelGGL((k_replica_mean<false>), dim3(grid_for(np4, 1)), dim3(kThreads), 0, st, (const f4 *)x,
-                       (f4 *)x_ref, n, np4);
+  const int U = outer_unroll();
+#define LAUNCH_MEAN(N, UU)                                                                                          \
+  hipLaunchKernelGGL((k_replica_mean<N, UU, true>), dim3(grid_for(np4, UU)), dim3(kThreads), 0, st, (const f4 *)x, \
+                     (f4 *)x_ref, n, np4)
+#define PICK_MEAN(N)           \
+  case N:                      \
+    if (U == 2)                \
+      LAUNCH_MEAN(N, 2);       \
+    else                       \
+      LAUNCH_MEAN(N, 1);       \
+    break
+  switch (n) {
+    PICK_MEAN(1);
+    PICK_MEAN(2);
+    PICK_MEAN(3);
+    PICK_MEAN(4);
+    PICK_MEAN(5);
+    PICK_MEAN(6);
+    PICK_MEAN(7);
+    PICK_MEAN(8);
+    default: LAUNCH_MEAN(0, 1); break;
+  }
+#undef PICK_MEAN
+#undef LAUNCH_MEAN
   return launched();
 }
 
@@ -510,10 +574,18 @@ parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, fl
 #undef LAUNCH_OUTER
     return launched();
   }
-  dim3 grid(grid_for(np4, 1));
-#define LAUNCH_FUSED(N, BF)                                                                                          \
-  hipLaunchKernelGGL((k_outer_fused<N, true, BF>), grid, dim3(kThreads), 0, st, (f4 *)x, (f4 *)z, (f4 *)vx, (f4 *)y, \
-                     (f4 *)vy, (f4 *)x_ref, (us4 *)y_bf16, n, np4, eta_outer, momentum, c_z, r, reset_flags, lagged)
+  const int U = outer_unroll();
+#define LAUNCH_FUSED_U(N, UU, BF)                                                                                       \
+  hipLaunchKernelGGL((k_outer_fused<N, UU, true, BF>), dim3(grid_for(np4, UU)), dim3(kThreads), 0, st, (f4 *)x, (f4 *)z, \
+                     (f4 *)vx, (f4 *)y, (f4 *)vy, (f4 *)x_ref, (us4 *)y_bf16, n, np4, eta_outer, momentum, c_z, r,       \
+                     reset_flags, lagged)
+#define LAUNCH_FUSED(N, BF)       \
+  do {                            \
+    if (U == 2 && N > 0)          \
+      LAUNCH_FUSED_U(N, 2, BF);   \
+    else                          \
+      LAUNCH_FUSED_U(N, 1, BF);   \
+  } while (0)
 #define PICK_FUSED(N)                                               \
   case N:                                                           \
     if (y_bf16) LAUNCH_FUSED(N, true); else LAUNCH_FUSED(N, false); \
@@ -533,6 +605,7 @@ parle_status parle_k_outer_update(void *hip_stream, int32_t n, int64_t n_pad, fl
   }
 #undef PICK_FUSED
 #undef LAUNCH_FUSED
+#undef LAUNCH_FUSED_U
   return launched();
 }
 
