@@ -89,8 +89,8 @@ def profile_roofline(name):
             if len(f) >= 7 and f[-1].endswith("%") and f[0].startswith("k_"):
                 kern = " ".join(f[:-6])
                 if kern in util and util[kern][0] > 0:
-                    return {"kernel": kern, "avg_launch_us": float(f[-5]), "share_of_kernel_time": float(f[-1].rstrip("%")) / 100,
-                            "mfma_util": util[kern][0], "lds_bank_conflict": util[kern][1],
+                    return {"kernel": kern, "avg_launch_us": float(f[-5]), "share_of_kernel_time": round(float(f[-1].rstrip("%")) / 100, 4),
+                            "mfma_util": round(util[kern][0], 4), "lds_bank_conflict": round(util[kern][1], 4),
                             "source": f"profiles/{name}_kernel_stats.txt, profiles/{name}_pmc_mfma.txt"}
     except (OSError, ValueError):
         pass
@@ -287,6 +287,8 @@ def main():
                     help="for runs under `rocprofv3 --pmc`: the backward pass on ONE stream (sets PARLE_OVERLAP_WGRAD=0 "
                          "before the library is loaded).  Counter collection serialises dispatches across hardware "
                          "queues, and queues that wait on each other's events have gone silent under it")
+    ap.add_argument("--blocks", type=int, default=2, help="model workloads: timed blocks of 25 inner steps (counter runs of the "
+                                                           "largest network use 1: fewer dispatches for the profiler to hold)")
     ap.add_argument("--only-models", action="store_true",
                     help="profiling aid: skip the headline workload and print only the model timings")
     args = ap.parse_args()
@@ -306,7 +308,7 @@ def main():
     torch.cuda.set_device(0)
     names = list(MODEL_WORKLOADS) if args.models == "all" else [m for m in args.models.split(",") if m and m != "none"]
     if args.only_models:
-        print(json.dumps({"models": {nm: bench_model(nm, torch, pb, graph=not args.no_graph and not args.counters,
+        print(json.dumps({"models": {nm: bench_model(nm, torch, pb, blocks=args.blocks, graph=not args.no_graph and not args.counters,
                                                       progress=args.progress) for nm in names}}))
         return
     n, N = N_REPLICAS, N_PARAMS
@@ -376,7 +378,7 @@ def main():
         ref["inner_update_vs_read5_write3"] = round(achieved / ref["read5_write3"], 4)
         out["stream_reference"] = ref
     if names:
-        out["models"] = {nm: bench_model(nm, torch, pb, graph=not args.no_graph and not args.counters,
+        out["models"] = {nm: bench_model(nm, torch, pb, blocks=args.blocks, graph=not args.no_graph and not args.counters,
                                          progress=args.progress, cpu=not args.no_cpu_baseline) for nm in names}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
