@@ -235,6 +235,9 @@ parle_status parle_outer_step(parle_ctx *ctx);
  * 1 <= count <= n*batch.  Writes to HOST: mean loss, number of misclassified samples, and (if
  * not NULL) spread = sum_a ||x^a - x_ref||^2.  Blocks until the stream is idle.
  * FLAT: images/labels must be NULL, count 0; only spread is produced.
+ * PARLE_ENONFINITE if the mean loss is NaN or infinite (the outputs are written all the same, the context stays
+ * usable).  It sees what reaches the logits: a NaN in front of a ReLU is turned into 0 by it (`v > 0 ? v : 0`)
+ * and is not reported.
  */
 parle_status parle_eval(parle_ctx *ctx, int32_t which, const float *images_dev, const int32_t *labels_dev,
                         int32_t count, float *loss_host, int32_t *n_err_host, float *spread_host);

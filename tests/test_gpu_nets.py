@@ -482,6 +482,28 @@ def test_eval_matches_oracle(gpu, name, bf16):
             check("bn running stats", got[r], ref, 1e-4 if not bf16 else 2e-2)
 
 
+def test_eval_reports_a_non_finite_loss_and_the_context_stays_usable(gpu):
+    torch, pb = gpu
+    a = SMALL["mlp_vec"]
+    P, O = make(pb, a, 2, 8, seed=4)
+    X, Y = synth.image_batches(9, 1, 1, 8, a["H"], a["W"], a["C"], a["classes"])
+    xd, yd = dev(torch, X[0, 0]), dev(torch, Y[0, 0])
+    good = P.parle_eval(1, xd, yd)
+    at = pb.parle_query_layout(P.cfg)[-1]["offset"]      # a bias of the last layer: it reaches the logits directly
+    kept = float(P.x[1, at])
+    P.x[1, at] = float("nan")
+    torch.cuda.synchronize()
+    with pytest.raises(pb.ParleError) as e:
+        P.parle_eval(1, xd, yd)
+    assert e.value.status == pb.PARLE_ENONFINITE and "finite" in str(e.value)
+    # the other replica is untouched, and the poisoned one evaluates as before once the value is back
+    loss0, _, _ = P.parle_eval(0, xd, yd, want_spread=False)
+    assert np.isfinite(loss0)
+    P.x[1, at] = kept
+    torch.cuda.synchronize()
+    assert P.parle_eval(1, xd, yd) == good
+
+
 # ---------------------------------------------------------------------------------------------
 # Elastic-SGD (Section 2.2) on networks, and blocks of inner steps replayed from a HIP graph
 # ---------------------------------------------------------------------------------------------
