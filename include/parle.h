@@ -322,6 +322,17 @@ typedef struct {
 /* y = [relu]( conv(x, w) + bias + resid ); bias [n][cout] fp32 or NULL; resid like y or NULL. */
 parle_status parle_k_conv_forward(void *hip_stream, const parle_conv_desc *desc, const void *x, const void *w,
                                   const float *bias, const void *resid, int32_t relu, void *y);
+
+/* The same forward convolution (no bias, no ReLU: the form in front of a batch-norm of the residual
+ * networks) that also leaves, for the batch-norm statistics of its output, column sums taken in its
+ * epilogue: partial [n][S][2][cout] doubles, row s of replica a holding the sums over a group of
+ * output rows of y (as stored, i.e. after rounding to dtype) and of their squares; summing the S rows
+ * gives the sums over all batch*ho*wo rows.  S is written to *splits_host (HOST); S = 0 means the kernel
+ * that runs this layer takes no sums (then `partial` is untouched and the caller reduces y itself).
+ * `capacity`: rows per replica `partial` has room for (S never exceeds it). */
+parle_status parle_k_conv_forward_colsums(void *hip_stream, const parle_conv_desc *desc, const void *x, const void *w,
+                                          const void *resid, void *y, double *partial, int32_t capacity,
+                                          int32_t *splits_host);
 /* dx (+)= conv^T(dy, w), multiplied by (relu_mask > 0) when relu_mask (like x) is given.
  * wt_scratch: n*cout*k*k*cin elements of the tensor dtype (receives the transposed weights). */
 parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *w,

@@ -87,6 +87,8 @@ _SIGNATURES = {
     "parle_k_stream_reference": [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
     "parle_k_conv_forward": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_int32, C.c_void_p],
+    "parle_k_conv_forward_colsums": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_int32)],
     "parle_k_conv_backward_data": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_int32, C.c_void_p, C.c_void_p],
     "parle_k_conv_backward_weight": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -228,6 +230,14 @@ def parle_k_spread_static(x, x_ref, out, stream=None):
 def parle_k_conv_forward(desc, x, w, bias, resid, relu, y, stream=None):
     _check(lib().parle_k_conv_forward(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(resid),
                                       int(relu), _ptr(y)))
+
+
+def parle_k_conv_forward_colsums(desc, x, w, resid, y, partial, capacity, stream=None):
+    """Returns S, the number of partial rows per replica written to ``partial`` (0: none taken)."""
+    splits = C.c_int32(0)
+    _check(lib().parle_k_conv_forward_colsums(_stream_handle(stream), C.byref(desc), _ptr(x), _ptr(w), _ptr(resid),
+                                              _ptr(y), _ptr(partial), int(capacity), C.byref(splits)))
+    return splits.value
 
 
 def parle_k_conv_backward_data(desc, dy, w, relu_mask, accumulate, wt_scratch, dx, stream=None):

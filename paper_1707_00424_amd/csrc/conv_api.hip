@@ -45,6 +45,31 @@ parle_status parle_k_conv_forward(void *hip_stream, const parle_conv_desc *desc,
   return launch_igemm((hipStream_t)hip_stream, desc->dtype, false, desc->n, g, io) == hipSuccess ? PARLE_OK : PARLE_EHIP;
 }
 
+parle_status parle_k_conv_forward_colsums(void *hip_stream, const parle_conv_desc *desc, const void *x, const void *w,
+                                          const void *resid, void *y, double *partial, int32_t capacity,
+                                          int32_t *splits_host) {
+  ConvShape c;
+  if (parle_status s = check_desc(desc, c)) return s;
+  if (!x || !w || !y || !partial || !splits_host || capacity < 1) return PARLE_EINVAL;
+  if (!aligned_to(x, 16) || !aligned_to(w, 16) || !aligned_to(y, 16) || !aligned_to(resid, 16) || !aligned_to(partial, 8))
+    return PARLE_EALIGN;
+  const int es = desc->dtype ? 2 : 4, vw = 16 / es;
+  const ConvGeom g = conv_fwd_geom(c);
+  GemmIO io{};
+  io.in = x, io.in_rs = (long long)c.B * c.H * c.W * c.Cin;
+  io.w = w, io.w_rs = (long long)g.N * g.K;
+  io.out = y, io.out_rs = (long long)g.M * g.N, io.ldc = g.N;
+  io.resid = resid, io.resid_rs = io.out_rs;
+  io.vecA = (c.Cin % vw == 0) && (io.in_rs % vw == 0);
+  io.vecB = (g.K % vw == 0);
+  io.in_bytes = io.in_rs * es;
+  io.stat = partial, io.stat_capacity = capacity;
+  int S = 0;
+  if (launch_igemm((hipStream_t)hip_stream, desc->dtype, false, desc->n, g, io, &S) != hipSuccess) return PARLE_EHIP;
+  *splits_host = S;
+  return PARLE_OK;
+}
+
 parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *w,
                                         const void *relu_mask, int32_t accumulate, void *wt_scratch, void *dx) {
   ConvShape c;

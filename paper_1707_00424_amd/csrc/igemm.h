@@ -61,6 +61,11 @@ struct GemmIO {
   int relu, accumulate;
   int vecA, vecB;     // 16-byte loads allowed for the gathered operand / the weight matrix
   long long in_bytes; // bytes of one replica's gathered tensor (range of the buffer loads)
+  // Column sums of the stored output and of its squares, per workgroup of pixel rows, for the batch-norm that
+  // follows: [replica][S][2][ldc] doubles, or NULL.  Only launch_igemm's callers that ask for the split count
+  // set it; kernels that do not produce the sums ignore it and launch_igemm reports S = 0.
+  double *stat;
+  int stat_capacity;  // partial rows per replica the buffer has room for
 };
 
 struct WgradIO {
@@ -101,7 +106,10 @@ inline ConvGeom conv_bwd_geom(const ConvShape &c) {
 }
 
 // dtype: 0 = fp32 (v_mfma_f32_32x32x2_f32), 1 = bf16 (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
-hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+// `stat_splits`: with io.stat set, receives the number S of partial rows of column sums the kernel writes
+// (0: the kernel that runs this layer does not produce them; the caller takes them in a pass of its own).
+hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io,
+                        int *stat_splits = nullptr);
 hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom &g, const WgradIO &io);
 // Vector fast paths (igemm_fast.hip); launch_igemm / launch_wgrad pick them when applicable.
 bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
@@ -109,6 +117,7 @@ hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replic
 // Stride-1 'same' convolutions with the input patch staged once in LDS (igemm_halo.hip).
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
 hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);
+int conv_halo_stat_splits(const ConvGeom &g, int replicas);
 bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
 void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
 hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);

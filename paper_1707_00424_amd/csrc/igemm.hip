@@ -370,8 +370,20 @@ int bf16_ntile(int n) {
 
 }  // namespace
 
-hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
+hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io_in,
+                        int *stat_splits) {
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
+  if (stat_splits) *stat_splits = 0;
+  if (io_in.stat && stat_splits && conv_halo_applicable(dtype, g, io_in, out_f32) &&
+      !conv_smallk_applicable(dtype, g, io_in)) {
+    const int S = conv_halo_stat_splits(g, replicas);
+    if (S > 0 && S <= io_in.stat_capacity) {
+      *stat_splits = S;
+      return launch_conv_halo(st, replicas, g, io_in);
+    }
+  }
+  GemmIO io = io_in;
+  io.stat = nullptr;
   if (conv_smallk_applicable(dtype, g, io)) return launch_conv_smallk(st, dtype, out_f32, replicas, g, io);
   if (conv_halo_applicable(dtype, g, io, out_f32)) return launch_conv_halo(st, replicas, g, io);
   if (dgrad_s2_applicable(dtype, g, io, out_f32)) return launch_dgrad_s2(st, replicas, g, io);

@@ -224,9 +224,15 @@ constexpr int kStageFloats = 32 * (TN * 32 + 4);
 
 constexpr uint32_t kOobOffset = 0x80000000u;  // beyond any per-replica tensor (each is < 2 GiB)
 
-template <typename T, int TM, int TN, bool OUT_F32>
+//
+// STAT: column sums of what is stored (the values as rounded to the output type) and of their squares, over the
+// wavefront's TM*32 rows: afterwards `wsum[c]` and `wsum[TN*32 + c]`, c < TN*32, hold them for channel ncol0 + c.
+// They are the statistics the batch-norm that follows the convolution needs, taken while the tile is at hand
+// instead of in a pass of their own over the tensor.  Order of the additions: a lane adds its vectors in walk
+// order, then the lanes that share a channel are added in row order - fixed, so the sums are reproducible.
+template <typename T, int TM, int TN, bool OUT_F32, bool STAT = false>
 __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
-                                               f16v (&acc)[TM][TN], float *stage) {
+                                               f16v (&acc)[TM][TN], float *stage, float *wsum = nullptr) {
   typedef unsigned int u2v __attribute__((ext_vector_type(2)));
   constexpr int CW = TN * 32, LD = CW + 4, CPR = CW / 4;
   constexpr int NIT = CPR / 2;                                  // vectors per lane and 32-row strip
@@ -246,6 +252,27 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
   // per lane and phase of the period: strip address, element offset inside a 32-row strip, validity
   int lds_b[PER], row_b[PER], ch_b[PER];
   f4 bias_b[PER];
+  f4 sum_b[STAT ? PER : 1], sq_b[STAT ? PER : 1];
+#pragma unroll
+  for (int r = 0; r < (STAT ? PER : 1); ++r) sum_b[r] = f4{0.f, 0.f, 0.f, 0.f}, sq_b[r] = f4{0.f, 0.f, 0.f, 0.f};
+  // what a lane adds for one vector: the stored value (zero outside the tile)
+  auto tally = [&](int r, f4 t, uint32_t off) {
+    if (off == kOobOffset) t = f4{0.f, 0.f, 0.f, 0.f};
+    sum_b[STAT ? r : 0] += t;
+    sq_b[STAT ? r : 0] += t * t;
+  };
+  // stores a vector and, with STAT, adds what was stored to the lane's sums
+  auto emit = [&](int r, const f4 &v, uint32_t off) {
+    const uint32_t bo = off == kOobOffset ? kOobOffset : off * OS;
+    if (OS == 4) {
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), o_rsrc, bo, 0, 0);
+      if (STAT) tally(r, v, off);
+    } else {
+      const us4 pk = f32x4_to_bf16x4(v);
+      __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, pk), o_rsrc, bo, 0, 0);
+      if (STAT) tally(r, Vec4<bf16_t>::to_f32(pk), off);
+    }
+  };
 #pragma unroll
   for (int r = 0; r < PER; ++r) {
     const int c = 64 * r + lane;
@@ -346,13 +373,7 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
           for (int i = 0; i < BATCH; ++i) val[i] += OS == 4 ? of[i] : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
         }
   #pragma unroll
-        for (int i = 0; i < BATCH; ++i) {
-          const uint32_t bo = off[i] == kOobOffset ? kOobOffset : off[i] * OS;
-          if (OS == 4)
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, val[i]), o_rsrc, bo, 0, 0);
-          else
-            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(val[i])), o_rsrc, bo, 0, 0);
-        }
+        for (int i = 0; i < BATCH; ++i) emit(0, val[i], off[i]);
       } else {
         // 96-wide tiles (period 3): the per-vector form measured faster there
 #pragma unroll
@@ -369,13 +390,27 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
             v.z = mk.z > 0.f ? v.z : 0.f, v.w = mk.w > 0.f ? v.w : 0.f;
           }
           if (io.accumulate) v += OS == 4 ? of[i] : Vec4<bf16_t>::to_f32(__builtin_bit_cast(us4, ov[i]));
-          const uint32_t bo = off[i] == kOobOffset ? kOobOffset : off[i] * OS;
-          if (OS == 4)
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u4, v), o_rsrc, bo, 0, 0);
-          else
-            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u2v, f32x4_to_bf16x4(v)), o_rsrc, bo, 0, 0);
+          emit((b0 + i) % PER, v, off[i]);
         }
       }
+    }
+  }
+  if (STAT) {
+    // lanes that share a channel group sit RPP rows apart in the walk: park the lane sums in the strip (rows
+    // 0 .. RPP-1 the sums, RPP .. 2*RPP-1 the squares) and let one lane per group add them
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+    for (int r = 0; r < PER; ++r) {
+      *(f4 *)&stage[lds_b[r]] = sum_b[STAT ? r : 0];
+      *(f4 *)&stage[RPP * LD + lds_b[r]] = sq_b[STAT ? r : 0];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if (lane < CPR) {
+      f4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < RPP; ++j) a += *(const f4 *)&stage[j * LD + 4 * lane], b += *(const f4 *)&stage[(RPP + j) * LD + 4 * lane];
+      *(f4 *)&wsum[4 * lane] = a;
+      *(f4 *)&wsum[CW + 4 * lane] = b;
     }
   }
 }

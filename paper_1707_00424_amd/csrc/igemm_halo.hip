@@ -35,15 +35,16 @@ struct HaloGeom {
 
 // LDS of a workgroup with TN column tiles: patch + a ring of three weight tiles; the epilogue reuses the same
 // bytes as its staging strips
-template <int TN>
+// with STAT, the column sums of the four wavefronts (2 x TN*32 floats each) lie behind the strips
+template <int TN, bool STAT = false>
 constexpr int halo_lds_bytes() {
   constexpr int pipe = (kHaloSlots + 3 * TN * 32) * (32 + 8) * 2;
-  constexpr int stage = 4 * kStageFloats<TN> * (int)sizeof(float);
+  constexpr int stage = 4 * kStageFloats<TN> * (int)sizeof(float) + (STAT ? 4 * 2 * TN * 32 * (int)sizeof(float) : 0);
   return pipe > stage ? pipe : stage;
 }
 
 // `tile`, `col`: pixel tile and column block of this workgroup; column blocks before it are hg.bn wide.
-template <int TN>
+template <int TN, bool STAT>
 __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &io, const HaloGeom &hg, char *smem,
                                                int tile, int col) {
   typedef bf16_t T;
@@ -239,8 +240,23 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   for (int i = 0; i < D - 1; ++i)
     if (kt + i < KT) step(kt + i, rq[i]);
   // the barrier that ends the last step: patch and weight tiles are dead, their LDS becomes the staging strips
-  store_tile_lds<T, TM, TN, false>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
-                                   reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
+  float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
+  store_tile_lds<T, TM, TN, false, STAT>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
+                                         reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>, wsums + wave * 2 * BN);
+  if (STAT) {
+    // the workgroup's 256 rows: the four wavefronts' sums added in wavefront order, one partial row per pixel tile
+    __syncthreads();
+    if (tid < 2 * BN / 4) {
+      f4 a = *(const f4 *)&wsums[4 * tid];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) a += *(const f4 *)&wsums[w * 2 * BN + 4 * tid];
+      const int k = tid >= BN / 4, c = n0 + 4 * (tid - k * (BN / 4));
+      if (c < g.N) {
+        double *dst = io.stat + (((long long)rep * hg.tiles + tile) * 2 + k) * io.ldc + c;
+        dst[0] = a.x, dst[1] = a.y, dst[2] = a.z, dst[3] = a.w;
+      }
+    }
+  }
 }
 
 // Workgroups are handed to the eight XCDs in turn, so ids that differ by 8 share an L2: the column blocks
@@ -255,25 +271,27 @@ __device__ __forceinline__ bool halo_block(const HaloGeom &hg, int &tile, int &c
 
 // Column blocks 0 .. nb-2 are TN tiles wide, the last one TL <= TN tiles (160 channels = 96 + 64,
 // 320 = 128 + 128 + 64): a narrower last block multiplies no padding.
-template <int TN, int TL>
-__global__ __launch_bounds__(kThreads) void k_conv_halo(const ConvGeom g, const GemmIO io, const HaloGeom hg) {
-  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<TN>()];
+template <int TN, int TL, bool STAT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void k_conv_halo(const ConvGeom g, const GemmIO io,
+                                                                                               const HaloGeom hg) {
+  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<TN, STAT>()];
   int tile, col;
   if (!halo_block(hg, tile, col)) return;
   if (TL != TN && col == hg.nb - 1)
-    conv_halo_body<TL>(g, io, hg, smem, tile, col);
+    conv_halo_body<TL, STAT>(g, io, hg, smem, tile, col);
   else
-    conv_halo_body<TN>(g, io, hg, smem, tile, col);
+    conv_halo_body<TN, STAT>(g, io, hg, smem, tile, col);
 }
 // 64 output channels: few enough registers for three workgroups per compute unit, which hides more of
 // the prologue and epilogue of one workgroup behind the matrix work of the others
+template <bool STAT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void k_conv_halo_n64(const ConvGeom g,
                                                                                                    const GemmIO io,
                                                                                                    const HaloGeom hg) {
-  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<2>()];
+  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<2, STAT>()];
   int tile, col;
   if (!halo_block(hg, tile, col)) return;
-  conv_halo_body<2>(g, io, hg, smem, tile, col);
+  conv_halo_body<2, STAT>(g, io, hg, smem, tile, col);
 }
 
 // grid of `tiles` pixel tiles x `nb` column blocks of `bn` channels (the last may be narrower), laid out in
@@ -288,7 +306,10 @@ dim3 halo_grid(const ConvGeom &g, int bn, int replicas, HaloGeom &hg) {
 template <int TN, int TL>
 hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, HaloGeom hg) {
   const dim3 grid = halo_grid(g, TN * 32, replicas, hg);
-  hipLaunchKernelGGL((k_conv_halo<TN, TL>), grid, dim3(kThreads), 0, st, g, io, hg);
+  if (TN == 4 && io.stat)
+    hipLaunchKernelGGL((k_conv_halo<TN, TL, TN == 4>), grid, dim3(kThreads), 0, st, g, io, hg);
+  else
+    hipLaunchKernelGGL((k_conv_halo<TN, TL, false>), grid, dim3(kThreads), 0, st, g, io, hg);
   return hipGetLastError();
 }
 
@@ -323,30 +344,57 @@ bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool o
          g.M >= 256 && make_halo_geom(g, hg);
 }
 
+namespace {
+
+// Which variant runs a layer.  A launch that wide blocks leave below two workgroups per compute unit runs 64-wide
+// ones when those fill the chip in one round at more than two and at most three per unit: every SIMD then holds
+// three wavefronts instead of one or two, which overlap each other's LDS reads and MFMAs (128 channels on
+// 16 x 16 images, three replicas of 128: -8 %).  With fewer narrow workgroups than that the wide ones are as fast
+// or faster.  Otherwise 96- or 128-wide column blocks, whichever pads the output channels least (ties go to the
+// wider tile); a last block of at most 64 channels runs two tiles wide.
+enum HaloVariant { kHalo64, kHalo96, kHalo128 };
+HaloVariant halo_variant(const ConvGeom &g, int replicas) {
+  constexpr int kCus = 256;
+  const int n = g.N;
+  const long long tiles = (g.M + 255) / 256, wide = tiles * ((n + 127) / 128) * replicas,
+                  narrow_wgs = tiles * (n / 64) * replicas;
+  const bool narrow = n % 64 == 0 && wide < 2 * kCus && narrow_wgs > 2 * kCus && narrow_wgs <= 3 * kCus;
+  if (n <= 64 || narrow) return kHalo64;
+  const int pad3 = (n + 95) / 96 * 96, pad4 = (n + 127) / 128 * 128;
+  return pad3 < pad4 ? kHalo96 : kHalo128;
+}
+
+}  // namespace
+
+// Partial rows of column sums (one per pixel tile) a launch with io.stat set writes; 0 where the variant that runs
+// the layer does not take them: in the 96-wide epilogue, whose walk visits three channel groups per lane, the
+// sums cost more than the reduction pass they replace (160 channels on 32 x 32 images: +0.5 % per step against
+// -0.7 % for the other layers of the same network).
+int conv_halo_stat_splits(const ConvGeom &g, int replicas) {
+  return halo_variant(g, replicas) == kHalo96 ? 0 : (g.M + 255) / 256;
+}
+
 hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io) {
   HaloGeom hg;
   if (!make_halo_geom(g, hg)) return hipErrorInvalidValue;
   const int n = g.N;
-  // A launch that wide blocks leave below two workgroups per compute unit runs 64-wide ones when those fill
-  // the chip in one round at more than two and at most three per unit: every SIMD then holds three wavefronts
-  // instead of one or two, which overlap each other's LDS reads and MFMAs (128 channels on 16 x 16 images,
-  // three replicas of 128: -8 %).  With fewer narrow workgroups than that the wide ones are as fast or faster.
-  constexpr int kCus = 256;
-  const long long tiles = (g.M + 255) / 256, wide = tiles * ((n + 127) / 128) * replicas,
-                  narrow_wgs = tiles * (n / 64) * replicas;
-  const bool narrow = n % 64 == 0 && wide < 2 * kCus && narrow_wgs > 2 * kCus && narrow_wgs <= 3 * kCus;
-  if (n <= 64 || narrow) {
-    const dim3 grid = halo_grid(g, 64, replicas, hg);
-    hipLaunchKernelGGL(k_conv_halo_n64, grid, dim3(kThreads), 0, st, g, io, hg);
-    return hipGetLastError();
+  switch (halo_variant(g, replicas)) {
+    case kHalo64: {
+      const dim3 grid = halo_grid(g, 64, replicas, hg);
+      if (io.stat)
+        hipLaunchKernelGGL(k_conv_halo_n64<true>, grid, dim3(kThreads), 0, st, g, io, hg);
+      else
+        hipLaunchKernelGGL(k_conv_halo_n64<false>, grid, dim3(kThreads), 0, st, g, io, hg);
+      return hipGetLastError();
+    }
+    case kHalo96: {
+      if (io.stat) return hipErrorInvalidValue;  // see conv_halo_stat_splits
+      const int last = n - ((n + 95) / 96 * 96 - 96);
+      return last <= 64 ? run_halo<3, 2>(st, replicas, g, io, hg) : run_halo<3, 3>(st, replicas, g, io, hg);
+    }
+    default: {
+      const int last = n - ((n + 127) / 128 * 128 - 128);
+      return last <= 64 ? run_halo<4, 2>(st, replicas, g, io, hg) : run_halo<4, 4>(st, replicas, g, io, hg);
+    }
   }
-  // 96- or 128-wide column blocks, whichever pads the output channels least (ties go to the wider tile);
-  // a last block of at most 64 channels runs two tiles wide
-  const int pad3 = (n + 95) / 96 * 96, pad4 = (n + 127) / 128 * 128;
-  if (pad3 < pad4) {
-    const int last = n - (pad3 - 96);
-    return last <= 64 ? run_halo<3, 2>(st, replicas, g, io, hg) : run_halo<3, 3>(st, replicas, g, io, hg);
-  }
-  const int last = n - (pad4 - 128);
-  return last <= 64 ? run_halo<4, 2>(st, replicas, g, io, hg) : run_halo<4, 4>(st, replicas, g, io, hg);
 }

@@ -36,7 +36,7 @@ parle_status parle_k_bn_forward(void *hip_stream, const parle_act_desc *desc, co
   if (!aligned_to(x, 16) || !aligned_to(out, 16) || !aligned_to(scratch, 16)) return PARLE_EALIGN;
   if (scratch_bytes < reduce_bytes(desc)) return PARLE_ESIZE;
   return done(launch_bn_train_fwd((hipStream_t)hip_stream, desc->dtype, desc->n, (int)rows(desc), desc->c, x, elems(desc),
-                                  gamma, beta, desc->c, (double *)scratch, saved, running, 2LL * desc->c, out, elems(desc)));
+                                  gamma, beta, desc->c, (double *)scratch, 0, saved, running, 2LL * desc->c, out, elems(desc)));
 }
 
 parle_status parle_k_bn_backward(void *hip_stream, const parle_act_desc *desc, const void *x, const void *dout,

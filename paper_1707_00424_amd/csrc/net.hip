@@ -50,6 +50,7 @@ struct Op {
   int gseg = -1, betaseg = -1;
   int64_t saved_off = -1, sums_off = -1, run_off = 0;  // run_off in floats inside a replica's BN row
   int bn_add = -1;         // tensor whose gradient is added to this op's input gradient
+  int stat_src = -1;       // the convolution that writes this op's input, if its epilogue can take the column sums
   // dropout
   int site = 0;            // index of the dropout site in execution order (part of the mask's key)
   bool drop_relu = false;  // the input is a ReLU output whose backward mask this op applies
@@ -295,6 +296,12 @@ bool build_plan(Net &N, std::string &err) {
       err = "model has no network";
       return false;
   }
+  // a batch-norm whose input a convolution of the chain writes can get its column sums from that convolution
+  for (size_t i = 0; i < N.ops.size(); ++i) {
+    if (N.ops[i].type != OP_BNRELU) continue;
+    for (size_t j = 0; j < i; ++j)
+      if (N.ops[j].type == OP_CONV && N.ops[j].out == N.ops[i].in && !N.ops[j].branch) N.ops[i].stat_src = (int)j;
+  }
   // gradients, transposed weights, scratch
   N.leaf_waves = N.max_bn_c > 0 ? 512 : 0;
   int64_t wpartial = 0, wpartial_main = 0, col_bytes = 0;
@@ -417,6 +424,16 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
   const bool branches = train && N.side != nullptr;  // shortcut convolutions beside the chain
   // a shortcut waits until the chain's next convolution has been enqueued (see the note on order in backward())
   int pending = -1;
+  // per convolution: partial rows of column sums its epilogue left for the batch-norm that reads its output
+  std::vector<int> stat_S(N.ops.size(), 0);
+  std::vector<char> wants_stat(N.ops.size(), 0);
+  static const bool epilogue_stats = [] {
+    const char *e = getenv("PARLE_EPILOGUE_STATS");
+    return !(e && atoi(e) == 0);
+  }();
+  if (train && epilogue_stats)
+    for (const Op &op : N.ops)
+      if (op.type == OP_BNRELU && op.stat_src >= 0) wants_stat[op.stat_src] = 1;
   auto conv_io = [&](const Op &op, const ConvGeom &g) {
     GemmIO io{};
     io.in = r.tptr(op.in), io.in_rs = r.trs(op.in);
@@ -458,7 +475,10 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
           HIP_TRY(launch_pending());
           HIP_TRY(hipStreamWaitEvent(r.st, N.br_out[op.join], 0));
         }
-        HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, conv_io(op, g)));
+        GemmIO io = conv_io(op, g);
+        // the sums go where the batch-norm's own reduction would put them (room for 1024 partial rows per replica)
+        if (wants_stat[oi]) io.stat = (double *)(r.ws + N.off_colpartial), io.stat_capacity = 1024;
+        HIP_TRY(launch_igemm(r.st, N.dtype, N.tensors[op.out].f32, r.n, g, io, &stat_S[oi]));
         HIP_TRY(launch_pending());
         break;
       }
@@ -489,8 +509,9 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         float *saved = (float *)(r.ws + op.saved_off);
         if (train) {
           HIP_TRY(launch_bn_train_fwd(r.st, N.dtype, r.n, M, ti.C, r.tptr(op.in), r.trs(op.in), r.fptr(op.gseg),
-                                      r.fptr(op.betaseg), r.p_rs, (double *)(r.ws + N.off_colpartial), saved,
-                                      bn_stats + op.run_off, N.bn_floats, r.tptr(op.out), r.trs(op.out)));
+                                      r.fptr(op.betaseg), r.p_rs, (double *)(r.ws + N.off_colpartial),
+                                      op.stat_src >= 0 ? stat_S[op.stat_src] : 0, saved, bn_stats + op.run_off,
+                                      N.bn_floats, r.tptr(op.out), r.trs(op.out)));
         } else {
           HIP_TRY(launch_bn_eval_fwd(r.st, N.dtype, M, ti.C, r.tptr(op.in), r.fptr(op.gseg), r.fptr(op.betaseg),
                                      bn_eval_row + op.run_off, saved, r.tptr(op.out)));

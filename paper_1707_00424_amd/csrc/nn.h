@@ -37,9 +37,11 @@ hipError_t launch_reduce_partials(hipStream_t st, int n, int S, long long len, c
 
 // Batch normalisation (per replica, per channel, over M rows), fused with the ReLU that follows it.
 // saved: [n][2][C] fp32 = mean, 1/sqrt(var + eps).  running: [2][C] per replica (mean, var), stride run_rs.
+// pre_splits > 0: `partial` already holds [n][pre_splits][2][C] column sums of x and x*x (left there by the
+// convolution that wrote x); the reduction pass over x is then skipped.
 hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
-                               const float *gamma, const float *beta, long long p_rs, double *partial, float *saved,
-                               float *running, long long run_rs, void *out, long long out_rs);
+                               const float *gamma, const float *beta, long long p_rs, double *partial, int pre_splits,
+                               float *saved, float *running, long long run_rs, void *out, long long out_rs);
 hipError_t launch_bn_eval_fwd(hipStream_t st, int dtype, int M, int C, const void *x, const float *gamma,
                               const float *beta, const float *running_row, float *saved, void *out);
 // dx = BN-ReLU backward of dout (+ add when not NULL); dgamma, dbeta written to grad (fp32, stride p_rs).

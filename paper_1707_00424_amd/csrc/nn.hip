@@ -1032,15 +1032,19 @@ hipError_t launch_reduce_partials(hipStream_t st, int n, int S, long long len, c
 }
 
 hipError_t launch_bn_train_fwd(hipStream_t st, int dtype, int n, int M, int C, const void *x, long long x_rs,
-                               const float *gamma, const float *beta, long long p_rs, double *partial, float *saved,
-                               float *running, long long run_rs, void *out, long long out_rs) {
-  const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
-  dim3 grid(S, n);
-  DISPATCH_T(dtype,
-             (run_colreduce<float, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
-                                      partial)),
-             (run_colreduce<bf16_t, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
-                                       partial)));
+                               const float *gamma, const float *beta, long long p_rs, double *partial, int pre_splits,
+                               float *saved, float *running, long long run_rs, void *out, long long out_rs) {
+  // pre_splits > 0: the kernel that wrote x has left that many partial rows of column sums in `partial`
+  const int S = pre_splits > 0 ? pre_splits : colreduce_splits(n, M);
+  if (pre_splits <= 0) {
+    const int chunk = col_chunk(M, S), ct = channel_lanes(C);
+    dim3 grid(S, n);
+    DISPATCH_T(dtype,
+               (run_colreduce<float, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr, 0LL,
+                                        partial)),
+               (run_colreduce<bf16_t, 1>(st, grid, M, C, chunk, ct, x, x_rs, nullptr, 0LL, nullptr, nullptr, nullptr,
+                                         0LL, partial)));
+  }
   hipLaunchKernelGGL(k_bn_stats_finalize, dim3(C, n), dim3(kFinThreads), 0, st, M, C, S, partial, saved, running,
                      run_rs);
   const int vw = dtype ? 8 : 4;

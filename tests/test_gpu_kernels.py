@@ -161,6 +161,57 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
         assert_near(f"wgrad[{r}]", download(gw[r]), rdw, 0.0, 2e-5 * np.abs(rdw).max())
 
 
+@pytest.mark.parametrize("case,expect_sums", [
+    # n, B, H, W, Cin, Cout, k, stride, pad; does the kernel that runs the layer take the sums?
+    ((2, 8, 16, 16, 16, 64, 3, 1, 1), True),      # 64-wide blocks
+    ((2, 3, 16, 16, 32, 128, 3, 1, 1), True),     # one 128-wide block
+    ((1, 6, 8, 8, 64, 320, 3, 1, 1), True),       # 320 = 128 + 128 + 64: the narrower last block; 4 images per tile, 6 images
+    ((3, 128, 32, 32, 64, 64, 3, 1, 1), True),    # WRN-16-4 group 1 at full size: 512 partial rows
+    ((3, 128, 8, 8, 256, 256, 3, 1, 1), True),    # WRN-16-4 group 3 at full size
+    ((2, 4, 16, 16, 32, 160, 3, 1, 1), False),    # 96-wide blocks: no sums, the caller reduces
+    ((2, 4, 16, 16, 32, 64, 3, 2, 1), False),     # stride 2: another kernel
+])
+def test_conv_epilogue_column_sums(gpu, case, expect_sums):
+    """The sums a convolution leaves for the batch-norm behind it are the column sums of exactly what it stored
+    (bf16 values) and of their squares, to fp32 summation accuracy; with a residual as in the second convolution
+    of a block."""
+    torch, pb = gpu
+    n, B, H, W, Cin, Cout, k, stride, pad = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    x = upload(torch, to_bf16_grid(rng.standard_normal((n, B, H, W, Cin))), 1)
+    w = upload(torch, to_bf16_grid(rng.standard_normal((n, Cout, k, k, Cin)) / np.sqrt(k * k * Cin)), 1)
+    # a per-channel offset makes mean^2 >> variance in some channels, where one-pass variances are delicate
+    shift = np.linspace(-4.0, 4.0, Cout).astype(np.float32)
+    resid = upload(torch, to_bf16_grid(rng.standard_normal((n, B, Ho, Wo, Cout)) + shift), 1)
+    desc = pb.parle_conv_desc(1, n, B, H, W, Cin, Cout, k, stride, pad)
+    cap = 1024
+    for res in (None, resid):
+        y = torch.zeros((n, B, Ho, Wo, Cout), dtype=torch.bfloat16, device="cuda")
+        y_plain = torch.zeros_like(y)
+        partial = torch.full((n * cap * 2 * Cout,), float("nan"), dtype=torch.float64, device="cuda")
+        S = pb.parle_k_conv_forward_colsums(desc, x, w, res, y, partial, cap)
+        pb.parle_k_conv_forward(desc, x, w, None, res, 0, y_plain)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_plain), "the sums must not change what is stored"
+        if not expect_sums:
+            assert S == 0 and bool(torch.isnan(partial).all())
+            continue
+        M = B * Ho * Wo
+        assert S == (M + 255) // 256
+        used = n * S * 2 * Cout          # [n][S][2][Cout], replicas S rows apart
+        got = partial[:used].cpu().numpy().reshape(n, S, 2, Cout)
+        assert np.isfinite(got).all() and bool(torch.isnan(partial[used:]).all())
+        yv = y.double().cpu().numpy().reshape(n, M, Cout)
+        # per partial row: the 256 rows of its pixel tile
+        pad_rows = S * 256 - M
+        yt = np.concatenate([yv, np.zeros((n, pad_rows, Cout))], axis=1).reshape(n, S, 256, Cout)
+        ref1, ref2 = yt.sum(axis=2), (yt * yt).sum(axis=2)
+        scale1 = np.abs(yt).sum(axis=2) + 1e-30
+        assert np.max(np.abs(got[:, :, 0] - ref1) / scale1) < 1e-5   # one element of 256 left out would show as 4e-3
+        assert np.max(np.abs(got[:, :, 1] - ref2) / (ref2 + 1e-30)) < 1e-5
+
+
 @pytest.mark.parametrize("layer", [
     # full-size layers of the workloads at the launch shapes the bench times (batch 128): dtype, n, B, H, W, Cin, Cout, k, stride, pad
     (1, 3, 128, 32, 32, 96, 96, 3, 1, 1),      # All-CNN-C conv2

@@ -11,7 +11,9 @@ import pytest
 from paper_1707_00424_amd import build as pbuild
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SAN = ["-Xarch_host", "-fsanitize=address,undefined", "-Xarch_host", "-fno-sanitize-recover=undefined", "-O1", "-g"]
+# host pass only: the device pass of every source is compiled as always
+SAN = "-Xarch_host -fsanitize=address,undefined -Xarch_host -fno-sanitize-recover=undefined -O1 -g".split()
+LINK = "--offload-arch=gfx950 -fno-gpu-sanitize -fsanitize=address,undefined".split()
 
 
 def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
@@ -29,8 +31,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, sources))
     exe = str(tmp_path / "host_walk")
-    r = subprocess.run([pbuild.HIPCC, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-o", exe, *objs],
-                       capture_output=True, text=True)
+    r = subprocess.run([pbuild.HIPCC, *LINK, "-o", exe, *objs], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
