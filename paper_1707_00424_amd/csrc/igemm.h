@@ -114,6 +114,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 // Vector fast paths (igemm_fast.hip); launch_igemm / launch_wgrad pick them when applicable.
 bool igemm_fast_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
 hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+int igemm_fast_stat_splits(int dtype, bool out_f32, const ConvGeom &g, const GemmIO &io);
 // Stride-1 'same' convolutions with the input patch staged once in LDS (igemm_halo.hip).
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
 hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);
@@ -124,6 +125,7 @@ hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, co
 // Layers whose whole contraction fits one tile, K = R*S*Cin <= 32 (igemm_smallk.hip).
 bool conv_smallk_applicable(int dtype, const ConvGeom &g, const GemmIO &io);
 hipError_t launch_conv_smallk(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
+int conv_smallk_stat_splits(const ConvGeom &g, bool out_f32);
 bool wgrad_smallk_applicable(int dtype, const ConvGeom &g);
 hipError_t launch_wgrad_smallk(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Stride-1 'same' 3x3 backward-weight with the patch staged in LDS and nine taps per wavefront (igemm_wgrad9.hip).

@@ -374,12 +374,21 @@ hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, c
                         int *stat_splits) {
   if (g.M < 1 || g.N < 1 || g.K < 1 || replicas < 1 || replicas > 65535) return hipErrorInvalidValue;
   if (stat_splits) *stat_splits = 0;
-  if (io_in.stat && stat_splits && conv_halo_applicable(dtype, g, io_in, out_f32) &&
-      !conv_smallk_applicable(dtype, g, io_in)) {
-    const int S = conv_halo_stat_splits(g, replicas);
+  if (io_in.stat && stat_splits) {
+    // the same order of choices as below, for the kernels whose epilogue can take the sums
+    int S = 0;
+    const bool smallk = conv_smallk_applicable(dtype, g, io_in);
+    const bool halo = !smallk && conv_halo_applicable(dtype, g, io_in, out_f32);
+    const bool fast = !smallk && !halo && !dgrad_s2_applicable(dtype, g, io_in, out_f32) &&
+                      !gemm_ksplit_applicable(dtype, replicas, g, io_in) && igemm_fast_applicable(dtype, g, io_in);
+    if (smallk) S = conv_smallk_stat_splits(g, out_f32);
+    if (halo) S = conv_halo_stat_splits(g, replicas);
+    if (fast) S = igemm_fast_stat_splits(dtype, out_f32, g, io_in);
     if (S > 0 && S <= io_in.stat_capacity) {
       *stat_splits = S;
-      return launch_conv_halo(st, replicas, g, io_in);
+      if (smallk) return launch_conv_smallk(st, dtype, out_f32, replicas, g, io_in);
+      if (halo) return launch_conv_halo(st, replicas, g, io_in);
+      return launch_igemm_fast(st, dtype, out_f32, replicas, g, io_in);
     }
   }
   GemmIO io = io_in;

@@ -230,9 +230,11 @@ constexpr uint32_t kOobOffset = 0x80000000u;  // beyond any per-replica tensor (
 // They are the statistics the batch-norm that follows the convolution needs, taken while the tile is at hand
 // instead of in a pass of their own over the tensor.  Order of the additions: a lane adds its vectors in walk
 // order, then the lanes that share a channel are added in row order - fixed, so the sums are reproducible.
+// (`sq_off`: where the squares go relative to the sums; TN*32 unless several wavefronts share a row of sums.)
 template <typename T, int TM, int TN, bool OUT_F32, bool STAT = false>
 __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &io, int rep, int mrow0, int ncol0, int lane,
-                                               f16v (&acc)[TM][TN], float *stage, float *wsum = nullptr) {
+                                               f16v (&acc)[TM][TN], float *stage, float *wsum = nullptr,
+                                               int sq_off = TN * 32) {
   typedef unsigned int u2v __attribute__((ext_vector_type(2)));
   constexpr int CW = TN * 32, LD = CW + 4, CPR = CW / 4;
   constexpr int NIT = CPR / 2;                                  // vectors per lane and 32-row strip
@@ -410,7 +412,27 @@ __device__ __forceinline__ void store_tile_lds(const ConvGeom &g, const GemmIO &
 #pragma unroll
       for (int j = 0; j < RPP; ++j) a += *(const f4 *)&stage[j * LD + 4 * lane], b += *(const f4 *)&stage[(RPP + j) * LD + 4 * lane];
       *(f4 *)&wsum[4 * lane] = a;
-      *(f4 *)&wsum[CW + 4 * lane] = b;
+      *(f4 *)&wsum[sq_off + 4 * lane] = b;
+    }
+  }
+}
+
+// Second half of STAT: `wsums` holds, for each of the WAVES_M wavefront rows of a workgroup's tile, BN sums and
+// BN sums of squares ([WAVES_M][2][BN] floats, written by store_tile_lds).  They are added in row order and
+// written as partial row `prow` of io.stat = [replica][S][2][ldc] doubles, channels n0 .. n0 + BN - 1.
+template <int BN, int WAVES_M>
+__device__ __forceinline__ void write_tile_sums(const ConvGeom &g, const GemmIO &io, int rep, int S, int prow, int n0,
+                                                int tid, const float *wsums) {
+  static_assert(2 * BN / 4 <= kThreads, "one thread per vector of sums");
+  __syncthreads();
+  if (tid < 2 * BN / 4) {
+    f4 a = *(const f4 *)&wsums[4 * tid];
+#pragma unroll
+    for (int w = 1; w < WAVES_M; ++w) a += *(const f4 *)&wsums[w * 2 * BN + 4 * tid];
+    const int k = tid >= BN / 4, c = n0 + 4 * (tid - k * (BN / 4));
+    if (c < g.N) {
+      double *dst = io.stat + (((long long)rep * S + prow) * 2 + k) * io.ldc + c;
+      dst[0] = a.x, dst[1] = a.y, dst[2] = a.z, dst[3] = a.w;
     }
   }
 }

@@ -181,7 +181,9 @@ __global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const Ge
 // ---------------------------------------------------------------------------------------------
 constexpr uint32_t kOob = 0x80000000u;  // beyond any per-replica tensor (each is < 2 GiB)
 
-template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32>
+// STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
+// row per row tile.
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32, bool STAT = false>
 __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
   constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
   // operand tiles (double-buffered); the epilogue reuses the same LDS as its staging strips
   constexpr int kPipeBytes = 2 * (BM + BN) * LK * (int)sizeof(T);
-  constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
+  constexpr int kStageBytes = (4 * kStageFloats<TN> + (STAT ? WAVES_M * 2 * BN : 0)) * (int)sizeof(float);
   __shared__ __attribute__((aligned(16))) char smem[kPipeBytes > kStageBytes ? kPipeBytes : kStageBytes];
   T(*As)[BM * LK] = reinterpret_cast<T(*)[BM * LK]>(smem);
   T(*Bs)[BN * LK] = reinterpret_cast<T(*)[BN * LK]>(smem + 2 * BM * LK * sizeof(T));
@@ -309,8 +311,12 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
   }
   if (kt < KT) mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
   __syncthreads();  // operand tiles are dead: their LDS becomes the staging strips
-  store_tile_lds<T, TM, TN, OUT_F32>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc,
-                                     reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
+  // sums of wavefront (wm, wn): row wm of [WAVES_M][2][BN], columns wn * TN * 32 ...
+  float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
+  store_tile_lds<T, TM, TN, OUT_F32, STAT>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc,
+                                           reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>,
+                                           wsums + wm * 2 * BN + wn * TN * 32, BN);
+  if (STAT) write_tile_sums<BN, WAVES_M>(g, io, rep, gridDim.x, blockIdx.x, n0, tid, wsums);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -476,10 +482,15 @@ template <typename T, int WM, int WN, int TM, int TN>
 hipError_t run_u(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   dim3 grid((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, replicas);
-  if (out_f32)
+  constexpr bool kStat = sizeof(T) == 2 && WM == 2 && WN == 2 && TM == 2 && (TN == 2 || TN == 4);  // see igemm_fast_stat_splits
+  if (io.stat) {
+    if (!kStat || out_f32) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_igemm_u<T, WM, WN, TM, TN, false, kStat>), grid, dim3(kThreads), 0, st, g, io);
+  } else if (out_f32) {
     hipLaunchKernelGGL((k_igemm_u<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
-  else
+  } else {
     hipLaunchKernelGGL((k_igemm_u<T, WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+  }
   return hipGetLastError();
 }
 
@@ -520,6 +531,16 @@ bool uniform_ok(int dtype, const ConvGeom &g, const GemmIO &io) {
   const int bk = dtype ? 32 : 16;
   return g.Cc % bk == 0 && g.R * g.S <= 32 && g.N % 4 == 0 && io.ldc % 4 == 0 && io.in_bytes > 0 &&
          io.in_bytes < (1LL << 31) && (long long)g.M * io.ldc * 4 < (1LL << 31) && (long long)g.N * g.K * (dtype ? 2 : 4) < (1LL << 31);
+}
+
+// Partial rows of column sums a launch with io.stat set writes: one per 128 output rows, for the bf16 layers the
+// uniform-tap kernel runs on 128 x 128 or 128 x 256 tiles (more than 96 output channels, not a multiple of 192);
+// 0: none.  Mirrors the choice of launch_igemm_fast below.
+int igemm_fast_stat_splits(int dtype, bool out_f32, const ConvGeom &g, const GemmIO &io) {
+  if (dtype != 1 || out_f32 || !(full_vector_ok(dtype, g, io) && uniform_ok(dtype, g, io))) return 0;
+  const int n = g.N;
+  const bool t22 = n > 96 && n <= 128, t24 = n > 192 && n % 192 != 0;
+  return t22 || t24 ? (g.M + 127) / 128 : 0;
 }
 
 hipError_t launch_igemm_fast(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g_in,

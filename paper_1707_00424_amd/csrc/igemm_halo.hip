@@ -243,20 +243,8 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
   store_tile_lds<T, TM, TN, false, STAT>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
                                          reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>, wsums + wave * 2 * BN);
-  if (STAT) {
-    // the workgroup's 256 rows: the four wavefronts' sums added in wavefront order, one partial row per pixel tile
-    __syncthreads();
-    if (tid < 2 * BN / 4) {
-      f4 a = *(const f4 *)&wsums[4 * tid];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) a += *(const f4 *)&wsums[w * 2 * BN + 4 * tid];
-      const int k = tid >= BN / 4, c = n0 + 4 * (tid - k * (BN / 4));
-      if (c < g.N) {
-        double *dst = io.stat + (((long long)rep * hg.tiles + tile) * 2 + k) * io.ldc + c;
-        dst[0] = a.x, dst[1] = a.y, dst[2] = a.z, dst[3] = a.w;
-      }
-    }
-  }
+  // the workgroup's 256 rows: one partial row per pixel tile
+  if (STAT) write_tile_sums<BN, 4>(g, io, rep, hg.tiles, tile, n0, tid, wsums);
 }
 
 // Workgroups are handed to the eight XCDs in turn, so ids that differ by 8 share an L2: the column blocks

@@ -28,7 +28,9 @@ __device__ __forceinline__ float buffer_load_elem<float>(__amdgpu_buffer_rsrc_t 
   return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
 }
 
-template <typename T, int TN, bool OUT_F32>
+// STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
+// row per workgroup.
+template <typename T, int TN, bool OUT_F32, bool STAT>
 __global__ __launch_bounds__(kThreads) void k_conv_smallk(const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;               // one contraction step of the MFMA helper: 32 bf16 / 16 fp32
@@ -36,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void k_conv_smallk(const ConvGeom g, cons
   constexpr int LK = BK + VW;
   constexpr int TM = 2, BM = 256, BN = TN * 32;
   constexpr int kTileBytes = STEPS * (BM + BN) * LK * (int)sizeof(T);
-  constexpr int kStageBytes = 4 * kStageFloats<TN> * (int)sizeof(float);
+  constexpr int kStageBytes = (4 * kStageFloats<TN> + (STAT ? 4 * 2 * BN : 0)) * (int)sizeof(float);
   __shared__ __attribute__((aligned(16))) char smem[kTileBytes > kStageBytes ? kTileBytes : kStageBytes];
   T *As = reinterpret_cast<T *>(smem);                                   // [STEPS][BM][LK]
   T *Bs = reinterpret_cast<T *>(smem) + STEPS * BM * LK;                 // [STEPS][BN][LK]
@@ -103,8 +105,11 @@ __global__ __launch_bounds__(kThreads) void k_conv_smallk(const ConvGeom g, cons
   for (int st = 0; st < STEPS; ++st)
     mma_tile_t<T, TM, TN, LK, VW>(As + st * BM * LK, Bs + st * BN * LK, wave * TM * 32, 0, lane, acc);
   __syncthreads();  // operand tiles are dead: their LDS becomes the staging strips
-  store_tile_lds<T, TM, TN, OUT_F32>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
-                                     reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
+  float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
+  store_tile_lds<T, TM, TN, OUT_F32, STAT>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
+                                           reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>,
+                                           wsums + wave * 2 * BN);
+  if (STAT) write_tile_sums<BN, 4>(g, io, rep, gridDim.x, blockIdx.x, n0, tid, wsums);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -240,10 +245,14 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
 template <typename T, int TN>
 hipError_t run_smallk(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   dim3 grid((g.M + 255) / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
-  if (out_f32)
-    hipLaunchKernelGGL((k_conv_smallk<T, TN, true>), grid, dim3(kThreads), 0, st, g, io);
-  else
-    hipLaunchKernelGGL((k_conv_smallk<T, TN, false>), grid, dim3(kThreads), 0, st, g, io);
+  if (io.stat) {
+    if (TN > 2 || out_f32) return hipErrorInvalidValue;  // see conv_smallk_stat_splits
+    hipLaunchKernelGGL((k_conv_smallk<T, TN, false, TN <= 2>), grid, dim3(kThreads), 0, st, g, io);
+  } else if (out_f32) {
+    hipLaunchKernelGGL((k_conv_smallk<T, TN, true, false>), grid, dim3(kThreads), 0, st, g, io);
+  } else {
+    hipLaunchKernelGGL((k_conv_smallk<T, TN, false, false>), grid, dim3(kThreads), 0, st, g, io);
+  }
   return hipGetLastError();
 }
 
@@ -256,6 +265,10 @@ bool conv_smallk_applicable(int dtype, const ConvGeom &g, const GemmIO &io) {
   return g.K <= kKP && g.dshift == 0 && (g.sr == 1 || (g.R == 1 && g.S == 1)) && g.plq == 0 && g.N % 4 == 0 && io.ldc % 4 == 0 && g.M >= (dtype ? 64 : 256) &&
          io.in_bytes > 0 && io.in_bytes < (1LL << 31) && (long long)g.M * io.ldc * 4 < (1LL << 31);
 }
+
+// partial rows of column sums a launch with io.stat set writes (one per 256 output pixels); 0: none (the
+// 96-wide epilogue does not take them)
+int conv_smallk_stat_splits(const ConvGeom &g, bool out_f32) { return g.N <= 64 && !out_f32 ? (g.M + 255) / 256 : 0; }
 
 hipError_t launch_conv_smallk(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   const int n = g.N;

@@ -169,7 +169,13 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
     ((3, 128, 32, 32, 64, 64, 3, 1, 1), True),    # WRN-16-4 group 1 at full size: 512 partial rows
     ((3, 128, 8, 8, 256, 256, 3, 1, 1), True),    # WRN-16-4 group 3 at full size
     ((2, 4, 16, 16, 32, 160, 3, 1, 1), False),    # 96-wide blocks: no sums, the caller reduces
-    ((2, 4, 16, 16, 32, 64, 3, 2, 1), False),     # stride 2: another kernel
+    ((2, 4, 16, 16, 32, 64, 3, 2, 1), False),     # stride 2, 64 outputs: a tile shape that takes none
+    ((2, 5, 16, 16, 64, 128, 3, 2, 1), True),     # stride 2 (first convolution of a group): 128-row tiles, 2 x 2 wavefronts
+    ((1, 6, 16, 16, 32, 320, 3, 2, 1), True),     # same, 320 outputs = 256 + a ragged second block
+    ((3, 128, 32, 32, 64, 128, 3, 2, 1), True),   # WRN-16-4 group 2's first convolution at full size
+    ((2, 4, 16, 16, 32, 160, 3, 2, 1), False),    # stride 2, 160 outputs: 96-wide tiles
+    ((2, 9, 16, 16, 3, 16, 3, 1, 1), True),       # the first layer (whole contraction in one tile), a ragged last tile
+    ((3, 128, 32, 32, 3, 16, 3, 1, 1), True),     # WRN's first layer at full size
 ])
 def test_conv_epilogue_column_sums(gpu, case, expect_sums):
     """The sums a convolution leaves for the batch-norm behind it are the column sums of exactly what it stored
@@ -198,14 +204,15 @@ def test_conv_epilogue_column_sums(gpu, case, expect_sums):
             assert S == 0 and bool(torch.isnan(partial).all())
             continue
         M = B * Ho * Wo
-        assert S == (M + 255) // 256
+        span = 256 if S == (M + 255) // 256 else 128      # rows of y per partial row: the kernel's row tile
+        assert S == (M + span - 1) // span
         used = n * S * 2 * Cout          # [n][S][2][Cout], replicas S rows apart
         got = partial[:used].cpu().numpy().reshape(n, S, 2, Cout)
         assert np.isfinite(got).all() and bool(torch.isnan(partial[used:]).all())
         yv = y.double().cpu().numpy().reshape(n, M, Cout)
-        # per partial row: the 256 rows of its pixel tile
-        pad_rows = S * 256 - M
-        yt = np.concatenate([yv, np.zeros((n, pad_rows, Cout))], axis=1).reshape(n, S, 256, Cout)
+        # per partial row: the rows of its tile
+        pad_rows = S * span - M
+        yt = np.concatenate([yv, np.zeros((n, pad_rows, Cout))], axis=1).reshape(n, S, span, Cout)
         ref1, ref2 = yt.sum(axis=2), (yt * yt).sum(axis=2)
         scale1 = np.abs(yt).sum(axis=2) + 1e-30
         assert np.max(np.abs(got[:, :, 0] - ref1) / scale1) < 1e-5   # one element of 256 left out would show as 4e-3
