@@ -392,6 +392,16 @@ parle_status parle_k_bias_grad(void *hip_stream, const parle_act_desc *desc, con
 parle_status parle_k_softmax_xent(void *hip_stream, int32_t dtype, int32_t n, int32_t batch, int32_t classes,
                                   const float *logits, const int32_t *labels, float *loss, void *dlogits);
 
+/* The classifier's last fully connected layer, the loss above and the layer's input gradient as ONE kernel (what a
+ * training step of the networks that end in such a layer runs): feat [n][batch, features], w [n][classes, features]
+ * (activation format), bias [n][classes] fp32 or NULL, 1 <= classes <= 16, (classes + 8) * features <= 16384.
+ *   logits = feat w^T + bias;  dlogits [n][batch, classes] = (softmax - onehot) / batch, stored in the activation
+ *   format;  dfeat [n][batch, features] = dlogits (as stored) x w, zero where relu_mask != 0 and feat <= 0.
+ * loss_img [n][batch] fp32 receives the per-image cross-entropies, loss [n] (may be NULL) their means. */
+parle_status parle_k_fc_head(void *hip_stream, int32_t dtype, int32_t n, int32_t batch, int32_t features,
+                             int32_t classes, const void *feat, const void *w, const float *bias, const int32_t *labels,
+                             int32_t relu_mask, float *loss_img, float *loss, void *dlogits, void *dfeat);
+
 #ifdef __cplusplus
 }
 #endif

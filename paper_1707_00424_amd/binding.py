@@ -106,6 +106,8 @@ _SIGNATURES = {
     "parle_k_bias_grad": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p],
     "parle_k_softmax_xent": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p],
+    "parle_k_fc_head": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                        C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
 }
 EXPORTS = sorted(list(_SIGNATURES) + ["parle_last_error", "parle_destroy", "parle_k_conv_scratch_bytes",
                                          "parle_k_layer_scratch_bytes"])
@@ -305,6 +307,14 @@ def parle_k_softmax_xent(dtype, logits, labels, loss, dlogits, stream=None):
     n, batch, classes = logits.shape
     _check(lib().parle_k_softmax_xent(_stream_handle(stream), int(dtype), n, batch, classes, _ptr(logits), _ptr(labels),
                                       _ptr(loss), _ptr(dlogits)))
+
+
+def parle_k_fc_head(dtype, feat, w, bias, labels, relu_mask, loss_img, loss, dlogits, dfeat, stream=None):
+    n, batch, features = feat.shape
+    classes = w.shape[1]
+    _check(lib().parle_k_fc_head(_stream_handle(stream), int(dtype), n, batch, features, classes, _ptr(feat), _ptr(w),
+                                 _ptr(bias), _ptr(labels), int(relu_mask), _ptr(loss_img), _ptr(loss), _ptr(dlogits),
+                                 _ptr(dfeat)))
 
 
 class Parle:

@@ -116,4 +116,19 @@ parle_status parle_k_softmax_xent(void *hip_stream, int32_t dtype, int32_t n, in
                                         labels, loss, dlogits, (long long)batch * classes));
 }
 
+parle_status parle_k_fc_head(void *hip_stream, int32_t dtype, int32_t n, int32_t batch, int32_t features,
+                             int32_t classes, const void *feat, const void *w, const float *bias, const int32_t *labels,
+                             int32_t relu_mask, float *loss_img, float *loss, void *dlogits, void *dfeat) {
+  if ((dtype | 1) != 1 || n < 1 || n > 65535 || batch < 1 || !fc_head_applicable(classes, features) || !feat || !w ||
+      !labels || !loss_img || !dlogits || !dfeat)
+    return PARLE_EINVAL;
+  if ((long long)batch * features >= (1LL << 31)) return PARLE_ESIZE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const hipError_t e = launch_fc_head(st, dtype, n, batch, features, classes, feat, (long long)batch * features, w,
+                                      (long long)classes * features, bias, classes, labels, loss_img, dlogits,
+                                      (long long)batch * classes, dfeat, (long long)batch * features, relu_mask != 0);
+  if (e != hipSuccess) return done(e);
+  return loss ? done(launch_loss_mean(st, n, batch, loss_img, loss)) : PARLE_OK;
+}
+
 }  // extern "C"

@@ -51,6 +51,9 @@ struct Op {
   int64_t saved_off = -1, sums_off = -1, run_off = 0;  // run_off in floats inside a replica's BN row
   int bn_add = -1;         // tensor whose gradient is added to this op's input gradient
   int stat_src = -1;       // the convolution that writes this op's input, if its epilogue can take the column sums
+  // conv / fc: the classifier's last layer.  In training its forward pass, the loss and its input gradient run as
+  // one kernel (launch_fc_head) in place of three on the chain; its weight and bias gradients stay as they are.
+  bool head = false;
   // dropout
   int site = 0;            // index of the dropout site in execution order (part of the mask's key)
   bool drop_relu = false;  // the input is a ReLU output whose backward mask this op applies
@@ -108,6 +111,8 @@ struct Net {
   }
   int64_t bn_floats = 0;
   int max_bn_c = 0;
+  int head_op = -1;          // index of the op with `head` set, -1 = the network ends otherwise
+  int64_t off_loss_img = 0;  // [n][B] per-image losses
   std::vector<TransposeTable> transposes;  // weights that backward-data reads transposed, in launch-sized groups
 
   int64_t alloc(int64_t bytes) {
@@ -296,6 +301,22 @@ bool build_plan(Net &N, std::string &err) {
       err = "model has no network";
       return false;
   }
+  {
+    static const bool fused_head = [] {
+      const char *e = getenv("PARLE_FUSED_HEAD");
+      return !(e && atoi(e) == 0);
+    }();
+    Op &last = N.ops.back();
+    if (fused_head && last.type == OP_CONV && last.out == N.t_logits && N.tensors[last.out].f32 && last.R == 1 &&
+        last.Hin == 1 && last.Win == 1 && last.stride == 1 && last.pad == 0 && last.need_dx && last.resid < 0 &&
+        !last.relu && fc_head_applicable(last.Cout, last.Cin) && last.Cin <= 256) {
+      // up to 256 features: MLP (128) -12 %, WRN-16-4 (256) -1.1 % per step; beyond, the one kernel was no gain over
+      // the three it replaces (LeNet, 500 features: +1.9 %; WRN-28-10, 640: +0.9 %)
+      last.head = true;
+      N.head_op = (int)N.ops.size() - 1;
+    }
+    N.off_loss_img = N.alloc((int64_t)N.n * N.B * 4);
+  }
   // a batch-norm whose input a convolution of the chain writes can get its column sums from that convolution
   for (size_t i = 0; i < N.ops.size(); ++i) {
     if (N.ops[i].type != OP_BNRELU) continue;
@@ -398,6 +419,7 @@ struct Run {
   char *ws;
   const float *images;
   const long long *step_dev;  // inner-step counter (dropout key); NULL outside training
+  float *loss_out = nullptr;  // [n] mean losses of this step, or NULL (training with the fused classifier head)
   void *tptr(int t) const {
     const Tensor &T = N->tensors[t];
     return T.external ? (void *)images : (void *)(ws + T.off);
@@ -464,6 +486,7 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
     const Op &op = N.ops[oi];
     switch (op.type) {
       case OP_CONV: {
+        if (train && op.head) break;  // runs with the loss (net_train_step)
         const ConvGeom g = fwd_geom(op, r.B);
         if (branches && op.branch) {
           HIP_TRY(launch_pending());
@@ -574,7 +597,7 @@ hipError_t backward(const Run &r, float *grad) {
         // The input gradient is enqueued before the leaves.  The order matters when the step is recorded into a
         // graph: the runtime keeps the first successor of a node on the node's own queue, and a chain that
         // lands behind a branch of leaves waits for them although nothing ties the two.
-        if (op.need_dx && !op.branch) {
+        if (op.need_dx && !op.branch && !op.head) {
           if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
           void *wt = r.ws + op.wt_off;  // transposed once per step, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
@@ -599,6 +622,7 @@ hipError_t backward(const Run &r, float *grad) {
           }
         }
         if (fork) HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
+
         // the block's shortcut shares this op's output gradient: its input gradient goes first on the second
         // stream (the block's first convolution waits for it), ahead of the weight gradients
         if (op.join >= 0) {
@@ -635,6 +659,9 @@ hipError_t backward(const Run &r, float *grad) {
             HIP_TRY(launch_reduce_partials(lst, r.n, S, wsize, io.out, grad + N.segs[op.wseg].offset, r.p_rs));
           }
         }
+        // the mean of the per-image losses is nobody's input: it is taken where the leaves run, after them
+        if (op.head && r.loss_out)
+          HIP_TRY(launch_loss_mean(lst, r.n, r.B, (const float *)(r.ws + N.off_loss_img), r.loss_out));
         break;
       }
       case OP_POOL: {
@@ -777,8 +804,17 @@ hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const v
     HIP_TRY(hipEventRecord(N.wt_ready, N.side));
   }
   const Tensor &tl = N.tensors[N.t_logits];
-  HIP_TRY(launch_softmax_xent_train(st, N.dtype, N.n, N.B, tl.C, (const float *)r.tptr(N.t_logits), r.trs(N.t_logits),
-                                    labels, loss_dev, r.gptr(N.t_logits), r.trs(N.t_logits)));
+  if (N.head_op >= 0) {
+    const Op &op = N.ops[N.head_op];
+    float *loss_img = (float *)(r.ws + N.off_loss_img);
+    HIP_TRY(launch_fc_head(st, N.dtype, N.n, N.B, op.Cin, op.Cout, r.tptr(op.in), r.trs(op.in), r.wptr(op.wseg), r.p_rs,
+                           op.bseg >= 0 ? r.fptr(op.bseg) : nullptr, r.p_rs, labels, loss_img, r.gptr(N.t_logits),
+                           r.trs(N.t_logits), r.gptr(op.in), r.trs(op.in), op.mask_in));
+    r.loss_out = loss_dev;  // averaged beside the chain, see backward()
+  } else {
+    HIP_TRY(launch_softmax_xent_train(st, N.dtype, N.n, N.B, tl.C, (const float *)r.tptr(N.t_logits),
+                                      r.trs(N.t_logits), labels, loss_dev, r.gptr(N.t_logits), r.trs(N.t_logits)));
+  }
   return backward(r, grad);
 }
 

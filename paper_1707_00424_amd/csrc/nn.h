@@ -10,6 +10,15 @@ hipError_t launch_softmax_xent_train(hipStream_t st, int dtype, int n, int B, in
                                      long long logits_rs, const int32_t *labels, float *loss_out, void *dlogits,
                                      long long dl_rs);
 // eval: one parameter set, `count` samples: loss_sum[0] = sum of losses, n_err[0] = #(argmax != label).
+// The classifier's last fully connected layer, the mean cross-entropy and the layer's input gradient in one
+// launch (training).  feat [n][B][D], w [n][C][D] (activation dtype), bias [n][C] fp32 or NULL, C <= 16 and (C + 8) * D <= 16384.
+// Writes dlogits [n][B][C] = (softmax - onehot)/B and dfeat [n][B][D] = dlogits x W (zero where `mask` and
+// feat <= 0) in the activation dtype, and the per-image losses loss_img [n][B]; launch_loss_mean averages them.
+bool fc_head_applicable(int classes, int features);
+hipError_t launch_fc_head(hipStream_t st, int dtype, int n, int B, int D, int C, const void *feat, long long feat_rs,
+                          const void *w, long long w_rs, const float *bias, long long bias_rs, const int32_t *labels,
+                          float *loss_img, void *dlogits, long long dl_rs, void *dfeat, long long dfeat_rs, bool mask);
+hipError_t launch_loss_mean(hipStream_t st, int n, int B, const float *loss_img, float *loss_out);
 hipError_t launch_softmax_xent_eval(hipStream_t st, int count, int C, const float *logits, const int32_t *labels,
                                     float *loss_sum, int32_t *n_err);
 

@@ -74,6 +74,131 @@ __global__ __launch_bounds__(kThreads) void k_softmax_train(int B, int C, const 
   }
 }
 
+// ------------------------------------------------------------------ classifier head
+// The last fully connected layer, the loss and that layer's input gradient in one launch: three dependent
+// launches on the critical chain become one (a step of the small networks is a chain of launches of a few
+// microseconds each).  One wavefront per image: lanes stride over the D features, the C <= kHeadClasses logits
+// are wavefront sums (xor tree: every lane ends up with all of them), softmax and cross-entropy in registers with
+// the formulas of k_softmax_train, dlogits rounded to the activation type as stored, then
+//   dfeat[d] = sum_c dlogits[c] * W[c][d]   (zero where MASK and feat[d] <= 0: the ReLU in front of the layer).
+// The per-image losses go to loss_img; k_loss_mean averages them (off the chain).
+constexpr int kHeadClasses = 16;
+constexpr int kHeadThreads = 512;  // eight wavefronts = eight images share one copy of the weights in LDS
+
+template <typename T>
+__device__ __forceinline__ float as_stored(float v);  // v after a round trip through the activation type
+template <>
+__device__ __forceinline__ float as_stored<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float as_stored<bf16_t>(float v) {
+  return bf16_to_f32(f32_to_bf16(v));
+}
+
+__device__ __forceinline__ float wave_allsum(float v) {
+#pragma unroll
+  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, PARLE_WAVE);
+  return v;
+}
+
+template <typename T, bool MASK>
+__global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, const T *__restrict__ feat, long long feat_rs,
+                                                      const T *__restrict__ w, long long w_rs,
+                                                      const float *__restrict__ bias, long long bias_rs,
+                                                      const int32_t *__restrict__ labels, float *__restrict__ loss_img,
+                                                      T *__restrict__ dl, long long dl_rs, T *__restrict__ dfeat,
+                                                      long long dfeat_rs) {
+  // the weights (shared by the workgroup's eight images) and the eight feature rows, as fp32, in LDS: both loops over
+  // the features then run at LDS latency, and the weights are fetched once per workgroup
+  extern __shared__ float head_lds[];
+  constexpr int kWaves = kHeadThreads / PARLE_WAVE;
+  float *Ws = head_lds;                 // [C][D]
+  float *Fs = head_lds + (size_t)C * D;  // [kWaves][D]
+  const int rep = blockIdx.y, lane = threadIdx.x & (PARLE_WAVE - 1), wave = threadIdx.x / PARLE_WAVE;
+  const int b0 = blockIdx.x * kWaves, b = b0 + wave;
+  const T *wp = w + rep * w_rs;
+  // sixteen loads in flight per thread: a loop that stores each value before it asks for the next would pay one
+  // round trip to L2 per element
+  auto stage = [&](float *dst, const T *src, int count) {
+    constexpr int U = 16;
+    for (int base = threadIdx.x; base < count; base += U * kHeadThreads) {
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = base + u * kHeadThreads < count ? ldf<T>(src, base + u * kHeadThreads) : 0.f;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (base + u * kHeadThreads < count) dst[base + u * kHeadThreads] = v[u];
+    }
+  };
+  stage(Ws, wp, C * D);
+  stage(Fs, feat + rep * feat_rs + (long long)b0 * D, min(kWaves, B - b0) * D);
+  __syncthreads();
+  if (b >= B) return;  // whole wavefronts leave; no barrier follows
+  const float *fs = Fs + wave * D;
+  float lg[kHeadClasses];
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c) lg[c] = 0.f;
+  for (int d = lane; d < D; d += PARLE_WAVE) {
+    const float fv = fs[d];
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < C) lg[c] += fv * Ws[c * D + d];
+  }
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c)
+    if (c < C) lg[c] = wave_allsum(lg[c]) + (bias ? bias[rep * bias_rs + c] : 0.f);
+  float mx = lg[0];
+#pragma unroll
+  for (int c = 1; c < kHeadClasses; ++c)
+    if (c < C) mx = fmaxf(mx, lg[c]);
+  float se = 0.f;
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c)
+    if (c < C) se += expf(lg[c] - mx);
+  const float lse = logf(se) + mx;
+  const int y = labels[(long long)rep * B + b];
+  const float invB = 1.0f / (float)B;
+  float ly = 0.f, mine = 0.f;
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c) {
+    if (c < C) {
+      if (c == y) ly = lg[c];
+      const float p = expf(lg[c] - lse);
+      // the gradient as the weight- and bias-gradient kernels will read it: rounded to the stored type
+      lg[c] = as_stored<T>((p - (c == y ? 1.f : 0.f)) * invB);
+      if (c == lane) mine = lg[c];
+    }
+  }
+  if (lane < C) stf<T>(dl + rep * dl_rs, (long long)b * C + lane, mine);
+  if (lane == 0) loss_img[(long long)rep * B + b] = lse - ly;
+  T *df = dfeat + rep * dfeat_rs + (long long)b * D;
+  for (int d = lane; d < D; d += PARLE_WAVE) {
+    float a = 0.f;
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < C) a += lg[c] * Ws[c * D + d];
+    if (MASK && !(fs[d] > 0.f)) a = 0.f;
+    stf<T>(df, d, a);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_loss_mean(int B, const float *__restrict__ loss_img,
+                                                        float *__restrict__ loss_out) {
+  __shared__ float red[kThreads / PARLE_WAVE];
+  const int rep = blockIdx.x;
+  float s = 0.f;
+  for (int b = threadIdx.x; b < B; b += kThreads) s += loss_img[(long long)rep * B + b];
+  s = wave_sum(s);
+  if ((threadIdx.x & (PARLE_WAVE - 1)) == 0) red[threadIdx.x / PARLE_WAVE] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kThreads / PARLE_WAVE; ++w) t += red[w];
+    loss_out[rep] = t / (float)B;
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void k_softmax_eval(int count, int C, const float *__restrict__ logits,
                                                            const int32_t *__restrict__ labels,
                                                            float *__restrict__ loss_sum, int32_t *__restrict__ n_err) {
@@ -910,6 +1035,35 @@ hipError_t launch_softmax_xent_train(hipStream_t st, int dtype, int n, int B, in
                                 loss_out, (float *)dlogits, dl_rs),
              hipLaunchKernelGGL(k_softmax_train<bf16_t>, dim3(n), dim3(kThreads), 0, st, B, C, logits, logits_rs,
                                 labels, loss_out, (bf16_t *)dlogits, dl_rs));
+  return hipGetLastError();
+}
+
+// at most 16 classes (registers), weights and eight feature rows within 64 KB of LDS
+bool fc_head_applicable(int classes, int features) {
+  return classes >= 1 && classes <= kHeadClasses && features >= 1 &&
+         ((long long)classes + kHeadThreads / PARLE_WAVE) * features * 4 <= 65536;
+}
+
+hipError_t launch_fc_head(hipStream_t st, int dtype, int n, int B, int D, int C, const void *feat, long long feat_rs,
+                          const void *w, long long w_rs, const float *bias, long long bias_rs, const int32_t *labels,
+                          float *loss_img, void *dlogits, long long dl_rs, void *dfeat, long long dfeat_rs, bool mask) {
+  if (!fc_head_applicable(C, D) || B < 1) return hipErrorInvalidValue;
+  const dim3 grid((B + kHeadThreads / PARLE_WAVE - 1) / (kHeadThreads / PARLE_WAVE), n);
+  const size_t lds = (size_t)(C + kHeadThreads / PARLE_WAVE) * D * sizeof(float);
+#define HEAD(T, MASK)                                                                                                  \
+  hipLaunchKernelGGL((k_fc_head<T, MASK>), grid, dim3(kHeadThreads), lds, st, B, D, C, (const T *)feat, feat_rs, (const T *)w, \
+                     w_rs, bias, bias_rs, labels, loss_img, (T *)dlogits, dl_rs, (T *)dfeat, dfeat_rs)
+  if (dtype == 0) {
+    if (mask) HEAD(float, true); else HEAD(float, false);
+  } else {
+    if (mask) HEAD(bf16_t, true); else HEAD(bf16_t, false);
+  }
+#undef HEAD
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_mean(hipStream_t st, int n, int B, const float *loss_img, float *loss_out) {
+  hipLaunchKernelGGL(k_loss_mean, dim3(n), dim3(kThreads), 0, st, B, loss_img, loss_out);
   return hipGetLastError();
 }
 

@@ -252,3 +252,46 @@ def test_softmax_cross_entropy(gpu, n, B, C, dtype):
         t.backward()
         assert abs(loss[r].item() - ref) <= 1e-5 * abs(ref) + 1e-6
         near("dlogits", down(dl[r]), lv.g, dtype)
+
+
+@pytest.mark.parametrize("n,B,D,C,mask", [(1, 1, 3, 2, 0), (3, 128, 128, 10, 1), (6, 128, 500, 10, 1), (3, 128, 256, 10, 0),
+                                          (2, 37, 70, 7, 1), (3, 128, 640, 10, 0), (2, 5, 64, 16, 1)])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_classifier_head(gpu, n, B, D, C, mask, dtype):
+    """Last fully connected layer + loss + its input gradient in one kernel, against the oracle's three steps."""
+    torch, pb = gpu
+    rng = np.random.default_rng(7 * n + 13 * B + D + C + mask)
+    q = (lambda a: up(torch, a, 1).float().cpu().numpy()) if dtype else (lambda a: np.asarray(a, np.float32))
+    feat = q(rng.standard_normal((n, B, D)))
+    if mask:
+        feat = np.maximum(feat, 0)          # the output of a ReLU
+    w = q(rng.standard_normal((n, C, D)) / np.sqrt(D) * 2)
+    bias = rng.standard_normal((n, C)).astype(np.float32)
+    labels = rng.integers(0, C, (n, B)).astype(np.int32)
+    tdt = torch.bfloat16 if dtype else torch.float32
+    loss_img = torch.zeros((n, B), dtype=torch.float32, device="cuda")
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dl = torch.zeros((n, B, C), dtype=tdt, device="cuda")
+    df = torch.full((n, B, D), 7.0, dtype=tdt, device="cuda")
+    pb.parle_k_fc_head(dtype, up(torch, feat, dtype), up(torch, w, dtype), torch.as_tensor(bias).cuda(),
+                       torch.as_tensor(labels).cuda(), mask, loss_img, loss, dl, df)
+    torch.cuda.synchronize()
+    for r in range(n):
+        t = onets.Tape()
+        pre = onets.Var(feat[r].astype(np.float64))
+        fv = onets.relu(t, pre) if mask else pre    # feat >= 0 already: relu is the identity forward, the mask backward
+        wv, bv = onets.Var(w[r].astype(np.float64)), onets.Var(bias[r].astype(np.float64))
+        lv = onets.linear(t, fv, wv, bv)
+        ref, _ = onets.softmax_xent(t, lv, labels[r])
+        t.backward()
+        assert abs(loss[r].item() - ref) <= 1e-5 * abs(ref) + 1e-6
+        assert abs(loss_img[r].double().mean().item() - ref) <= 1e-5 * abs(ref) + 1e-6
+        near("dlogits", down(dl[r]), lv.g, dtype)
+        # the input gradient from the dlogits as stored (the weight gradient reads the same values)
+        t2 = onets.Tape()
+        pre2 = onets.Var(feat[r].astype(np.float64))
+        fv2 = onets.relu(t2, pre2) if mask else pre2
+        lv2 = onets.linear(t2, fv2, wv, bv)
+        lv2.g = down(dl[r])
+        t2.backward()
+        near("dfeat", down(df[r]), pre2.g, dtype)
