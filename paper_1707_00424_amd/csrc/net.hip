@@ -340,7 +340,7 @@ bool build_plan(Net &N, std::string &err) {
       const int64_t wsize = (int64_t)op.Cout * op.R * op.R * op.Cin;
       if (op.need_dx) {
         N.want_grad(op.in);
-        op.wt_off = N.alloc((int64_t)N.n * wsize * N.esize);
+        if (!op.head) op.wt_off = N.alloc((int64_t)N.n * wsize * N.esize);  // the head kernel reads the weights as they lie
         // few input channels under a wide window (LeNet's second convolution: 20 channels, 25 taps): as a
         // direct implicit GEMM the pass has 20 output columns on 32-wide fp32 MFMA tiles and a contraction
         // of 1250; as dy x W (500 columns, contraction 50) plus a gather over the window it is a fraction
@@ -375,7 +375,7 @@ bool build_plan(Net &N, std::string &err) {
   for (int vec = 1; vec >= 0; --vec) {
     bool open = false;
     for (const Op &op : N.ops) {
-      if (op.type != OP_CONV || !op.need_dx) continue;
+      if (op.type != OP_CONV || !op.need_dx || op.head) continue;
       if ((int)transpose_vector_ok(N.dtype, op.Cout, op.Cin, N.segs[op.wseg].offset) != vec) continue;
       if (!open || N.transposes.back().count == TransposeTable::kMax) {
         N.transposes.emplace_back();
