@@ -402,6 +402,12 @@ parle_status parle_k_fc_head(void *hip_stream, int32_t dtype, int32_t n, int32_t
                              int32_t classes, const void *feat, const void *w, const float *bias, const int32_t *labels,
                              int32_t relu_mask, float *loss_img, float *loss, void *dlogits, void *dfeat);
 
+/* The same for a network that ends in a global average pool over class maps (All-CNN-C): feat [n][batch, h, w, c]
+ * with c <= 16 classes; logits = mean over the h*w pixels; dlogits [n][batch, c] as above;
+ * dfeat [n][batch, h, w, c] = dlogits / (h*w) at every pixel; loss_img, loss as above. */
+parle_status parle_k_gap_head(void *hip_stream, const parle_act_desc *desc, const void *feat, const int32_t *labels,
+                              float *loss_img, float *loss, void *dlogits, void *dfeat);
+
 #ifdef __cplusplus
 }
 #endif

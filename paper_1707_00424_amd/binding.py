@@ -106,6 +106,8 @@ _SIGNATURES = {
     "parle_k_bias_grad": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p],
     "parle_k_softmax_xent": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p],
+    "parle_k_gap_head": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                         C.c_void_p, C.c_void_p],
     "parle_k_fc_head": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                         C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
 }
@@ -315,6 +317,11 @@ def parle_k_fc_head(dtype, feat, w, bias, labels, relu_mask, loss_img, loss, dlo
     _check(lib().parle_k_fc_head(_stream_handle(stream), int(dtype), n, batch, features, classes, _ptr(feat), _ptr(w),
                                  _ptr(bias), _ptr(labels), int(relu_mask), _ptr(loss_img), _ptr(loss), _ptr(dlogits),
                                  _ptr(dfeat)))
+
+
+def parle_k_gap_head(desc, feat, labels, loss_img, loss, dlogits, dfeat, stream=None):
+    _check(lib().parle_k_gap_head(_stream_handle(stream), C.byref(desc), _ptr(feat), _ptr(labels), _ptr(loss_img),
+                                  _ptr(loss), _ptr(dlogits), _ptr(dfeat)))
 
 
 class Parle:

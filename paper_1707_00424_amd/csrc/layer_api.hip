@@ -131,4 +131,15 @@ parle_status parle_k_fc_head(void *hip_stream, int32_t dtype, int32_t n, int32_t
   return loss ? done(launch_loss_mean(st, n, batch, loss_img, loss)) : PARLE_OK;
 }
 
+parle_status parle_k_gap_head(void *hip_stream, const parle_act_desc *desc, const void *feat, const int32_t *labels,
+                              float *loss_img, float *loss, void *dlogits, void *dfeat) {
+  if (parle_status s = check_act(desc)) return s;
+  if (!feat || !labels || !loss_img || !dlogits || !dfeat || desc->c > 16) return PARLE_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const hipError_t e = launch_gap_head(st, desc->dtype, desc->n, desc->batch, desc->h * desc->w, desc->c, feat, elems(desc),
+                                       labels, loss_img, dlogits, (long long)desc->batch * desc->c, dfeat, elems(desc));
+  if (e != hipSuccess) return done(e);
+  return loss ? done(launch_loss_mean(st, desc->n, desc->batch, loss_img, loss)) : PARLE_OK;
+}
+
 }  // extern "C"

@@ -315,6 +315,12 @@ bool build_plan(Net &N, std::string &err) {
       last.head = true;
       N.head_op = (int)N.ops.size() - 1;
     }
+    // ... or a global average pool over class maps: pooling, loss and the pooling's backward pass in one kernel
+    if (fused_head && last.type == OP_GAP && last.out == N.t_logits && N.tensors[last.out].f32 &&
+        N.tensors[last.in].C <= 16) {
+      last.head = true;
+      N.head_op = (int)N.ops.size() - 1;
+    }
     N.off_loss_img = N.alloc((int64_t)N.n * N.B * 4);
   }
   // a batch-norm whose input a convolution of the chain writes can get its column sums from that convolution
@@ -512,6 +518,7 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
         break;
       }
       case OP_GAP: {
+        if (train && op.head) break;  // runs with the loss (net_train_step)
         const Tensor &ti = N.tensors[op.in];
         HIP_TRY(launch_gap_fwd(r.st, N.dtype, N.tensors[op.out].f32, r.n, r.B, ti.H * ti.W, ti.C, r.tptr(op.in),
                                r.trs(op.in), r.tptr(op.out), r.trs(op.out)));
@@ -671,6 +678,20 @@ hipError_t backward(const Run &r, float *grad) {
         break;
       }
       case OP_GAP: {
+        if (op.head) {
+          // the head kernel has written this op's input gradient; the mean of its per-image losses is taken beside
+          // the chain
+          if (r.loss_out) {
+            hipStream_t ls = r.st;
+            if (N.side) {
+              HIP_TRY(hipEventRecord(N.dy_ready[oi], r.st));
+              HIP_TRY(hipStreamWaitEvent(N.side, N.dy_ready[oi], 0));
+              ls = N.side;
+            }
+            HIP_TRY(launch_loss_mean(ls, r.n, r.B, (const float *)(r.ws + N.off_loss_img), r.loss_out));
+          }
+          break;
+        }
         const Tensor &ti = N.tensors[op.in];
         HIP_TRY(launch_gap_bwd(r.st, N.dtype, r.n, r.B, ti.H * ti.W, ti.C, r.gptr(op.out), r.trs(op.out), r.gptr(op.in),
                                r.trs(op.in)));
@@ -804,7 +825,14 @@ hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const v
     HIP_TRY(hipEventRecord(N.wt_ready, N.side));
   }
   const Tensor &tl = N.tensors[N.t_logits];
-  if (N.head_op >= 0) {
+  if (N.head_op >= 0 && N.ops[N.head_op].type == OP_GAP) {
+    const Op &op = N.ops[N.head_op];
+    const Tensor &ti = N.tensors[op.in];
+    HIP_TRY(launch_gap_head(st, N.dtype, N.n, N.B, ti.H * ti.W, ti.C, r.tptr(op.in), r.trs(op.in), labels,
+                            (float *)(r.ws + N.off_loss_img), r.gptr(N.t_logits), r.trs(N.t_logits), r.gptr(op.in),
+                            r.trs(op.in)));
+    r.loss_out = loss_dev;
+  } else if (N.head_op >= 0) {
     const Op &op = N.ops[N.head_op];
     float *loss_img = (float *)(r.ws + N.off_loss_img);
     HIP_TRY(launch_fc_head(st, N.dtype, N.n, N.B, op.Cin, op.Cout, r.tptr(op.in), r.trs(op.in), r.wptr(op.wseg), r.p_rs,

@@ -18,6 +18,11 @@ bool fc_head_applicable(int classes, int features);
 hipError_t launch_fc_head(hipStream_t st, int dtype, int n, int B, int D, int C, const void *feat, long long feat_rs,
                           const void *w, long long w_rs, const float *bias, long long bias_rs, const int32_t *labels,
                           float *loss_img, void *dlogits, long long dl_rs, void *dfeat, long long dfeat_rs, bool mask);
+// A network that ends in a global average pool over C <= 16 class maps: pooling, loss and the pooling's backward
+// pass in one launch.  feat [n][B][HW][C]; writes dlogits [n][B][C], dfeat [n][B][HW][C] = dlogits / HW, loss_img.
+hipError_t launch_gap_head(hipStream_t st, int dtype, int n, int B, int HW, int C, const void *feat, long long feat_rs,
+                           const int32_t *labels, float *loss_img, void *dlogits, long long dl_rs, void *dfeat,
+                           long long dfeat_rs);
 hipError_t launch_loss_mean(hipStream_t st, int n, int B, const float *loss_img, float *loss_out);
 hipError_t launch_softmax_xent_eval(hipStream_t st, int count, int C, const float *logits, const int32_t *labels,
                                     float *loss_sum, int32_t *n_err);

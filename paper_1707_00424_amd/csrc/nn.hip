@@ -183,6 +183,62 @@ __global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, c
   }
 }
 
+// The same for a network that ends in a global average pool over class maps (All-CNN-C): logits = mean over the
+// HW pixels of feat [B][HW][C], the loss, and dfeat[p][c] = dlogits[c] / HW for every pixel - pooling, loss and the
+// pooling's backward pass in one launch.  One wavefront per image, lanes stride over the pixels.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_gap_head(int B, int HW, int C, const T *__restrict__ feat,
+                                                       long long feat_rs, const int32_t *__restrict__ labels,
+                                                       float *__restrict__ loss_img, T *__restrict__ dl, long long dl_rs,
+                                                       T *__restrict__ dfeat, long long dfeat_rs) {
+  const int rep = blockIdx.y, lane = threadIdx.x & (PARLE_WAVE - 1);
+  const int b = blockIdx.x * (kThreads / PARLE_WAVE) + threadIdx.x / PARLE_WAVE;
+  if (b >= B) return;  // whole wavefronts leave; the kernel has no barrier
+  const T *f = feat + rep * feat_rs + (long long)b * HW * C;
+  float lg[kHeadClasses];
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c) lg[c] = 0.f;
+  for (int p = lane; p < HW; p += PARLE_WAVE) {
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < C) lg[c] += ldf<T>(f, (long long)p * C + c);
+  }
+  const float inv = 1.0f / (float)HW;
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c)
+    if (c < C) lg[c] = wave_allsum(lg[c]) * inv;
+  float mx = lg[0];
+#pragma unroll
+  for (int c = 1; c < kHeadClasses; ++c)
+    if (c < C) mx = fmaxf(mx, lg[c]);
+  float se = 0.f;
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c)
+    if (c < C) se += expf(lg[c] - mx);
+  const float lse = logf(se) + mx;
+  const int y = labels[(long long)rep * B + b];
+  const float invB = 1.0f / (float)B;
+  float ly = 0.f, mine = 0.f;
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c) {
+    if (c < C) {
+      if (c == y) ly = lg[c];
+      const float p = expf(lg[c] - lse);
+      lg[c] = as_stored<T>((p - (c == y ? 1.f : 0.f)) * invB);  // dlogits as stored
+      if (c == lane) mine = lg[c];
+      lg[c] *= inv;                                              // the share of one pixel
+    }
+  }
+  if (lane < C) stf<T>(dl + rep * dl_rs, (long long)b * C + lane, mine);
+  if (lane == 0) loss_img[(long long)rep * B + b] = lse - ly;
+  T *df = dfeat + rep * dfeat_rs + (long long)b * HW * C;
+  for (int p = lane; p < HW; p += PARLE_WAVE) {
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < C) stf<T>(df, (long long)p * C + c, lg[c]);
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void k_loss_mean(int B, const float *__restrict__ loss_img,
                                                         float *__restrict__ loss_out) {
   __shared__ float red[kThreads / PARLE_WAVE];
@@ -1059,6 +1115,19 @@ hipError_t launch_fc_head(hipStream_t st, int dtype, int n, int B, int D, int C,
     if (mask) HEAD(bf16_t, true); else HEAD(bf16_t, false);
   }
 #undef HEAD
+  return hipGetLastError();
+}
+
+hipError_t launch_gap_head(hipStream_t st, int dtype, int n, int B, int HW, int C, const void *feat, long long feat_rs,
+                           const int32_t *labels, float *loss_img, void *dlogits, long long dl_rs, void *dfeat,
+                           long long dfeat_rs) {
+  if (C < 1 || C > kHeadClasses || B < 1 || HW < 1) return hipErrorInvalidValue;
+  const dim3 grid((B + kThreads / PARLE_WAVE - 1) / (kThreads / PARLE_WAVE), n);
+  DISPATCH_T(dtype,
+             hipLaunchKernelGGL(k_gap_head<float>, grid, dim3(kThreads), 0, st, B, HW, C, (const float *)feat, feat_rs,
+                                labels, loss_img, (float *)dlogits, dl_rs, (float *)dfeat, dfeat_rs),
+             hipLaunchKernelGGL(k_gap_head<bf16_t>, grid, dim3(kThreads), 0, st, B, HW, C, (const bf16_t *)feat, feat_rs,
+                                labels, loss_img, (bf16_t *)dlogits, dl_rs, (bf16_t *)dfeat, dfeat_rs));
   return hipGetLastError();
 }
 

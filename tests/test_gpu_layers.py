@@ -295,3 +295,37 @@ def test_classifier_head(gpu, n, B, D, C, mask, dtype):
         lv2.g = down(dl[r])
         t2.backward()
         near("dfeat", down(df[r]), pre2.g, dtype)
+
+
+@pytest.mark.parametrize("n,B,H,W,C", [(1, 1, 1, 1, 2), (3, 128, 8, 8, 10), (2, 9, 5, 3, 7), (2, 6, 12, 11, 16)])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_pooling_head(gpu, n, B, H, W, C, dtype):
+    """Global average pool over class maps + loss + the pool's backward pass in one kernel, against the oracle's steps."""
+    torch, pb = gpu
+    rng = np.random.default_rng(3 * n + 5 * B + H * W + C)
+    q = (lambda a: up(torch, a, 1).float().cpu().numpy()) if dtype else (lambda a: np.asarray(a, np.float32))
+    feat = q(rng.standard_normal((n, B, H, W, C)) * 3)
+    labels = rng.integers(0, C, (n, B)).astype(np.int32)
+    tdt = torch.bfloat16 if dtype else torch.float32
+    loss_img = torch.zeros((n, B), dtype=torch.float32, device="cuda")
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dl = torch.zeros((n, B, C), dtype=tdt, device="cuda")
+    df = torch.full((n, B, H, W, C), 7.0, dtype=tdt, device="cuda")
+    desc = pb.parle_act_desc(dtype, n, B, H, W, C)
+    pb.parle_k_gap_head(desc, up(torch, feat, dtype), torch.as_tensor(labels).cuda(), loss_img, loss, dl, df)
+    torch.cuda.synchronize()
+    for r in range(n):
+        t = onets.Tape()
+        fv = onets.Var(feat[r].astype(np.float64))
+        lv = onets.gap(t, fv)
+        ref, _ = onets.softmax_xent(t, lv, labels[r])
+        t.backward()
+        assert abs(loss[r].item() - ref) <= 1e-5 * abs(ref) + 1e-6
+        near("dlogits", down(dl[r]), lv.g, dtype)
+        # the pool's backward pass applied to the dlogits as stored
+        t2 = onets.Tape()
+        fv2 = onets.Var(feat[r].astype(np.float64))
+        lv2 = onets.gap(t2, fv2)
+        lv2.g = down(dl[r])
+        t2.backward()
+        near("dfeat", down(df[r]), fv2.g, dtype)
