@@ -96,10 +96,20 @@ __device__ __forceinline__ float as_stored<bf16_t>(float v) {
   return bf16_to_f32(f32_to_bf16(v));
 }
 
-__device__ __forceinline__ float wave_allsum(float v) {
+// Wavefront sums of kHeadClasses values at once, every lane receiving all of them (xor tree).  The steps of the
+// tree are the outer loop: the shuffles of a step are independent and go out back to back, where one tree after
+// the other would wait for every single shuffle (six dependent ones per value).
+__device__ __forceinline__ void wave_allsum(float (&v)[kHeadClasses], int count) {
 #pragma unroll
-  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, PARLE_WAVE);
-  return v;
+  for (int off = PARLE_WAVE / 2; off > 0; off >>= 1) {
+    float t[kHeadClasses];
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < count) t[c] = __shfl_xor(v[c], off, PARLE_WAVE);
+#pragma unroll
+    for (int c = 0; c < kHeadClasses; ++c)
+      if (c < count) v[c] += t[c];
+  }
 }
 
 template <typename T, bool MASK>
@@ -145,9 +155,10 @@ __global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, c
     for (int c = 0; c < kHeadClasses; ++c)
       if (c < C) lg[c] += fv * Ws[c * D + d];
   }
+  wave_allsum(lg, C);
 #pragma unroll
   for (int c = 0; c < kHeadClasses; ++c)
-    if (c < C) lg[c] = wave_allsum(lg[c]) + (bias ? bias[rep * bias_rs + c] : 0.f);
+    if (c < C) lg[c] += bias ? bias[rep * bias_rs + c] : 0.f;
   float mx = lg[0];
 #pragma unroll
   for (int c = 1; c < kHeadClasses; ++c)
@@ -204,9 +215,10 @@ __global__ __launch_bounds__(kThreads) void k_gap_head(int B, int HW, int C, con
       if (c < C) lg[c] += ldf<T>(f, (long long)p * C + c);
   }
   const float inv = 1.0f / (float)HW;
+  wave_allsum(lg, C);
 #pragma unroll
   for (int c = 0; c < kHeadClasses; ++c)
-    if (c < C) lg[c] = wave_allsum(lg[c]) * inv;
+    if (c < C) lg[c] *= inv;
   float mx = lg[0];
 #pragma unroll
   for (int c = 1; c < kHeadClasses; ++c)
