@@ -11,7 +11,7 @@ running statistics.
 Bars: the loss of every step and every state tensor within 2e-2 (the bound the workload definition states for
 bf16 compute).  25 steps move the parameters by a few per cent of their size at most, so that bar alone would
 also pass a device that did not train; what binds is the DISPLACEMENT from the start of the block, held per
-parameter segment in direction and size (bars below, with the measured figures in the design doc)."""
+parameter segment in direction and size (bars below; measured worst cases beside them)."""
 import json
 import os
 
