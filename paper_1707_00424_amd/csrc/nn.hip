@@ -586,6 +586,30 @@ __device__ __forceinline__ void sum_splits(const double *__restrict__ partial, i
   for (int w = 0; w < kFinThreads / PARLE_WAVE; ++w) s1 += red[0][w], s2 += red[1][w];
 }
 
+// Bias gradient of a layer with few rows (a fully connected layer: one row per image), in one launch: a thread owns
+// a channel and adds its M values in row order (eight loads in flight; lanes run over consecutive channels, so every
+// row is read in whole lines).  The two-kernel reduction below would launch one workgroup per channel and replica
+// to add two or three partial sums.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void k_bias_rows(int M, int C, const T *__restrict__ dy, long long dy_rs,
+                                                        float *__restrict__ grad, long long grad_rs) {
+  const int rep = blockIdx.y, c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= C) return;
+  const T *p = dy + rep * dy_rs + c;
+  double s = 0.0;
+  constexpr int U = 8;
+  int r = 0;
+  for (; r + U <= M; r += U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = ldf<T>(p, (long long)(r + u) * C);
+#pragma unroll
+    for (int u = 0; u < U; ++u) s += (double)v[u];
+  }
+  for (; r < M; ++r) s += (double)ldf<T>(p, (long long)r * C);
+  grad[rep * grad_rs + c] = (float)s;
+}
+
 // bias gradient: grad[c] = sum over splits of s1
 __global__ __launch_bounds__(kFinThreads) void k_bias_finalize(int C, int S, const double *__restrict__ partial,
                                                               float *__restrict__ grad, long long grad_rs) {
@@ -1243,6 +1267,15 @@ int colreduce_splits(int n, int M) {
 
 hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, const void *dy, long long dy_rs,
                             double *partial, float *grad, long long grad_rs) {
+  if (M <= 512) {  // fully connected layers
+    dim3 rgrid((C + kThreads - 1) / kThreads, n);
+    DISPATCH_T(dtype,
+               hipLaunchKernelGGL(k_bias_rows<float>, rgrid, dim3(kThreads), 0, st, M, C, (const float *)dy, dy_rs, grad,
+                                  grad_rs),
+               hipLaunchKernelGGL(k_bias_rows<bf16_t>, rgrid, dim3(kThreads), 0, st, M, C, (const bf16_t *)dy, dy_rs, grad,
+                                  grad_rs));
+    return hipGetLastError();
+  }
   const int S = colreduce_splits(n, M), chunk = col_chunk(M, S), ct = channel_lanes(C);
   dim3 grid(S, n);
   DISPATCH_T(dtype,
