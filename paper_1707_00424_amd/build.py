@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libparle.so")
 
-SOURCES = ["update.hip", "api.hip", "arch.cpp", "net.hip", "igemm.hip", "igemm_fast.hip", "igemm_halo.hip", "igemm_dgrad2.hip", "igemm_ksplit.hip", "igemm_wgrad9.hip", "igemm_smallk.hip", "nn.hip", "conv_api.hip", "layer_api.hip"]
+SOURCES = ["update.hip", "api.hip", "arch.cpp", "net.hip", "igemm.hip", "igemm_fast.hip", "igemm_halo.hip", "igemm_dgrad2.hip", "igemm_dgrad_win.hip", "igemm_ksplit.hip", "igemm_wgrad9.hip", "igemm_smallk.hip", "nn.hip", "conv_api.hip", "layer_api.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-pass-failed", "-Wno-bitwise-instead-of-logical",

@@ -81,6 +81,15 @@ parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc 
   const int es = desc->dtype ? 2 : 4, vw = 16 / es;
   hipStream_t st = (hipStream_t)hip_stream;
   const long long wsize = (long long)c.Cout * c.R * c.R * c.Cin;
+  if (dgrad_window_applicable(desc->dtype, c.B, c.H, c.W, c.Cin, c.Cout, c.R, c.stride, c.pad)) {
+    // the path the network executor takes for such a layer: per-tap products in LDS, weights as they lie
+    const long long x_rs = (long long)c.B * c.H * c.W * c.Cin;
+    return launch_dgrad_window(st, desc->n, c.B, c.H, c.W, c.Cin, c.Cout, c.R, c.pad, (const float *)dy,
+                               (long long)c.B * c.Ho() * c.Wo() * c.Cout, (const float *)w, wsize,
+                               (const float *)relu_mask, x_rs, accumulate, (float *)dx, x_rs) == hipSuccess
+               ? PARLE_OK
+               : PARLE_EHIP;
+  }
   if (launch_weight_transpose(st, desc->dtype, desc->n, c.Cout, c.R * c.R, c.Cin, w, wsize, wt_scratch, wsize) !=
       hipSuccess)
     return PARLE_EHIP;

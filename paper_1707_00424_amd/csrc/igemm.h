@@ -77,6 +77,10 @@ struct WgradIO {
   long long out_rs, split_stride;
   int splits, chunk;  // K-splits over M and rows of M per split (multiple of 32)
   int pairA, pairB;   // packed loads allowed for dy / x
+  // Kernels that can (see wgrad_takes_bias) also write the layer's bias gradient, the column sums of dy, behind the
+  // N*K weight-gradient values of `out`: N more floats per (replica, split).  In a parameter row the bias segment
+  // follows the weight segment, so the one reduction over the splits, or the direct write, covers both.
+  int with_bias;
 };
 
 // A convolution layer as the kernels see it: [B, H, W, Cin] -> [B, Ho, Wo, Cout], R x R window.
@@ -119,6 +123,16 @@ int igemm_fast_stat_splits(int dtype, bool out_f32, const ConvGeom &g, const Gem
 bool conv_halo_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);
 hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io);
 int conv_halo_stat_splits(const ConvGeom &g, int replicas);
+// fp32 backward-data of a stride-1 layer with few input channels under a wide window, the per-tap products of one
+// image held in LDS (igemm_dgrad_win.hip).  w: the layer's weights as they lie, [Cout][R][R][Cin].
+// ... and its backward-weight pass with the window gather in LDS (splits over images; partial sums per split).
+bool wgrad_window_applicable(int dtype, const ConvGeom &g);
+int wgrad_window_plan(int replicas, const ConvGeom &g, int *chunk_out);
+hipError_t launch_wgrad_window(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
+bool dgrad_window_applicable(int dtype, int B, int H, int W, int Cin, int Cout, int R, int stride, int pad);
+hipError_t launch_dgrad_window(hipStream_t st, int n, int B, int H, int W, int Cin, int Cout, int R, int pad,
+                               const float *dy, long long dy_rs, const float *w, long long w_rs,
+                               const float *mask, long long mask_rs, int accumulate, float *dx, long long dx_rs);
 bool wgrad_fast_applicable(int dtype, const ConvGeom &g);
 void wgrad_fast_tile(const ConvGeom &g, int *bm, int *bn);
 hipError_t launch_wgrad_fast(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
@@ -137,6 +151,8 @@ bool gemm_ksplit_applicable(int dtype, int replicas, const ConvGeom &g, const Ge
 hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io);
 // fp32 backward-weight with at most 32 output channels and a window of at most 32 values (igemm_ksplit.hip).
 bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g);
+// True when launch_wgrad would run a kernel that honours WgradIO::with_bias for this layer.
+bool wgrad_takes_bias(int dtype, const ConvGeom &g);
 hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Backward-data of stride-2 3x3 pad-1 layers, four parity classes per workgroup (igemm_dgrad2.hip).
 bool dgrad_s2_applicable(int dtype, const ConvGeom &g, const GemmIO &io, bool out_f32);

@@ -413,6 +413,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
     return hipErrorInvalidValue;
   if (wgrad_smallk_applicable(dtype, g) && aligned_to(io.dy, 16)) return launch_wgrad_smallk(st, replicas, g, io);
   if (wgrad_small_f32_applicable(dtype, g)) return launch_wgrad_small_f32(st, replicas, g, io);
+  if (wgrad_window_applicable(dtype, g)) return launch_wgrad_window(st, replicas, g, io);
   if (wgrad9_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad9(st, replicas, g, io);
   if (wgrad_fast_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad_fast(st, replicas, g, io);
   if (dtype == 0) return run_wgrad<float, 2, 2, 1, 1>(st, replicas, g, io);
@@ -426,6 +427,8 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
 
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   if (wgrad9_applicable(dtype, g)) return wgrad9_plan(replicas, g, chunk_out);
+  if (!wgrad_smallk_applicable(dtype, g) && !wgrad_small_f32_applicable(dtype, g) && wgrad_window_applicable(dtype, g))
+    return wgrad_window_plan(replicas, g, chunk_out);
   int bm, bn;
   if (wgrad_smallk_applicable(dtype, g)) {
     bm = 128, bn = 32;

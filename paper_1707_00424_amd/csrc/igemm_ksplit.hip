@@ -109,6 +109,8 @@ hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int repli
 // each; an MFMA (32 x 32 x 2) contracts two rows, whose operands are one float of dy and one gathered float of
 // the input per lane, loaded straight into registers (the window position of a lane is fixed, its pixel
 // advances by two per MFMA).  The four partial tiles are added in wavefront order.
+// With io.with_bias (window of fewer than 32 values) the first unused column of the x operand is all ones: that
+// column of the result is sum_m dy[m][n], the bias gradient, at no cost; it goes behind the N*K values.
 // ---------------------------------------------------------------------------------------------
 namespace {
 
@@ -148,6 +150,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, 
       const bool tap_ok = ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win;
       av[u] = (live && n_ok) ? dy[(long long)m * g.N + col] : 0.f;
       bv[u] = (live && k_ok && tap_ok) ? x[((long long)(b * g.Hin + ih) * g.Win + iw) * g.Cc + kc] : 0.f;
+      if (io.with_bias && col == g.K) bv[u] = live ? 1.f : 0.f;
       m += 2, q += 2;
       while (q >= g.Q) {
         q -= g.Q;
@@ -179,6 +182,12 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, 
       const int n = 8 * (v >> 2) + 4 * h + (v & 3);
       if (n < g.N) out[(long long)n * g.K + col] = acc[v];
     }
+  } else if (io.with_bias && col == g.K) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int n = 8 * (v >> 2) + 4 * h + (v & 3);
+      if (n < g.N) out[(long long)g.N * g.K + n] = acc[v];
+    }
   }
 }
 
@@ -187,6 +196,8 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, 
 bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g) {
   return dtype == 0 && g.K <= 32 && g.N <= 32 && g.dshift == 0 && g.sr == 1 && g.M >= 1 && g.Q >= 1;
 }
+
+bool wgrad_takes_bias(int dtype, const ConvGeom &g) { return wgrad_small_f32_applicable(dtype, g) && g.K < 32; }
 
 hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   dim3 grid(1, 1, replicas * io.splits);

@@ -44,6 +44,7 @@ struct Op {
   int dx_after = -1;       // index of the shortcut op whose input gradient this op's accumulates onto
   int64_t wt_off = -1;     // transposed weights (bytes)
   int64_t col_off = -1;    // per-tap products of the two-pass backward-data (bytes), -1 = direct kernel
+  bool win = false;        // backward-data through per-tap products held in LDS, one image per workgroup
   // pool
   bool pool_relu_mask = false;
   // bn
@@ -351,16 +352,26 @@ bool build_plan(Net &N, std::string &err) {
         // direct implicit GEMM the pass has 20 output columns on 32-wide fp32 MFMA tiles and a contraction
         // of 1250; as dy x W (500 columns, contraction 50) plus a gather over the window it is a fraction
         if (N.dtype == 0 && op.stride == 1 && op.R > 1 && op.Cin <= 32 && op.R * op.R * op.Cin >= 128 &&
-            (int64_t)N.B * op.Ho * op.Wo * op.Cin * op.R * op.R < (1LL << 31))
-          col_bytes = std::max(col_bytes, (int64_t)N.n * N.B * op.Ho * op.Wo * op.Cin * op.R * op.R * 4), op.col_off = 0;
+            (int64_t)N.B * op.Ho * op.Wo * op.Cin * op.R * op.R < (1LL << 31)) {
+          // the products of one image fit in LDS: one kernel, nothing through memory
+          static const bool window_kernel = [] {
+            const char *e = getenv("PARLE_DGRAD_WINDOW");
+            return !(e && atoi(e) == 0);
+          }();
+          if (window_kernel && dgrad_window_applicable(N.dtype, N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad))
+            op.win = true;
+          else
+            col_bytes = std::max(col_bytes, (int64_t)N.n * N.B * op.Ho * op.Wo * op.Cin * op.R * op.R * 4), op.col_off = 0;
+        }
       }
       // the complete forward geometry: the split plan depends on which kernel variant will run
       ConvGeom g = conv_fwd_geom(ConvShape{N.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad});
       g.leaf_waves = N.leaf_waves;
       int chunk = 0;
       const int S = wgrad_plan(N.dtype, N.n, g, &chunk);
-      if (S > 1 && (int64_t)N.n * S * wsize * 4 > (op.need_dx ? wpartial : wpartial_main))
-        (op.need_dx ? wpartial : wpartial_main) = (int64_t)N.n * S * wsize * 4;
+      // (+ Cout: a kernel that also takes the bias gradient puts it behind the weight gradient, see backward())
+      if (S > 1 && (int64_t)N.n * S * (wsize + op.Cout) * 4 > (op.need_dx ? wpartial : wpartial_main))
+        (op.need_dx ? wpartial : wpartial_main) = (int64_t)N.n * S * (wsize + op.Cout) * 4;
       if ((int64_t)N.B * op.Hin * op.Win * op.Cin >= (1LL << 31) || (int64_t)g.M * op.Cout >= (1LL << 31) ||
           wsize >= (1LL << 31)) {
         err = "a layer exceeds 2^31 elements per replica";
@@ -381,7 +392,7 @@ bool build_plan(Net &N, std::string &err) {
   for (int vec = 1; vec >= 0; --vec) {
     bool open = false;
     for (const Op &op : N.ops) {
-      if (op.type != OP_CONV || !op.need_dx || op.head) continue;
+      if (op.type != OP_CONV || !op.need_dx || op.head || op.win) continue;  // these read the weights as they lie
       if ((int)transpose_vector_ok(N.dtype, op.Cout, op.Cin, N.segs[op.wseg].offset) != vec) continue;
       if (!open || N.transposes.back().count == TransposeTable::kMax) {
         N.transposes.emplace_back();
@@ -608,7 +619,12 @@ hipError_t backward(const Run &r, float *grad) {
           if (N.side && op.dx_after >= 0) HIP_TRY(hipStreamWaitEvent(r.st, N.br_dx[op.dx_after], 0));
           void *wt = r.ws + op.wt_off;  // transposed once per step, all layers in one launch
           const int64_t wsize = N.segs[op.wseg].size;
-          if (op.col_off > 0) {
+          if (op.win) {
+            HIP_TRY(launch_dgrad_window(r.st, r.n, r.B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.pad, (const float *)dy,
+                                        dy_rs, (const float *)r.wptr(op.wseg), r.p_rs,
+                                        op.mask_in ? (const float *)r.tptr(op.in) : nullptr, r.trs(op.in),
+                                        op.dx_accumulate, (float *)r.gptr(op.in), r.trs(op.in)));
+          } else if (op.col_off > 0) {
             // col = dy x W: the transposed weights, here ordered [RS][Cin][Cout], are the [N][K] operand as they lie
             const int RS = op.R * op.R, M = r.B * op.Ho * op.Wo, Ncol = op.Cin * RS;
             const ConvGeom gc = conv_fwd_geom(ConvShape{M, 1, 1, op.Cout, Ncol, 1, 1, 0});
@@ -636,7 +652,11 @@ hipError_t backward(const Run &r, float *grad) {
           HIP_TRY(launch_dgrad(N.ops[op.join], lst));
           if (N.side) HIP_TRY(hipEventRecord(N.br_dx[op.join], N.side));
         }
-        if (op.bseg >= 0) {
+        // the weight-gradient kernel of this layer takes the bias gradient along (a first layer in fp32 with a
+        // window of fewer than 32 values): the bias segment follows the weight segment in the parameter row
+        const bool bias_in_wgrad = op.bseg >= 0 && wgrad_takes_bias(N.dtype, gf) &&
+                                   N.segs[op.bseg].offset == N.segs[op.wseg].offset + N.segs[op.wseg].size;
+        if (op.bseg >= 0 && !bias_in_wgrad) {
           hipStream_t bst = lst;
           if (fork && N.side2 && N.bias_stream) {
             HIP_TRY(hipStreamWaitEvent(N.side2, N.dy_ready[oi], 0));
@@ -654,7 +674,8 @@ hipError_t backward(const Run &r, float *grad) {
           io.splits = S, io.chunk = chunk;
           io.pairA = (op.Cout % 2 == 0) && aligned_to(dy, 4);
           io.pairB = (op.Cin % 2 == 0) && aligned_to(io.x, 4);
-          const int64_t wsize = N.segs[op.wseg].size;
+          io.with_bias = bias_in_wgrad;
+          const int64_t wsize = N.segs[op.wseg].size + (bias_in_wgrad ? op.Cout : 0);  // values per (replica, split)
           if (S == 1) {
             io.out = grad + N.segs[op.wseg].offset, io.out_rs = r.p_rs, io.split_stride = 0;
             HIP_TRY(launch_wgrad(lst, N.dtype, r.n, gf, io));

@@ -92,6 +92,8 @@ CASES = [
     (1, 2, 16, 16, 40, 48, 3, 1, 1),    # same, one full chunk and a ragged one, in both directions
     (2, 3, 6, 7, 8, 12, 5, 1, 2),       # padded 5x5 window on 6 x 7 pixels, 8 channels
     (1, 2, 8, 8, 32, 10, 2, 1, 0),      # 2x2 window, no padding
+    (2, 5, 12, 12, 20, 50, 5, 1, 0),    # LeNet's second convolution: fp32 backward-data with the per-tap products in LDS
+    (1, 3, 7, 9, 6, 13, 3, 1, 1),       # same path, padded 3x3 window, odd sizes (63 output pixels, 13 output channels)
     (3, 128, 1, 1, 784, 128, 1, 1, 0),  # the MLP's first layer: contraction split over the wavefronts of a workgroup
     (2, 20, 1, 1, 504, 10, 1, 1, 0),    # same, ten outputs, contraction not a multiple of the four quarters
 ]
