@@ -586,28 +586,38 @@ __device__ __forceinline__ void sum_splits(const double *__restrict__ partial, i
   for (int w = 0; w < kFinThreads / PARLE_WAVE; ++w) s1 += red[0][w], s2 += red[1][w];
 }
 
-// Bias gradient of a layer with few rows (a fully connected layer: one row per image), in one launch: a thread owns
-// a channel and adds its M values in row order (eight loads in flight; lanes run over consecutive channels, so every
-// row is read in whole lines).  The two-kernel reduction below would launch one workgroup per channel and replica
-// to add two or three partial sums.
+// Bias gradient of a layer with few rows (a fully connected layer: one row per image), in one launch: a workgroup
+// owns 64 channels, its four wavefronts a quarter of the rows each (row r goes to wavefront r % 4; eight loads in
+// flight per thread, lanes on consecutive channels so every row is read in whole lines); the four partial sums
+// are added in wavefront order.  The two-kernel reduction below would launch one workgroup per channel and
+// replica to add two or three partial sums.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_bias_rows(int M, int C, const T *__restrict__ dy, long long dy_rs,
                                                         float *__restrict__ grad, long long grad_rs) {
-  const int rep = blockIdx.y, c = blockIdx.x * kThreads + threadIdx.x;
-  if (c >= C) return;
-  const T *p = dy + rep * dy_rs + c;
+  __shared__ double part[kThreads / PARLE_WAVE][PARLE_WAVE];
+  constexpr int RL = kThreads / PARLE_WAVE;
+  const int rep = blockIdx.y, lane = threadIdx.x & (PARLE_WAVE - 1), rl = threadIdx.x / PARLE_WAVE;
+  const int c = blockIdx.x * PARLE_WAVE + lane;
+  const T *p = dy + rep * dy_rs + (c < C ? c : 0);
   double s = 0.0;
   constexpr int U = 8;
-  int r = 0;
-  for (; r + U <= M; r += U) {
+  int r = rl;
+  for (; r + (U - 1) * RL < M; r += U * RL) {
     float v[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = ldf<T>(p, (long long)(r + u) * C);
+    for (int u = 0; u < U; ++u) v[u] = ldf<T>(p, (long long)(r + u * RL) * C);
 #pragma unroll
     for (int u = 0; u < U; ++u) s += (double)v[u];
   }
-  for (; r < M; ++r) s += (double)ldf<T>(p, (long long)r * C);
-  grad[rep * grad_rs + c] = (float)s;
+  for (; r < M; r += RL) s += (double)ldf<T>(p, (long long)r * C);
+  part[rl][lane] = s;
+  __syncthreads();
+  if (rl == 0 && c < C) {
+    double t = part[0][lane];
+#pragma unroll
+    for (int w = 1; w < RL; ++w) t += part[w][lane];
+    grad[rep * grad_rs + c] = (float)t;
+  }
 }
 
 // bias gradient: grad[c] = sum over splits of s1
@@ -1268,7 +1278,7 @@ int colreduce_splits(int n, int M) {
 hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, const void *dy, long long dy_rs,
                             double *partial, float *grad, long long grad_rs) {
   if (M <= 512) {  // fully connected layers
-    dim3 rgrid((C + kThreads - 1) / kThreads, n);
+    dim3 rgrid((C + PARLE_WAVE - 1) / PARLE_WAVE, n);
     DISPATCH_T(dtype,
                hipLaunchKernelGGL(k_bias_rows<float>, rgrid, dim3(kThreads), 0, st, M, C, (const float *)dy, dy_rs, grad,
                                   grad_rs),
