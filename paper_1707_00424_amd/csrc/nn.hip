@@ -128,6 +128,11 @@ __global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, c
   const int rep = blockIdx.y, lane = threadIdx.x & (PARLE_WAVE - 1), wave = threadIdx.x / PARLE_WAVE;
   const int b0 = blockIdx.x * kWaves, b = b0 + wave;
   const T *wp = w + rep * w_rs;
+  // the image's label and the biases travel while the operands are staged
+  const int y = b < B ? labels[(long long)rep * B + b] : 0;
+  float bv[kHeadClasses];
+#pragma unroll
+  for (int c = 0; c < kHeadClasses; ++c) bv[c] = (bias && c < C) ? bias[rep * bias_rs + c] : 0.f;
   // sixteen loads in flight per thread: a loop that stores each value before it asks for the next would pay one
   // round trip to L2 per element
   auto stage = [&](float *dst, const T *src, int count) {
@@ -158,7 +163,7 @@ __global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, c
   wave_allsum(lg, C);
 #pragma unroll
   for (int c = 0; c < kHeadClasses; ++c)
-    if (c < C) lg[c] += bias ? bias[rep * bias_rs + c] : 0.f;
+    if (c < C) lg[c] += bv[c];
   float mx = lg[0];
 #pragma unroll
   for (int c = 1; c < kHeadClasses; ++c)
@@ -168,7 +173,6 @@ __global__ __launch_bounds__(kHeadThreads) void k_fc_head(int B, int D, int C, c
   for (int c = 0; c < kHeadClasses; ++c)
     if (c < C) se += expf(lg[c] - mx);
   const float lse = logf(se) + mx;
-  const int y = labels[(long long)rep * B + b];
   const float invB = 1.0f / (float)B;
   float ly = 0.f, mine = 0.f;
 #pragma unroll
