@@ -158,6 +158,32 @@ def test_one_step_loss_and_gradient(gpu, name, bf16):
         check(f"{name} {t}", got[t], getattr(O.st, t), 1e-5)
 
 
+MANY_CLASSES = {
+    # more classes than the one-kernel heads take (16): the last layer, the loss and the pool keep their own kernels;
+    # 300 features: more than the fully connected head takes (256)
+    "mlp_17": onets.arch("mlp", H=6, W=6, C=1, hidden=40, classes=17),
+    "mlp_300": onets.arch("mlp", H=6, W=6, C=1, hidden=300, classes=10),
+    "allcnn_18": onets.arch("allcnn", H=8, W=8, C=3, ca=8, cb=16, classes=18),
+    "wrn_20": onets.arch("wrn", H=8, W=8, C=3, base=4, widen=2, nb=1, classes=20),
+}
+
+
+@pytest.mark.parametrize("name", list(MANY_CLASSES))
+def test_heads_beyond_the_one_kernel_limits(gpu, name):
+    torch, pb = gpu
+    a = MANY_CLASSES[name]
+    n, B = 2, 7
+    P, O = make(pb, a, n, B, seed=5, distinct_init=True)
+    X, Y = synth.image_batches(6, 1, n, B, a["H"], a["W"], a["C"], a["classes"])
+    loss = torch.zeros(n, dtype=torch.float32, device="cuda")
+    P.parle_inner_step(dev(torch, X[0]), dev(torch, Y[0]), loss)
+    ref_loss = O.inner_step(X[0], Y[0])
+    np.testing.assert_allclose(loss.cpu().numpy(), ref_loss, rtol=1e-5)
+    got = P.state()
+    for seg, err, _ in segment_errors(onets.layout(a), got["grad"].astype(np.float64), O.last_grad):
+        assert err <= 1e-4, (name, seg, err)
+
+
 TINY_BF16 = {
     # few enough stored values that about half of the replicas see no rounding event at all
     "allcnn": onets.arch("allcnn", H=8, W=8, C=3, ca=8, cb=16, classes=5),
