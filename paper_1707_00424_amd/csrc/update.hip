@@ -199,7 +199,9 @@ __global__ __launch_bounds__(kThreads) void k_outer_update(f4 *__restrict__ X, f
 }
 
 // Same update with the replica mean formed in registers: every x^a[i] is read once, the mean is
-// written to x_ref, and no second pass over x is needed.  N > 0: compile-time replica count.
+// written to x_ref, and no second pass over x is needed.  N > 0: compile-time replica count; the N loads
+// of x are issued together, z^a and v^a are fetched per replica as its update is formed (holding all
+// 3N vectors costs a wavefront of occupancy and gains nothing).
 template <int N, int U, bool NT, bool BF>
 __global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4 *__restrict__ Z, f4 *__restrict__ VX,
                                                           f4 *__restrict__ Y, f4 *__restrict__ VY,
@@ -209,22 +211,18 @@ __global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4
   const f4 zero = {0.f, 0.f, 0.f, 0.f};
   const int n = N > 0 ? N : n_rt;
   const float fn = (float)n;
-  // a block owns U adjacent 4 KiB chunks of every row; all loads of a chunk are issued before its arithmetic
+  // a block owns U adjacent 4 KiB chunks of every row
   const int64_t trip = (int64_t)gridDim.x * kThreads * U;
   for (int64_t q0 = (int64_t)blockIdx.x * kThreads * U + threadIdx.x; q0 < np4; q0 += trip) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t q = q0 + u * kThreads;
       if (q >= np4) break;
-      f4 xs[N > 0 ? N : 1], zs[N > 0 ? N : 1], vs[N > 0 ? N : 1];
+      f4 xs[N > 0 ? N : 1];
       f4 s;
       if (N > 0) {
 #pragma unroll
         for (int a = 0; a < N; ++a) xs[a] = ld4<NT>(X + (int64_t)a * np4 + q);
-#pragma unroll
-        for (int a = 0; a < N; ++a) zs[a] = ld4<NT>(Z + (int64_t)a * np4 + q);
-#pragma unroll
-        for (int a = 0; a < N; ++a) vs[a] = ld4<NT>(VX + (int64_t)a * np4 + q);
         s = xs[0];
 #pragma unroll
         for (int a = 1; a < N; ++a) s += xs[a];
@@ -239,8 +237,8 @@ __global__ __launch_bounds__(kThreads) void k_outer_fused(f4 *__restrict__ X, f4
       for (int a = 0; a < n; ++a) {
         const int64_t o = (int64_t)a * np4 + q;
         const f4 x = N > 0 ? xs[N > 0 ? a : 0] : X[o];
-        const f4 z = N > 0 ? zs[N > 0 ? a : 0] : ld4<NT>(Z + o);
-        const f4 v = N > 0 ? vs[N > 0 ? a : 0] : ld4<NT>(VX + o);
+        const f4 z = ld4<NT>(Z + o);
+        const f4 v = ld4<NT>(VX + o);
         const f4 d = cz * (x - z) + r * (x - xr);
         const f4 vn = mu * v + d;
         const f4 xn = x - eta * (d + mu * vn);
