@@ -341,7 +341,16 @@ parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc 
  * workgroups and reduced in a fixed order; scratch must hold parle_k_conv_scratch_bytes(desc). */
 parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *x,
                                           float *scratch, int64_t scratch_bytes, float *dw);
-int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc); /* -1 on a bad descriptor */
+/* The same weight gradient with the layer's bias gradient (Section 1.1's loss differentiated with
+ * respect to a per-channel offset of y: the sum of dy over batch and positions) taken along by the
+ * kernels that read all of dy anyway: dwb [n][cout*k*k*cin + cout] fp32, each replica's bias gradient
+ * behind its weight gradient, as the two segments lie in a parameter row.  *took_bias_host (HOST) = 1
+ * when the kernel that runs this layer wrote the cout bias values, 0 when it left them untouched (the
+ * caller then sums dy itself, parle_k_bias_grad).  Scratch as above. */
+parle_status parle_k_conv_backward_weight_bias(void *hip_stream, const parle_conv_desc *desc, const void *dy,
+                                               const void *x, float *scratch, int64_t scratch_bytes, float *dwb,
+                                               int32_t *took_bias_host);
+int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc); /* -1 on a bad descriptor; covers both forms */
 
 /* ------------------------------------------------------------------------------------------
  * The memory-bound layer kernels of the same forward / backward pass (Section 1.1's loss; the

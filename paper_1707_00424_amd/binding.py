@@ -93,6 +93,8 @@ _SIGNATURES = {
                                    C.c_int32, C.c_void_p, C.c_void_p],
     "parle_k_conv_backward_weight": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_void_p],
+    "parle_k_conv_backward_weight_bias": [C.c_void_p, C.POINTER(parle_conv_desc), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int64, C.c_void_p, C.POINTER(C.c_int32)],
     "parle_k_bn_forward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                            C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p],
     "parle_k_bn_backward": [C.c_void_p, C.POINTER(parle_act_desc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -253,6 +255,15 @@ def parle_k_conv_backward_weight(desc, dy, x, scratch, dw, stream=None):
     nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
     _check(lib().parle_k_conv_backward_weight(_stream_handle(stream), C.byref(desc), _ptr(dy), _ptr(x), _ptr(scratch),
                                               nbytes, _ptr(dw)))
+
+
+def parle_k_conv_backward_weight_bias(desc, dy, x, scratch, dwb, stream=None) -> bool:
+    """Returns whether the bias gradient was written behind each replica's weight gradient."""
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    took = C.c_int32(-1)
+    _check(lib().parle_k_conv_backward_weight_bias(_stream_handle(stream), C.byref(desc), _ptr(dy), _ptr(x),
+                                                   _ptr(scratch), nbytes, _ptr(dwb), C.byref(took)))
+    return bool(took.value)
 
 
 def parle_k_conv_scratch_bytes(desc) -> int:

@@ -106,15 +106,19 @@ parle_status parle_k_conv_backward_data(void *hip_stream, const parle_conv_desc 
   return launch_igemm(st, desc->dtype, false, desc->n, g, io) == hipSuccess ? PARLE_OK : PARLE_EHIP;
 }
 
-parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *x,
-                                          float *scratch, int64_t scratch_bytes, float *dw) {
+}  // extern "C"
+
+namespace {
+// dw [n][wsize (+ cout)]: with `took_bias_host` given, the bias gradient follows the weight gradient of each replica
+// where the kernel that runs this layer takes it along
+parle_status backward_weight(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *x, float *scratch,
+                             int64_t scratch_bytes, float *dw, int32_t *took_bias_host) {
   ConvShape c;
   if (parle_status s = check_desc(desc, c)) return s;
   if (!dy || !x || !dw) return PARLE_EINVAL;
   if (!aligned_to(dy, 16) || !aligned_to(x, 16) || !aligned_to(dw, 16) || !aligned_to(scratch, 16)) return PARLE_EALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
   const ConvGeom g = conv_fwd_geom(c);
-  const long long wsize = (long long)g.N * g.K;
   WgradIO io{};
   io.dy = dy, io.dy_rs = (long long)g.M * g.N;
   io.x = x, io.x_rs = (long long)c.B * c.H * c.W * c.Cin;
@@ -123,14 +127,35 @@ parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_des
   io.splits = S, io.chunk = chunk;
   io.pairA = (c.Cout % 2 == 0);
   io.pairB = (c.Cin % 2 == 0);
+  io.with_bias = took_bias_host && wgrad_takes_bias(desc->dtype, g, io);
+  if (took_bias_host) *took_bias_host = io.with_bias;
+  // values a kernel writes per (replica, split), and the caller's row: the bias slots exist in dw whenever the caller
+  // asked for this form, and are written only by a kernel that takes the bias along
+  const long long wsize = (long long)g.N * g.K + (io.with_bias ? g.N : 0);
+  const long long row = (long long)g.N * g.K + (took_bias_host ? g.N : 0);
   if (S == 1) {
-    io.out = dw, io.out_rs = wsize, io.split_stride = 0;
+    io.out = dw, io.out_rs = row, io.split_stride = 0;
     return launch_wgrad(st, desc->dtype, desc->n, g, io) == hipSuccess ? PARLE_OK : PARLE_EHIP;
   }
   if (!scratch || scratch_bytes < (int64_t)desc->n * S * wsize * 4) return PARLE_ESIZE;
   io.out = scratch, io.out_rs = (long long)S * wsize, io.split_stride = wsize;
   if (launch_wgrad(st, desc->dtype, desc->n, g, io) != hipSuccess) return PARLE_EHIP;
-  return launch_reduce_partials(st, desc->n, S, wsize, scratch, dw, wsize) == hipSuccess ? PARLE_OK : PARLE_EHIP;
+  return launch_reduce_partials(st, desc->n, S, wsize, scratch, dw, row) == hipSuccess ? PARLE_OK : PARLE_EHIP;
+}
+}  // namespace
+
+extern "C" {
+
+parle_status parle_k_conv_backward_weight(void *hip_stream, const parle_conv_desc *desc, const void *dy, const void *x,
+                                          float *scratch, int64_t scratch_bytes, float *dw) {
+  return backward_weight(hip_stream, desc, dy, x, scratch, scratch_bytes, dw, nullptr);
+}
+
+parle_status parle_k_conv_backward_weight_bias(void *hip_stream, const parle_conv_desc *desc, const void *dy,
+                                               const void *x, float *scratch, int64_t scratch_bytes, float *dwb,
+                                               int32_t *took_bias_host) {
+  if (!took_bias_host) return PARLE_EINVAL;
+  return backward_weight(hip_stream, desc, dy, x, scratch, scratch_bytes, dwb, took_bias_host);
 }
 
 int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc) {
@@ -139,7 +164,7 @@ int64_t parle_k_conv_scratch_bytes(const parle_conv_desc *desc) {
   const ConvGeom g = conv_fwd_geom(c);
   int chunk = 0;
   const int S = wgrad_plan(desc->dtype, desc->n, g, &chunk);
-  return S == 1 ? 0 : (int64_t)desc->n * S * g.N * g.K * 4;
+  return S == 1 ? 0 : (int64_t)desc->n * S * ((int64_t)g.N * g.K + g.N) * 4;
 }
 
 }  // extern "C"

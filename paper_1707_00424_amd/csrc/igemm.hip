@@ -425,6 +425,14 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
   }
 }
 
+// mirrors the order of launch_wgrad
+bool wgrad_takes_bias(int dtype, const ConvGeom &g, const WgradIO &io) {
+  if (wgrad_smallk_applicable(dtype, g) && aligned_to(io.dy, 16)) return g.K < 32;
+  if (wgrad_small_f32_applicable(dtype, g)) return g.K < 32;
+  if (wgrad_window_applicable(dtype, g)) return false;
+  return (wgrad9_applicable(dtype, g) || wgrad_fast_applicable(dtype, g)) && io.pairA && io.pairB;
+}
+
 int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
   if (wgrad9_applicable(dtype, g)) return wgrad9_plan(replicas, g, chunk_out);
   if (!wgrad_smallk_applicable(dtype, g) && !wgrad_small_f32_applicable(dtype, g) && wgrad_window_applicable(dtype, g))

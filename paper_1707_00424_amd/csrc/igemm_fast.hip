@@ -335,7 +335,9 @@ __device__ __forceinline__ u4 lds_tr_frag(const bf16_t *tile, int ld, int krow, 
   return r;
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN>
+// BIAS: the workgroups of the first column tile also sum the dy vectors they stage and write the layer's bias
+// gradient, the column sums of dy, behind the weights.
+template <int WAVES_M, int WAVES_N, int TM, int TN, bool BIAS>
 __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const WgradIO io) {
   constexpr int BKM = 32;  // pixels per contraction step
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
@@ -371,6 +373,14 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
   const int b_tapoff = ((b_r - (-g.off)) * g.Win + (b_s - (-g.off))) * g.Cc + b_c;  // (r - pad, s - pad)
 
   const u4 zero4 = {0u, 0u, 0u, 0u};
+  const bool tally = BIAS && blockIdx.x == 0;
+  float bsum[BIAS ? A_IT : 1][8];
+  if (BIAS) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) bsum[i][e] = 0.f;
+  }
 
   // rows at or beyond m_end are masked, so the pipeline may load two steps ahead unconditionally
   auto load_tiles = [&](int mbase, u4 (&areg)[A_IT], u4 (&breg)[B_IT]) {
@@ -403,6 +413,17 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) *(u4 *)&Bs[buf][(i * B_ROWS + brow0) * LDB + bcv * 8] = breg[i];
+    if (BIAS && tally) {  // masked rows and columns hold zeros
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) {
+        const uint32_t w[4] = {areg[i].x, areg[i].y, areg[i].z, areg[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          bsum[i][2 * e] += __uint_as_float(w[e] << 16);
+          bsum[i][2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+        }
+      }
+    }
   };
 
   f16v acc[TM][TN];
@@ -465,6 +486,26 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const W
         if (n < g.N) out[(long long)n * g.K + k] = acc[tm][tn][v];
       }
   }
+  if (BIAS && tally) {
+    // vector v of a step lies in pixel row v / AV: the 32 rows are added in a fixed order
+    float *bs = (float *)&As[0][0];  // [BKM][BM]
+    static_assert(sizeof(As) >= BKM * BM * 4, "bias staging");
+    __syncthreads();  // the last fragments have been read
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int v = i * kThreads + tid;
+      if (BKM * AV % kThreads == 0 || v < BKM * AV) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bs[(v / AV) * BM + (v % AV) * 8 + e] = bsum[i][e];
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < BM; c += kThreads) {
+      float t = 0.f;
+      for (int q = 0; q < BKM; ++q) t += bs[q * BM + c];
+      if (n0 + c < g.N) out[(long long)g.N * g.K + n0 + c] = t;
+    }
+  }
 }
 
 template <typename T, int WM, int WN, int TM, int TN, int GB = 16>
@@ -498,7 +539,10 @@ template <int WM, int WN, int TM, int TN>
 hipError_t run_tr(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   dim3 grid((g.K + BN - 1) / BN, (g.N + BM - 1) / BM, replicas * io.splits);
-  hipLaunchKernelGGL((k_wgrad_tr<WM, WN, TM, TN>), grid, dim3(kThreads), 0, st, g, io);
+  if (io.with_bias)
+    hipLaunchKernelGGL((k_wgrad_tr<WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+  else
+    hipLaunchKernelGGL((k_wgrad_tr<WM, WN, TM, TN, false>), grid, dim3(kThreads), 0, st, g, io);
   return hipGetLastError();
 }
 

@@ -197,8 +197,6 @@ bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g) {
   return dtype == 0 && g.K <= 32 && g.N <= 32 && g.dshift == 0 && g.sr == 1 && g.M >= 1 && g.Q >= 1;
 }
 
-bool wgrad_takes_bias(int dtype, const ConvGeom &g) { return wgrad_small_f32_applicable(dtype, g) && g.K < 32; }
-
 hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   dim3 grid(1, 1, replicas * io.splits);
   hipLaunchKernelGGL(k_wgrad_small_f32, grid, dim3(kThreads), 0, st, g, io);

@@ -184,6 +184,8 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
     for (int e = 0; e < 4; ++e) {
       const bool ok = mok && (unsigned)(h0 + k_r[e]) < (unsigned)g.Hin && (unsigned)(w0 + k_s[e]) < (unsigned)g.Win;
       breg[e] = __builtin_amdgcn_raw_buffer_load_b16(x_rsrc, ok ? (uint32_t)((base + k_off[e]) * 2) : kOobOffset, 0, 0);
+      // the first unused column is all ones over the live pixels: its products are the column sums of dy
+      if (io.with_bias && kq + e == g.K) breg[e] = mok ? (unsigned short)0x3F80 : (unsigned short)0;
     }
   };
   auto store_tiles = [&](int buf, const u4 (&areg)[A_IT], const unsigned short (&breg)[4]) {
@@ -238,6 +240,12 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
     for (int v = 0; v < 16; ++v) {
       const int n = n0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
       if (n < g.N) out[(long long)n * g.K + k] = acc[v];
+    }
+  } else if (io.with_bias && k == g.K) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int n = n0 + wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+      if (n < g.N) out[(long long)g.N * g.K + n] = acc[v];
     }
   }
 }

@@ -21,6 +21,8 @@
 // (8 rows x 16 columns, or two 8 x 8 images) of the images of its split; the operands of the next block travel from memory to
 // registers while the current block is multiplied, LDS is single-buffered.  Partial sums of the
 // splits go to per-split buffers that a second kernel adds in a fixed order (no float atomics).
+// BIAS: the workgroups of the first x tile also sum the dy vectors they stage (a thread keeps the same eight
+// channels for the whole kernel) and write the layer's bias gradient, the column sums of dy, behind the weights.
 #include "igemm_dev.h"
 
 namespace {
@@ -62,7 +64,7 @@ __device__ __forceinline__ u4 tr_frag(const bf16_t *tile, int ld, int krow, int 
   return r;
 }
 
-template <int NT, int KC>
+template <int NT, int KC, bool BIAS>
 __global__ __launch_bounds__(NT * 64) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad9(const Wg9Geom wg, const WgradIO io) {
   typedef Patch<KC> PT;
   constexpr int kSlots = PT::SLOTS, kPC = PT::PC;
@@ -102,6 +104,12 @@ __global__ __launch_bounds__(NT * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int d_pitch = (KC == 16 ? wg.W : 16) * wg.N * 2;
 
   u4 xreg[X_IT], dreg[D_IT];
+  const bool tally = BIAS && ct == 0;
+  float bsum[BIAS ? 8 : 1];
+  if (BIAS) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bsum[e] = 0.f;
+  }
   auto load_block = [&](int blk) {
     const bool live = blk < blk_end;
     int b, row0, col0;
@@ -134,6 +142,17 @@ __global__ __launch_bounds__(NT * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
 #pragma unroll
     for (int it = 0; it < D_IT; ++it) *(u4 *)&ds[(it * 16 + d_pcol) * DS + d_vec * 16] = dreg[it];
+    if (BIAS && tally) {
+#pragma unroll
+      for (int it = 0; it < D_IT; ++it) {
+        const uint32_t w[4] = {dreg[it].x, dreg[it].y, dreg[it].z, dreg[it].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          bsum[2 * e] += __uint_as_float(w[e] << 16);
+          bsum[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+        }
+      }
+    }
   };
 
   f16v acc[3][3];
@@ -238,6 +257,20 @@ __global__ __launch_bounds__(NT * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         const int n = (ng * NT + wave) * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
         out[(long long)n * K + (r * 3 + s) * wg.Cin + c] = acc[r][s][v];
       }
+  if (BIAS && tally) {
+    // the sixteen threads that share a channel vector (one per pixel column of a sub-step) are added in a fixed order
+    float *bs = (float *)ds;  // [16][NT * 32]
+    __syncthreads();          // the last block's fragments have been read
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bs[d_pcol * (NT * 32) + d_vec * 8 + e] = bsum[e];
+    __syncthreads();
+    if (tid < NT * 32) {
+      float t = 0.f;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) t += bs[q * (NT * 32) + tid];
+      out[(long long)wg.N * K + ng * NT * 32 + tid] = t;
+    }
+  }
 }
 
 int wg9_tiles(int nt32) {  // dy tiles per workgroup for N/32 tiles in all
@@ -310,12 +343,19 @@ hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const 
   if (wg.bps < 1 || (long long)wg.bps * io.splits < wg.total_blocks) return hipErrorInvalidValue;
   const int nt = wg9_tiles(g.N / 32);
   dim3 grid(g.Cc / 32, g.N / 32 / nt, replicas * io.splits);
-#define WG9_CASE(NTV)                                                                      \
-  case NTV:                                                                                \
-    if (wg.W == 8)                                                                         \
-      hipLaunchKernelGGL((k_wgrad9<NTV, 8>), grid, dim3(NTV * 64), 0, st, wg, io);         \
-    else                                                                                   \
-      hipLaunchKernelGGL((k_wgrad9<NTV, 16>), grid, dim3(NTV * 64), 0, st, wg, io);        \
+#define WG9_LAUNCH(NTV, KCV)                                                                  \
+  do {                                                                                        \
+    if (io.with_bias)                                                                         \
+      hipLaunchKernelGGL((k_wgrad9<NTV, KCV, true>), grid, dim3(NTV * 64), 0, st, wg, io);    \
+    else                                                                                      \
+      hipLaunchKernelGGL((k_wgrad9<NTV, KCV, false>), grid, dim3(NTV * 64), 0, st, wg, io);   \
+  } while (0)
+#define WG9_CASE(NTV)          \
+  case NTV:                    \
+    if (wg.W == 8)             \
+      WG9_LAUNCH(NTV, 8);      \
+    else                       \
+      WG9_LAUNCH(NTV, 16);     \
     break
   switch (nt) {
     WG9_CASE(2);
@@ -325,5 +365,6 @@ hipError_t launch_wgrad9(hipStream_t st, int replicas, const ConvGeom &g, const 
     default: return hipErrorInvalidValue;
   }
 #undef WG9_CASE
+#undef WG9_LAUNCH
   return hipGetLastError();
 }

@@ -83,6 +83,7 @@ struct Net {
   // All of a network's bias gradients or none: networks of small layers (LeNet, the MLP) lose more to the extra
   // events than the stream hides (+4 %), and a mix of both placements measured worst of all.
   bool bias_stream = false;
+  bool bias_in_wgrad = true;  // PARLE_BIAS_IN_WGRAD=0: every bias gradient by its own column-sum kernels
   // Wavefronts a weight-gradient launch of the nine-tap kernel puts in flight.  Where batch-norm passes share
   // the chain of input gradients, that chain is the longer one and the leaves have slack: they take half the
   // chip's SIMDs and leave the rest to the chain (WRN-16-4 -3 %); without batch-norm the leaves are the longer
@@ -387,6 +388,8 @@ bool build_plan(Net &N, std::string &err) {
       if (op.type == OP_CONV && op.bseg >= 0 && op.need_dx)
         ++with_bias, large += (int64_t)N.B * op.Ho * op.Wo * op.Cout >= (1LL << 20) ? 1 : 0;
     N.bias_stream = with_bias >= 2 && 2 * large > with_bias;
+    const char *e = getenv("PARLE_BIAS_IN_WGRAD");
+    N.bias_in_wgrad = !(e && atoi(e) == 0);
   }
   // two kinds of tables: layers whose rows fill whole 16-byte vectors (tiled, vector kernel) and the rest
   for (int vec = 1; vec >= 0; --vec) {
@@ -652,9 +655,14 @@ hipError_t backward(const Run &r, float *grad) {
           HIP_TRY(launch_dgrad(N.ops[op.join], lst));
           if (N.side) HIP_TRY(hipEventRecord(N.br_dx[op.join], N.side));
         }
-        // the weight-gradient kernel of this layer takes the bias gradient along (a first layer in fp32 with a
-        // window of fewer than 32 values): the bias segment follows the weight segment in the parameter row
-        const bool bias_in_wgrad = op.bseg >= 0 && wgrad_takes_bias(N.dtype, gf) &&
+        // the weight-gradient kernel of this layer takes the bias gradient along where it can (it reads all of dy
+        // anyway): the bias segment follows the weight segment in the parameter row
+        WgradIO io{};
+        io.dy = dy, io.dy_rs = dy_rs;
+        io.x = r.tptr(op.in), io.x_rs = r.trs(op.in);
+        io.pairA = (op.Cout % 2 == 0) && aligned_to(dy, 4);
+        io.pairB = (op.Cin % 2 == 0) && aligned_to(io.x, 4);
+        const bool bias_in_wgrad = op.bseg >= 0 && N.bias_in_wgrad && wgrad_takes_bias(N.dtype, gf, io) &&
                                    N.segs[op.bseg].offset == N.segs[op.wseg].offset + N.segs[op.wseg].size;
         if (op.bseg >= 0 && !bias_in_wgrad) {
           hipStream_t bst = lst;
@@ -666,14 +674,9 @@ hipError_t backward(const Run &r, float *grad) {
                                    grad + N.segs[op.bseg].offset, r.p_rs));
         }
         {
-          WgradIO io{};
-          io.dy = dy, io.dy_rs = dy_rs;
-          io.x = r.tptr(op.in), io.x_rs = r.trs(op.in);
           int chunk = 0;
           const int S = wgrad_plan(N.dtype, r.n, gf, &chunk);
           io.splits = S, io.chunk = chunk;
-          io.pairA = (op.Cout % 2 == 0) && aligned_to(dy, 4);
-          io.pairB = (op.Cin % 2 == 0) && aligned_to(io.x, 4);
           io.with_bias = bias_in_wgrad;
           const int64_t wsize = N.segs[op.wseg].size + (bias_in_wgrad ? op.Cout : 0);  // values per (replica, split)
           if (S == 1) {

@@ -56,6 +56,33 @@ def oracle_conv(x, w, bias, resid, relu, stride, pad, dy=None, mask_relu_input=F
     return o.v, xv.g, wv.g
 
 
+def oracle_bias_grad(x, w_shape, dy, stride, pad):
+    """Gradient of the layer's bias under the output gradient dy, by the oracle's convolution backward."""
+    t = onets.Tape()
+    bv = onets.Var(np.zeros(w_shape[0]))
+    o = onets.conv2d(t, onets.Var(x.astype(np.float64)), onets.Var(np.zeros(w_shape)), bv, stride, pad)
+    o.g = dy.astype(np.float64)
+    t.backward()
+    return bv.g
+
+
+def check_weight_and_bias_gradient(torch, pb, desc, dy_dev, x_dev, gw):
+    """The form that takes the bias gradient along: same weight gradient; returns the bias part
+    [n][cout] (None when the kernel that runs this layer leaves it to the caller, then untouched)."""
+    n, Cout = desc.n, desc.cout
+    wsize = Cout * desc.k * desc.k * desc.cin
+    scratch = torch.zeros(max(pb.parle_k_conv_scratch_bytes(desc) // 4, 4), dtype=torch.float32, device="cuda")
+    gwb = torch.full((n, wsize + Cout), float("nan"), dtype=torch.float32, device="cuda")
+    took = pb.parle_k_conv_backward_weight_bias(desc, dy_dev, x_dev, scratch, gwb)
+    torch.cuda.synchronize()
+    # the same kernel; only the grouping of the split sums may differ with the row length (16-byte vectors or not)
+    assert float((gwb[:, :wsize] - gw.reshape(n, wsize)).abs().max()) <= 2e-6 * float(gw.abs().max())
+    if not took:
+        assert bool(torch.isnan(gwb[:, wsize:]).all())
+        return None
+    return download(gwb[:, wsize:])
+
+
 CASES = [
     # n, B, H, W, Cin, Cout, k, stride, pad
     (2, 3, 9, 7, 3, 10, 3, 1, 1),       # scalar gathers, narrow output
@@ -97,6 +124,19 @@ CASES = [
     (3, 128, 1, 1, 784, 128, 1, 1, 0),  # the MLP's first layer: contraction split over the wavefronts of a workgroup
     (2, 20, 1, 1, 504, 10, 1, 1, 0),    # same, ten outputs, contraction not a multiple of the four quarters
 ]
+
+
+def _takes_bias(case, dtype):
+    """Layers whose weight-gradient kernel also writes the bias gradient: the small first-layer kernels when the
+    window leaves one of their 32 contraction columns free, and in bf16 the stride-1 3x3 kernel and the
+    transpose-read kernel (channel counts that are multiples of 8, at least 32 outputs)."""
+    n, B, H, W, Cin, Cout, k, stride, pad = case
+    K = k * k * Cin
+    if dtype == 0:
+        return K < 32 and Cout <= 32
+    if K <= 32 and Cout % 8 == 0:
+        return K < 32
+    return Cin % 8 == 0 and Cout % 8 == 0 and Cout >= 32
 
 
 def tolerances(dtype, ref):
@@ -150,8 +190,13 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
     gw = torch.zeros((n, Cout, k, k, Cin), dtype=torch.float32, device="cuda")
     pb.parle_k_conv_backward_weight(desc, ddy, dx_, scratch, gw)
     torch.cuda.synchronize()
+    gb = check_weight_and_bias_gradient(torch, pb, desc, ddy, dx_, gw)
+    assert (gb is not None) == _takes_bias(case, dtype), "which kernels take the bias gradient along changed"
 
     for r in range(n):
+        if gb is not None:
+            rdb = oracle_bias_grad(x[r], w[r].shape, dy[r], stride, pad)
+            assert_near(f"bias gradient[{r}]", gb[r], rdb, 0.0, 2e-5 * np.abs(dy[r]).sum(axis=(0, 1, 2)).max())
         ref1, rdx, rdw = oracle_conv(x[r], w[r], None, None, False, stride, pad, dy[r])
         ref2, _, _ = oracle_conv(x[r], w[r], bias[r], resid[r], True, stride, pad)
         assert_near(f"fwd[{r}]", download(y1[r]), ref1, *tolerances(dtype, ref1))
@@ -276,3 +321,11 @@ def test_full_size_layers_sampled(gpu, layer):
         sub = got[cos][:, :, :, cis]
         assert np.abs(rdw).max() > 0.2 * scale                       # the sample is not a corner of small entries
         assert_near("wgrad", sub, rdw, 1e-5, 2e-5 * scale)
+    gb = check_weight_and_bias_gradient(torch, pb, desc, dy, x, gw)
+    assert (gb is not None) == _takes_bias(layer[1:], dtype)
+    if gb is not None:
+        for r in (0, n - 1):
+            cos = np.sort(rng.choice(Cout, size=min(Cout, 6), replace=False))
+            dys = download(dy[r][..., cos])
+            rdb = oracle_bias_grad(download(x[r][..., :1]), (len(cos), k, k, 1), dys, stride, pad)
+            assert_near("bias gradient", gb[r][cos], rdb, 0.0, 2e-5 * np.abs(dys).sum(axis=(0, 1, 2)).max())
