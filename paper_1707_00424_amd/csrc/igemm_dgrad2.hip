@@ -12,6 +12,8 @@
 //   a = 0: r = 1, di = 0;   a = 1: r = 0, di = 1 and r = 2, di = 0   (columns alike)
 // The four wavefronts write the interleaved pixels of the same rows at the same time, so whole lines form in
 // L2, and they share one staged patch of dy for all their shifted taps.
+#include <stdlib.h>
+
 #include "igemm_dev.h"
 
 namespace {
@@ -35,7 +37,7 @@ constexpr int dgrad_lds_bytes() {
 }
 
 template <int TN>
-__global__ __launch_bounds__(kThreads) void k_dgrad_s2(const ConvGeom g, const GemmIO io) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) void k_dgrad_s2(const ConvGeom g, const GemmIO io, const int rot_mask) {
   typedef bf16_t T;
   constexpr int TM = 2, BN = TN * 32;
   constexpr int H_IT = (kPatchSlots * 4 + kThreads - 1) / kThreads;  // 16-byte vectors per thread: patch
@@ -46,7 +48,14 @@ __global__ __launch_bounds__(kThreads) void k_dgrad_s2(const ConvGeom g, const G
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z, tile = blockIdx.x, n0 = blockIdx.y * BN;
-  const int a = wave >> 1, c = wave & 1;  // parity class of this wavefront's pixels
+  // Parity class of this wavefront's pixels.  Wavefront i of every workgroup lands on SIMD i, and the classes differ
+  // in work (1, 2, 2, 4 taps): the assignment rotates with the tile so that no SIMD collects the four-tap class of
+  // every workgroup on its compute unit.
+  // (workgroup ids 8 apart share an XCD: the rotation is taken from the id within the XCD, mixed so that neither
+  // a round-robin over the 32 compute units nor a blocked assignment lines the classes up again)
+  const int kx = tile >> 3;
+  const int cls = (wave + ((kx + (kx >> 2) + (kx >> 5)) & rot_mask)) & 3;
+  const int a = cls >> 1, c = cls & 1;
   const int row_l = lane & 31, h = lane >> 5;
   const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void *)((const T *)io.in + rep * io.in_rs), 0, (int)(io.in_bytes), 0x00020000);
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void k_dgrad_s2(const ConvGeom g, const G
     }
   }
 
-  store_tile_lds<T, TM, TN, false>(g, io, rep, tile * 256 + wave * 64, n0, lane, acc,
+  store_tile_lds<T, TM, TN, false>(g, io, rep, tile * 256 + cls * 64, n0, lane, acc,
                                    reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>);
 }
 
@@ -163,7 +172,11 @@ int exact_log2(int v) {
 template <int TN>
 hipError_t run_dgrad_s2(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io) {
   dim3 grid(g.M / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
-  hipLaunchKernelGGL((k_dgrad_s2<TN>), grid, dim3(kThreads), 0, st, g, io);
+  static const int rot = [] {
+    const char *e = getenv("PARLE_S2_ROT");
+    return e ? atoi(e) : 3;
+  }();
+  hipLaunchKernelGGL((k_dgrad_s2<TN>), grid, dim3(kThreads), 0, st, g, io, rot);
   return hipGetLastError();
 }
 

@@ -183,8 +183,11 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any per-replica tensor (each i
 
 // STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
 // row per row tile.
+// (the widest tiles are held to two wavefronts per SIMD: left alone, their epilogue variants take more than 256
+// registers and a compute unit then holds one workgroup)
 template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32, bool STAT = false>
-__global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const GemmIO io) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TM * TN >= 8 ? 2 : 1))) void k_igemm_u(
+    const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;
   constexpr int LK = BK + VW;
@@ -289,28 +292,36 @@ __global__ __launch_bounds__(kThreads) void k_igemm_u(const ConvGeom g, const Ge
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.f;
 
-  // two-step-deep software pipeline, unrolled by two (see k_igemm_v)
-  u4 a0[A_IT], b0[B_IT], a1[A_IT], b1[B_IT];
-  load_tiles(a0, b0);
-  advance_k();
-  load_tiles(a1, b1);
-  store_tiles(0, a0, b0);
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 1 < KT; kt += 2) {
-    advance_k();
-    load_tiles(a0, b0);
-    mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
-    store_tiles(1, a1, b1);
-    __syncthreads();
-    advance_k();
-    load_tiles(a1, b1);
-    mma_tile_t<T, TM, TN, LK, VW>(As[1], Bs[1], wm * TM * 32, wn * TN * 32, lane, acc);
-    store_tiles(0, a0, b0);
-    __syncthreads();
+  // Software pipeline: LDS is double-buffered, and D steps travel from memory in registers.  Memory answers in more
+  // cycles than a step multiplies (a step is TM*TN*2 MFMAs per wavefront), so the tile stored to LDS in step t was
+  // requested in step t - D + 1: with two register sets every step waited out most of a memory round trip.
+  constexpr int D = (A_IT + B_IT) * TM * TN <= 24 ? 4 : 3;
+  u4 ra[D][A_IT], rb[D][B_IT];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    if (i) advance_k();
+    load_tiles(ra[i], rb[i]);  // steps past the end load nothing
   }
-  if (kt < KT) mma_tile_t<T, TM, TN, LK, VW>(As[0], Bs[0], wm * TM * 32, wn * TN * 32, lane, acc);
-  __syncthreads();  // operand tiles are dead: their LDS becomes the staging strips
+  store_tiles(0, ra[0], rb[0]);
+  __syncthreads();
+  // step t: set `cur` held tile t (in LDS since the previous step) and is refilled with tile t + D; set `nxt`
+  // holds tile t + 1, which goes to the other LDS buffer
+  auto step = [&](int t, u4 (&ca)[A_IT], u4 (&cb)[B_IT], const u4 (&na)[A_IT], const u4 (&nb)[B_IT]) {
+    advance_k();
+    load_tiles(ca, cb);
+    mma_tile_t<T, TM, TN, LK, VW>(As[t & 1], Bs[t & 1], wm * TM * 32, wn * TN * 32, lane, acc);
+    store_tiles((t + 1) & 1, na, nb);
+    __syncthreads();
+  };
+  int kt = 0;
+  for (; kt + D - 1 < KT; kt += D) {
+#pragma unroll
+    for (int i = 0; i < D; ++i) step(kt + i, ra[i], rb[i], ra[(i + 1) % D], rb[(i + 1) % D]);
+  }
+#pragma unroll
+  for (int i = 0; i < D - 1; ++i)
+    if (kt + i < KT) step(kt + i, ra[i], rb[i], ra[(i + 1) % D], rb[(i + 1) % D]);
+  // the barrier that ended the last step: operand tiles are dead, their LDS becomes the staging strips
   // sums of wavefront (wm, wn): row wm of [WAVES_M][2][BN], columns wn * TN * 32 ...
   float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
   store_tile_lds<T, TM, TN, OUT_F32, STAT>(g, io, rep, m0 + wm * TM * 32, n0 + wn * TN * 32, lane, acc,
