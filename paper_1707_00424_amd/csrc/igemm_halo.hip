@@ -12,6 +12,11 @@
 // Step order: channel chunk outer, tap inner (the contraction order is free).  The weight tile of
 // each step is double-buffered in LDS with a two-step register prefetch; the next chunk's patch
 // is prefetched into registers during the R*S steps of the current one.
+//
+// Stride-2 3x3 layers (forward) run the same body on 128 output pixels per workgroup: their patch is
+// (2 rows + 1) x (2 width + 1) input pixels, four times the output tile, and every input pixel is under some tap, so
+// staging the patch once reads the input exactly once, in whole rows; a kernel that gathers the rows of each tap
+// from memory reads 64-byte pieces 2 pixels apart, nine times over, and is bound by that.
 #include <stdlib.h>
 
 #include "igemm_dev.h"
@@ -21,7 +26,8 @@ namespace {
 using namespace igemm_dev;
 
 constexpr uint32_t kOob = 0x80000000u;
-constexpr int kHaloSlots = 400;  // LDS patch capacity in pixels (32 KB at 32 channels + padding)
+constexpr int kHaloSlots = 400;    // LDS patch capacity in pixels (32 KB at 32 channels + padding)
+constexpr int kHaloSlotsS2 = 592;  // stride 2: 17 x 33 (16 output columns) or 2 x 17 x 17 (two 8 x 8 outputs), 47 KB
 
 struct HaloGeom {
   int TH;          // output rows of one image inside a tile
@@ -36,24 +42,25 @@ struct HaloGeom {
 // LDS of a workgroup with TN column tiles: patch + a ring of three weight tiles; the epilogue reuses the same
 // bytes as its staging strips
 // with STAT, the column sums of the four wavefronts (2 x TN*32 floats each) lie behind the strips
-template <int TN, bool STAT = false>
+template <int TN, bool STAT = false, int SLOTS = kHaloSlots>
 constexpr int halo_lds_bytes() {
-  constexpr int pipe = (kHaloSlots + 3 * TN * 32) * (32 + 8) * 2;
+  constexpr int pipe = (SLOTS + 3 * TN * 32) * (32 + 8) * 2;
   constexpr int stage = 4 * kStageFloats<TN> * (int)sizeof(float) + (STAT ? 4 * 2 * TN * 32 * (int)sizeof(float) : 0);
   return pipe > stage ? pipe : stage;
 }
 
 // `tile`, `col`: pixel tile and column block of this workgroup; column blocks before it are hg.bn wide.
-template <int TN, bool STAT>
+// TM: 32-pixel tiles per wavefront (the workgroup's tile is TM * 128 output pixels); SLOTS: patch capacity; SP: stride.
+template <int TN, bool STAT, int TM = 2, int SLOTS = kHaloSlots, int SP = 1>
 __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &io, const HaloGeom &hg, char *smem,
                                                int tile, int col) {
   typedef bf16_t T;
   constexpr int VW = 8, BK = 32, LK = BK + VW;
-  constexpr int TM = 2, BM = 256, BN = TN * 32;  // four wavefronts stacked along the pixel axis
+  constexpr int BM = TM * 128, BN = TN * 32;  // four wavefronts stacked along the pixel axis
   constexpr int B_IT = (BN + 63) / 64;
-  constexpr int H_IT = (kHaloSlots * 4 + kThreads - 1) / kThreads;
+  constexpr int H_IT = (SLOTS * 4 + kThreads - 1) / kThreads;
   T *Hs = reinterpret_cast<T *>(smem);
-  T *Bs = reinterpret_cast<T *>(smem + kHaloSlots * LK * sizeof(T));  // tile i of the ring at Bs + i * BN * LK
+  T *Bs = reinterpret_cast<T *>(smem + SLOTS * LK * sizeof(T));  // tile i of the ring at Bs + i * BN * LK
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
@@ -76,7 +83,7 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
     if (slot < hg.slots) {
       const int img = (int)fdiv((uint32_t)slot, hg.dImg), rem = slot - img * hg.HR * hg.HC;
       const int hh = (int)fdiv((uint32_t)rem, hg.dHC), ww = rem - hh * hg.HC;
-      const int b = b0 + img, ih = p0 + hh + hg.omin_h, iw = ww + hg.omin_w;
+      const int b = b0 + img, ih = SP * p0 + hh + hg.omin_h, iw = ww + hg.omin_w;
       if ((b * PQ < g.M) && ih >= 0 && ih < g.Hin && iw >= 0 && iw < g.Win)
         off = (uint32_t)((((b * g.Hin + ih) * g.Win + iw) * g.Cc + (v & 3) * VW) * (int)sizeof(T));
     }
@@ -95,7 +102,7 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
     const int ml = wave * (TM * 32) + tm * 32 + (lane & 31);
     const int img = (int)fdiv((uint32_t)ml, hg.dRows), rem = ml - img * hg.TH * g.Q;
     const int ph = (int)fdiv((uint32_t)rem, g.dQ), pw = rem - ph * g.Q;
-    a_lds[tm] = (((img * hg.HR + ph) * hg.HC + pw) * LK + (lane >> 5) * VW);
+    a_lds[tm] = (((img * hg.HR + SP * ph) * hg.HC + SP * pw) * LK + (lane >> 5) * VW);
   }
   const int b_lds = (lane & 31) * LK + (lane >> 5) * VW;
 
@@ -112,7 +119,7 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
 #pragma unroll
     for (int it = 0; it < H_IT; ++it) {
       const int v = it * kThreads + tid;
-      if (v < kHaloSlots * 4) *(u4 *)&Hs[(v >> 2) * LK + (v & 3) * VW] = hreg[it];
+      if (v < SLOTS * 4) *(u4 *)&Hs[(v >> 2) * LK + (v & 3) * VW] = hreg[it];
     }
   };
   // weight tile of step t: channels of chunk t / RS at tap t % RS
@@ -243,7 +250,7 @@ __device__ __forceinline__ void conv_halo_body(const ConvGeom &g, const GemmIO &
   float *wsums = reinterpret_cast<float *>(smem) + 4 * kStageFloats<TN>;
   store_tile_lds<T, TM, TN, false, STAT>(g, io, rep, m0 + wave * TM * 32, n0, lane, acc,
                                          reinterpret_cast<float *>(smem) + wave * kStageFloats<TN>, wsums + wave * 2 * BN);
-  // the workgroup's 256 rows: one partial row per pixel tile
+  // the workgroup's rows: one partial row per pixel tile
   if (STAT) write_tile_sums<BN, 4>(g, io, rep, hg.tiles, tile, n0, tid, wsums);
 }
 
@@ -282,13 +289,37 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3))) v
   conv_halo_body<2, STAT>(g, io, hg, smem, tile, col);
 }
 
+// Stride 2 (forward): 128 output pixels per workgroup, one 32-pixel tile per wavefront.
+template <int TN, int TL, bool STAT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2))) void k_conv_halo_s2(const ConvGeom g, const GemmIO io,
+                                                                                                  const HaloGeom hg) {
+  __shared__ __attribute__((aligned(16))) char smem[halo_lds_bytes<TN, STAT, kHaloSlotsS2>()];
+  int tile, col;
+  if (!halo_block(hg, tile, col)) return;
+  if (TL != TN && col == hg.nb - 1)
+    conv_halo_body<TL, STAT, 1, kHaloSlotsS2, 2>(g, io, hg, smem, tile, col);
+  else
+    conv_halo_body<TN, STAT, 1, kHaloSlotsS2, 2>(g, io, hg, smem, tile, col);
+}
+
 // grid of `tiles` pixel tiles x `nb` column blocks of `bn` channels (the last may be narrower), laid out in
 // groups of 8 tiles (see halo_block)
 dim3 halo_grid(const ConvGeom &g, int bn, int replicas, HaloGeom &hg) {
-  hg.tiles = (g.M + 255) / 256;
+  const int bm = g.sp == 2 ? 128 : 256;
+  hg.tiles = (g.M + bm - 1) / bm;
   hg.bn = bn;
   hg.nb = (g.N + bn - 1) / bn;
   return dim3((hg.tiles + 7) / 8 * 8 * hg.nb, 1, replicas);
+}
+
+template <int TN, int TL>
+hipError_t run_halo_s2(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io, HaloGeom hg) {
+  const dim3 grid = halo_grid(g, TN * 32, replicas, hg);
+  if (TN != 3 && io.stat)
+    hipLaunchKernelGGL((k_conv_halo_s2<TN, TL, TN != 3>), grid, dim3(kThreads), 0, st, g, io, hg);
+  else
+    hipLaunchKernelGGL((k_conv_halo_s2<TN, TL, false>), grid, dim3(kThreads), 0, st, g, io, hg);
+  return hipGetLastError();
 }
 
 template <int TN, int TL>
@@ -302,8 +333,21 @@ hipError_t run_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmI
 }
 
 bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
-  const int BM = 256;
-  if (g.sp != 1 || g.dshift != 0 || g.P != g.Hin || g.Q != g.Win) return false;
+  const bool s2 = g.sp == 2;
+  const int BM = s2 ? 128 : 256;
+  if (g.dshift != 0) return false;
+  if (s2) {  // forward 3x3, padding 1, even image
+    // with few input channels a workgroup is mostly prologue and epilogue, and the kernel that gathers per tap, at
+    // three workgroups per compute unit instead of two, is as fast or faster (96 channels: 38 against 44 us)
+    static const int min_c = [] {
+      const char *e = getenv("PARLE_HALO_S2_MINC");
+      return e ? atoi(e) : 128;
+    }();
+    if (g.Cc < min_c) return false;
+    if (g.R != 3 || g.S != 3 || g.off != -1 || g.sr != 1 || 2 * g.P != g.Hin || 2 * g.Q != g.Win) return false;
+  } else if (g.sp != 1 || g.P != g.Hin || g.Q != g.Win) {
+    return false;
+  }
   if (BM % g.Q != 0) return false;
   const int PQ = g.P * g.Q;
   if (PQ >= BM) {
@@ -313,14 +357,14 @@ bool make_halo_geom(const ConvGeom &g, HaloGeom &hg) {
     if (BM % PQ != 0) return false;
     hg.TH = g.P, hg.nimg = BM / PQ;
   }
-  hg.HR = hg.TH + g.R - 1, hg.HC = g.Q + g.S - 1;
+  hg.HR = g.sp * (hg.TH - 1) + g.R, hg.HC = g.sp * (g.Q - 1) + g.S;
   hg.slots = hg.nimg * hg.HR * hg.HC;
   hg.dImg = make_fastdiv(hg.HR * hg.HC), hg.dHC = make_fastdiv(hg.HC), hg.dRows = make_fastdiv(hg.TH * g.Q);
   const int o_first = g.off, o_last = g.off + (g.R - 1) * g.sr;
   hg.omin_h = o_first < o_last ? o_first : o_last;
   const int w_first = g.off, w_last = g.off + (g.S - 1) * g.sr;
   hg.omin_w = w_first < w_last ? w_first : w_last;
-  return hg.slots <= kHaloSlots;
+  return hg.slots <= (s2 ? kHaloSlotsS2 : kHaloSlots);
 }
 
 }  // namespace
@@ -344,6 +388,10 @@ enum HaloVariant { kHalo64, kHalo96, kHalo128 };
 HaloVariant halo_variant(const ConvGeom &g, int replicas) {
   constexpr int kCus = 256;
   const int n = g.N;
+  if (g.sp == 2) {  // 128-pixel tiles: one width rule
+    if (n <= 64) return kHalo64;
+    return (n + 95) / 96 * 96 < (n + 127) / 128 * 128 ? kHalo96 : kHalo128;
+  }
   const long long tiles = (g.M + 255) / 256, wide = tiles * ((n + 127) / 128) * replicas,
                   narrow_wgs = tiles * (n / 64) * replicas;
   const bool narrow = n % 64 == 0 && wide < 2 * kCus && narrow_wgs > 2 * kCus && narrow_wgs <= 3 * kCus;
@@ -359,13 +407,28 @@ HaloVariant halo_variant(const ConvGeom &g, int replicas) {
 // sums cost more than the reduction pass they replace (160 channels on 32 x 32 images: +0.5 % per step against
 // -0.7 % for the other layers of the same network).
 int conv_halo_stat_splits(const ConvGeom &g, int replicas) {
-  return halo_variant(g, replicas) == kHalo96 ? 0 : (g.M + 255) / 256;
+  const int bm = g.sp == 2 ? 128 : 256;
+  return halo_variant(g, replicas) == kHalo96 ? 0 : (g.M + bm - 1) / bm;
 }
 
 hipError_t launch_conv_halo(hipStream_t st, int replicas, const ConvGeom &g, const GemmIO &io) {
   HaloGeom hg;
   if (!make_halo_geom(g, hg)) return hipErrorInvalidValue;
   const int n = g.N;
+  if (g.sp == 2) {
+    switch (halo_variant(g, replicas)) {
+      case kHalo64: return run_halo_s2<2, 2>(st, replicas, g, io, hg);
+      case kHalo96: {
+        if (io.stat) return hipErrorInvalidValue;
+        const int last = n - ((n + 95) / 96 * 96 - 96);
+        return last <= 64 ? run_halo_s2<3, 2>(st, replicas, g, io, hg) : run_halo_s2<3, 3>(st, replicas, g, io, hg);
+      }
+      default: {
+        const int last = n - ((n + 127) / 128 * 128 - 128);
+        return last <= 64 ? run_halo_s2<4, 2>(st, replicas, g, io, hg) : run_halo_s2<4, 4>(st, replicas, g, io, hg);
+      }
+    }
+  }
   switch (halo_variant(g, replicas)) {
     case kHalo64: {
       const dim3 grid = halo_grid(g, 64, replicas, hg);

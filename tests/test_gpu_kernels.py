@@ -121,6 +121,9 @@ CASES = [
     (1, 2, 8, 8, 32, 10, 2, 1, 0),      # 2x2 window, no padding
     (2, 5, 12, 12, 20, 50, 5, 1, 0),    # LeNet's second convolution: fp32 backward-data with the per-tap products in LDS
     (1, 3, 7, 9, 6, 13, 3, 1, 1),       # same path, padded 3x3 window, odd sizes (63 output pixels, 13 output channels)
+    (2, 3, 16, 16, 128, 96, 3, 2, 1),   # stride-2 forward with the input patch in LDS (128 channels or more): two 8 x 8 outputs per tile, odd batch
+    (1, 4, 32, 32, 136, 128, 3, 2, 1),  # same, 16 output columns (half an image per tile), a ragged channel chunk
+    (1, 2, 32, 32, 128, 320, 3, 2, 1),  # same, 320 outputs = 128 + 128 + 64
     (3, 128, 1, 1, 784, 128, 1, 1, 0),  # the MLP's first layer: contraction split over the wavefronts of a workgroup
     (2, 20, 1, 1, 504, 10, 1, 1, 0),    # same, ten outputs, contraction not a multiple of the four quarters
 ]
@@ -217,6 +220,8 @@ def test_conv_kernels_match_oracle(gpu, case, dtype):
     ((3, 128, 8, 8, 256, 256, 3, 1, 1), True),    # WRN-16-4 group 3 at full size
     ((2, 4, 16, 16, 32, 160, 3, 1, 1), False),    # 96-wide blocks: no sums, the caller reduces
     ((2, 4, 16, 16, 32, 64, 3, 2, 1), False),     # stride 2, 64 outputs: a tile shape that takes none
+    ((2, 5, 16, 16, 128, 64, 3, 2, 1), True),     # stride 2 with the patch in LDS (128 input channels or more): 64-wide blocks, odd batch
+    ((1, 6, 16, 16, 160, 320, 3, 2, 1), True),    # same, 320 outputs = 128 + 128 + a 64-wide last block
     ((2, 5, 16, 16, 64, 128, 3, 2, 1), True),     # stride 2 (first convolution of a group): 128-row tiles, 2 x 2 wavefronts
     ((1, 6, 16, 16, 32, 320, 3, 2, 1), True),     # same, 320 outputs = 256 + a ragged second block
     ((3, 128, 32, 32, 64, 128, 3, 2, 1), True),   # WRN-16-4 group 2's first convolution at full size
