@@ -36,7 +36,8 @@ struct GatherVec<8> {
 // GB: bytes per gather (16, or 8 for channel counts that are only a multiple of half a vector, e.g. 50 fp32
 // channels); the LDS layout and the fragment reads are the same for both.
 template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32, int GB>
-__global__ __launch_bounds__(kThreads) void k_igemm_v(const ConvGeom g, const GemmIO io) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TM * TN >= 8 ? 2 : 1))) void k_igemm_v(
+    const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);   // elements per fragment read
   constexpr int GV = GB / sizeof(T);   // elements per gather
   constexpr int BK = 4 * VW;
@@ -183,10 +184,11 @@ constexpr uint32_t kOob = 0x80000000u;  // beyond any per-replica tensor (each i
 
 // STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
 // row per row tile.
-// (the widest tiles are held to two wavefronts per SIMD: left alone, their epilogue variants take more than 256
-// registers and a compute unit then holds one workgroup)
+// (register budgets: the widest tiles are held to two wavefronts per SIMD - left alone, their epilogue variants take
+// more than 256 registers and a compute unit then holds one workgroup - and the 128 x 64 and 128 x 128 tiles, which
+// came out a few registers above 168, to three)
 template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool OUT_F32, bool STAT = false>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TM * TN >= 8 ? 2 : 1))) void k_igemm_u(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TM * TN >= 8 ? 2 : (TM * TN == 2 || (TM * TN == 4 && WAVES_M == 2) ? 3 : 1)))) void k_igemm_u(
     const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;
@@ -348,8 +350,10 @@ __device__ __forceinline__ u4 lds_tr_frag(const bf16_t *tile, int ld, int krow, 
 
 // BIAS: the workgroups of the first column tile also sum the dy vectors they stage and write the layer's bias
 // gradient, the column sums of dy, behind the weights.
+// (the 256 x 128 tile is held to two wavefronts per SIMD: at 264 registers a compute unit held one workgroup)
 template <int WAVES_M, int WAVES_N, int TM, int TN, bool BIAS>
-__global__ __launch_bounds__(kThreads) void k_wgrad_tr(const ConvGeom g, const WgradIO io) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(TM * TN >= 8 ? 2 : 1))) void k_wgrad_tr(
+    const ConvGeom g, const WgradIO io) {
   constexpr int BKM = 32;  // pixels per contraction step
   constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
   constexpr int LDA = BM + 16, LDB = BN + 16;  // row strides = 32 (mod 128) bytes: conflict-free transpose reads

@@ -29,9 +29,10 @@ __device__ __forceinline__ float buffer_load_elem<float>(__amdgpu_buffer_rsrc_t 
 }
 
 // STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
-// row per workgroup.
+// row per workgroup.  (The 64-wide bf16 variant came out at 172 registers, four over the budget of three wavefronts
+// per SIMD: it is held to that budget.)
 template <typename T, int TN, bool OUT_F32, bool STAT>
-__global__ __launch_bounds__(kThreads) void k_conv_smallk(const ConvGeom g, const GemmIO io) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 2 && TN == 2 && !OUT_F32 ? 3 : 1))) void k_conv_smallk(const ConvGeom g, const GemmIO io) {
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;               // one contraction step of the MFMA helper: 32 bf16 / 16 fp32
   constexpr int STEPS = kKP / BK;          // 1 / 2
