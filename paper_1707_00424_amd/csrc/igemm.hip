@@ -458,7 +458,15 @@ int wgrad_plan(int dtype, int replicas, const ConvGeom &g, int *chunk_out) {
     return v > 0 ? v : 512;
   }();
   // at most `target` workgroups: two per compute unit, never a few stragglers in a third round
-  long long want = target / tiles;
+  // (the one-tile fp32 kernel is bound by the round trips of its operand loads, has few registers and writes a
+  // 32 x 32 tile per split: it takes more, smaller splits)
+  static const int target_small = [] {
+    const char *e = getenv("PARLE_WGRAD_SMALL_BLOCKS");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 1024;
+  }();
+  const bool small_f32 = !wgrad_smallk_applicable(dtype, g) && wgrad_small_f32_applicable(dtype, g);
+  long long want = (small_f32 ? target_small : target) / tiles;
   if (want > steps / 4) want = steps / 4;             // keep >= 4 steps (128 rows) per split
   if (want < 1) want = 1;
   const long long cap = 65535 / replicas;

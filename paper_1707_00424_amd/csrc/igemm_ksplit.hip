@@ -140,9 +140,9 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, 
   f16v acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  // operands of U MFMAs per batch; the next batch is requested before the current one is multiplied
   constexpr int U = 8;
-  for (int mj = m0; mj < m1; mj += 2 * U) {
-    float av[U], bv[U];
+  auto load_batch = [&](float (&av)[U], float (&bv)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool live = m < m1;
@@ -157,8 +157,16 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_small_f32(const ConvGeom g, 
         if (++p == g.P) p = 0, ++b;
       }
     }
+  };
+  float a0[U], b0[U], a1[U], b1[U];
+  load_batch(a0, b0);
+  for (int mj = m0; mj < m1; mj += 4 * U) {
+    load_batch(a1, b1);  // rows at or beyond m1 load nothing
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv[u], acc, 0, 0, 0);
+    for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b0[u], acc, 0, 0, 0);
+    load_batch(a0, b0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b1[u], acc, 0, 0, 0);
   }
   if (wave) {
 #pragma unroll
