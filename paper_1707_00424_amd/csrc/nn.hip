@@ -917,6 +917,27 @@ __global__ __launch_bounds__(kThreads) void k_reduce_partials_v(int S, long long
   }
 }
 
+// Few splits: one thread per vector of four columns adds all of them in order, eight loads in flight; no LDS, no
+// barrier, a quarter of the workgroups.
+__global__ __launch_bounds__(kThreads) void k_reduce_partials_t(int S, long long len4, const f4 *__restrict__ partial,
+                                                                f4 *__restrict__ out, long long out_rs4) {
+  const int rep = blockIdx.y;
+  const long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= len4) return;
+  const f4 *src = partial + (long long)rep * S * len4 + i;
+  f4 s = {0.f, 0.f, 0.f, 0.f};
+  int sp = 0;
+  for (; sp + 8 <= S; sp += 8) {
+    f4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + (long long)(sp + u) * len4);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; sp < S; ++sp) s += __builtin_nontemporal_load(src + (long long)sp * len4);
+  out[rep * out_rs4 + i] = s;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void k_weight_transpose(int Cout, int RS, int Cin, const T *__restrict__ w,
                                                                long long w_rs, T *__restrict__ wt, long long wt_rs) {
@@ -1303,6 +1324,15 @@ hipError_t launch_bias_grad(hipStream_t st, int dtype, int n, int M, int C, cons
 
 hipError_t launch_reduce_partials(hipStream_t st, int n, int S, long long len, const float *partial, float *out,
                                   long long out_rs) {
+  static const int t_max = [] {
+    const char *e = getenv("PARLE_REDUCE_T");  // splits up to which the one-thread-per-vector form runs
+    return e ? atoi(e) : 32;
+  }();
+  if (len % 4 == 0 && out_rs % 4 == 0 && aligned_to(partial, 16) && aligned_to(out, 16) && S <= t_max) {
+    hipLaunchKernelGGL(k_reduce_partials_t, dim3((unsigned)((len / 4 + kThreads - 1) / kThreads), n), dim3(kThreads), 0, st, S,
+                       len / 4, (const f4 *)partial, (f4 *)out, out_rs / 4);
+    return hipGetLastError();
+  }
   if (len % 4 == 0 && out_rs % 4 == 0 && aligned_to(partial, 16) && aligned_to(out, 16) && len / 4 / 64 < (1LL << 31)) {
     hipLaunchKernelGGL(k_reduce_partials_v, dim3((unsigned)((len / 4 + 63) / 64), n), dim3(kThreads), 0, st, S, len / 4,
                        (const f4 *)partial, (f4 *)out, out_rs / 4);
