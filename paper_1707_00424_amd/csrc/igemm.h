@@ -61,6 +61,10 @@ struct GemmIO {
   int relu, accumulate;
   int vecA, vecB;     // 16-byte loads allowed for the gathered operand / the weight matrix
   long long in_bytes; // bytes of one replica's gathered tensor (range of the buffer loads)
+  // The gathered tensor lies in memory as fp32 although the layer computes in bf16 (the caller's images in front of a
+  // first layer): values are rounded to bf16 as they are gathered.  Only the small-window kernel takes it;
+  // launch_igemm fails for a layer that kernel does not run.
+  int in_f32;
   // Column sums of the stored output and of its squares, per workgroup of pixel rows, for the batch-norm that
   // follows: [replica][S][2][ldc] doubles, or NULL.  Only launch_igemm's callers that ask for the split count
   // set it; kernels that do not produce the sums ignore it and launch_igemm reports S = 0.
@@ -81,6 +85,7 @@ struct WgradIO {
   // N*K weight-gradient values of `out`: N more floats per (replica, split).  In a parameter row the bias segment
   // follows the weight segment, so the one reduction over the splits, or the direct write, covers both.
   int with_bias;
+  int x_f32;  // x lies in memory as fp32 (see GemmIO::in_f32); only the small-window bf16 kernel takes it
 };
 
 // A convolution layer as the kernels see it: [B, H, W, Cin] -> [B, Ho, Wo, Cout], R x R window.

@@ -393,6 +393,7 @@ hipError_t launch_igemm(hipStream_t st, int dtype, bool out_f32, int replicas, c
   }
   GemmIO io = io_in;
   io.stat = nullptr;
+  if (io.in_f32 && !(dtype == 1 && !out_f32 && conv_smallk_applicable(dtype, g, io))) return hipErrorInvalidValue;
   if (conv_smallk_applicable(dtype, g, io)) return launch_conv_smallk(st, dtype, out_f32, replicas, g, io);
   if (conv_halo_applicable(dtype, g, io, out_f32)) return launch_conv_halo(st, replicas, g, io);
   if (dgrad_s2_applicable(dtype, g, io, out_f32)) return launch_dgrad_s2(st, replicas, g, io);
@@ -412,6 +413,7 @@ hipError_t launch_wgrad(hipStream_t st, int dtype, int replicas, const ConvGeom 
       io.chunk < 32 || (io.chunk & 31))
     return hipErrorInvalidValue;
   if (wgrad_smallk_applicable(dtype, g) && aligned_to(io.dy, 16)) return launch_wgrad_smallk(st, replicas, g, io);
+  if (io.x_f32) return hipErrorInvalidValue;  // only the kernel above reads fp32 memory for a bf16 layer
   if (wgrad_small_f32_applicable(dtype, g)) return launch_wgrad_small_f32(st, replicas, g, io);
   if (wgrad_window_applicable(dtype, g)) return launch_wgrad_window(st, replicas, g, io);
   if (wgrad9_applicable(dtype, g) && io.pairA && io.pairB) return launch_wgrad9(st, replicas, g, io);

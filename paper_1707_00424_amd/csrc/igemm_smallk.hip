@@ -31,8 +31,10 @@ __device__ __forceinline__ float buffer_load_elem<float>(__amdgpu_buffer_rsrc_t 
 // STAT: also the column sums of the output for the batch-norm behind the layer (see store_tile_lds), one partial
 // row per workgroup.  (The 64-wide bf16 variant came out at 172 registers, four over the budget of three wavefronts
 // per SIMD: it is held to that budget.)
-template <typename T, int TN, bool OUT_F32, bool STAT>
+// IN_F32 (bf16 layers): the gathered tensor is fp32 in memory, rounded to bf16 as it is gathered.
+template <typename T, int TN, bool OUT_F32, bool STAT, bool IN_F32 = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 2 && TN == 2 && !OUT_F32 ? 3 : 1))) void k_conv_smallk(const ConvGeom g, const GemmIO io) {
+  static_assert(!IN_F32 || sizeof(T) == 2, "fp32 layers read fp32 as it is");
   constexpr int VW = 16 / sizeof(T);
   constexpr int BK = 4 * VW;               // one contraction step of the MFMA helper: 32 bf16 / 16 fp32
   constexpr int STEPS = kKP / BK;          // 1 / 2
@@ -47,8 +49,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rep = blockIdx.z;
   const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  constexpr int IS = IN_F32 ? 4 : (int)sizeof(T);  // bytes per gathered element in memory
   const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)((const T *)io.in + rep * io.in_rs), 0, (int)(io.in_bytes), 0x00020000);
+      (void *)((const char *)io.in + rep * io.in_rs * IS), 0, (int)(io.in_bytes), 0x00020000);
   const T *__restrict__ w = (const T *)io.w + rep * io.w_rs;
 
   // this thread's pixel
@@ -68,8 +71,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(sizeof
     for (int k = 0; k < kKP; ++k) {
       const bool live = k < g.K;
       const bool ok = live && m_ok && (unsigned)(h0 + r) < (unsigned)g.Hin && (unsigned)(w0 + s) < (unsigned)g.Win;
-      const uint32_t off = ok ? (uint32_t)((base + (r * g.Win + s) * g.Cc + c) * (int)sizeof(T)) : kOobOffset;
-      vals[k] = buffer_load_elem<T>(a_rsrc, off);
+      const uint32_t off = ok ? (uint32_t)((base + (r * g.Win + s) * g.Cc + c) * IS) : kOobOffset;
+      if constexpr (IN_F32)
+        vals[k] = (T)f32_to_bf16(buffer_load_elem<float>(a_rsrc, off));
+      else
+        vals[k] = buffer_load_elem<T>(a_rsrc, off);
       if (++c == g.Cc) {
         c = 0;
         if (++s == g.S) s = 0, ++r;
@@ -133,6 +139,7 @@ __device__ __forceinline__ u4 tr_frag16(const bf16_t *tile, int ld, int krow, in
   return r;
 }
 
+template <bool X_F32>
 __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, const WgradIO io) {
   constexpr int BKM = 32;             // pixels per contraction step
   constexpr int BM = 128, BN = kKP;   // output tile: 128 output channels (four wavefronts) x 32 contraction columns
@@ -147,8 +154,9 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
   const int n0 = blockIdx.y * BM;
   const int m_begin = split * io.chunk, m_end = min(g.M, m_begin + io.chunk);
   const int PQ = g.P * g.Q;
+  constexpr int XS = X_F32 ? 4 : 2;  // bytes per element of x in memory
   const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      (void *)((const bf16_t *)io.x + rep * io.x_rs), 0, (int)((long long)(g.M / PQ) * g.Hin * g.Win * g.Cc * 2), 0x00020000);
+      (void *)((const char *)io.x + rep * io.x_rs * XS), 0, (int)((long long)(g.M / PQ) * g.Hin * g.Win * g.Cc * XS), 0x00020000);
   const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void *)((const bf16_t *)io.dy + rep * io.dy_rs), 0, (int)((long long)g.M * g.N * 2), 0x00020000);
 
@@ -184,7 +192,11 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const bool ok = mok && (unsigned)(h0 + k_r[e]) < (unsigned)g.Hin && (unsigned)(w0 + k_s[e]) < (unsigned)g.Win;
-      breg[e] = __builtin_amdgcn_raw_buffer_load_b16(x_rsrc, ok ? (uint32_t)((base + k_off[e]) * 2) : kOobOffset, 0, 0);
+      const uint32_t xo = ok ? (uint32_t)((base + k_off[e]) * XS) : kOobOffset;
+      if constexpr (X_F32)
+        breg[e] = f32_to_bf16(__uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(x_rsrc, xo, 0, 0)));
+      else
+        breg[e] = __builtin_amdgcn_raw_buffer_load_b16(x_rsrc, xo, 0, 0);
       // the first unused column is all ones over the live pixels: its products are the column sums of dy
       if (io.with_bias && kq + e == g.K) breg[e] = mok ? (unsigned short)0x3F80 : (unsigned short)0;
     }
@@ -254,6 +266,18 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_smallk(const ConvGeom g, con
 template <typename T, int TN>
 hipError_t run_smallk(hipStream_t st, bool out_f32, int replicas, const ConvGeom &g, const GemmIO &io) {
   dim3 grid((g.M + 255) / 256, (g.N + TN * 32 - 1) / (TN * 32), replicas);
+  if (io.in_f32) {  // a bf16 layer over fp32 memory
+    if constexpr (sizeof(T) == 2) {
+      if (out_f32 || (io.stat && TN > 2)) return hipErrorInvalidValue;
+      if (io.stat)
+        hipLaunchKernelGGL((k_conv_smallk<T, TN, false, TN <= 2, true>), grid, dim3(kThreads), 0, st, g, io);
+      else
+        hipLaunchKernelGGL((k_conv_smallk<T, TN, false, false, true>), grid, dim3(kThreads), 0, st, g, io);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   if (io.stat) {
     if (TN > 2 || out_f32) return hipErrorInvalidValue;  // see conv_smallk_stat_splits
     hipLaunchKernelGGL((k_conv_smallk<T, TN, false, TN <= 2>), grid, dim3(kThreads), 0, st, g, io);
@@ -298,6 +322,9 @@ bool wgrad_smallk_applicable(int dtype, const ConvGeom &g) {
 
 hipError_t launch_wgrad_smallk(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   dim3 grid(1, (g.N + 127) / 128, replicas * io.splits);
-  hipLaunchKernelGGL(k_wgrad_smallk, grid, dim3(kThreads), 0, st, g, io);
+  if (io.x_f32)
+    hipLaunchKernelGGL(k_wgrad_smallk<true>, grid, dim3(kThreads), 0, st, g, io);
+  else
+    hipLaunchKernelGGL(k_wgrad_smallk<false>, grid, dim3(kThreads), 0, st, g, io);
   return hipGetLastError();
 }

@@ -84,6 +84,9 @@ struct Net {
   // events than the stream hides (+4 %), and a mix of both placements measured worst of all.
   bool bias_stream = false;
   bool bias_in_wgrad = true;  // PARLE_BIAS_IN_WGRAD=0: every bias gradient by its own column-sum kernels
+  // bf16 networks: the first layer gathers the caller's fp32 images itself, rounding as it gathers, where its
+  // kernels can (the small-window ones); otherwise a bf16 copy is made first.  PARLE_IMAGES_DIRECT=0: always copy.
+  int images_reader = -1;  // the one convolution that reads the images, or -1
   // Wavefronts a weight-gradient launch of the nine-tap kernel puts in flight.  Where batch-norm passes share
   // the chain of input gradients, that chain is the longer one and the leaves have slack: they take half the
   // chip's SIMDs and leave the rest to the chain (WRN-16-4 -3 %); without batch-norm the leaves are the longer
@@ -390,6 +393,13 @@ bool build_plan(Net &N, std::string &err) {
     N.bias_stream = with_bias >= 2 && 2 * large > with_bias;
     const char *e = getenv("PARLE_BIAS_IN_WGRAD");
     N.bias_in_wgrad = !(e && atoi(e) == 0);
+    const char *d = getenv("PARLE_IMAGES_DIRECT");
+    int readers = 0, reader = -1;
+    for (int oi = 0; oi < (int)N.ops.size(); ++oi)
+      if (N.ops[oi].in == N.t_images || (N.ops[oi].type == OP_CONV && N.ops[oi].resid == N.t_images)) ++readers, reader = oi;
+    if (!(d && atoi(d) == 0) && readers == 1 && N.ops[reader].type == OP_CONV && N.ops[reader].in == N.t_images &&
+        !N.ops[reader].need_dx && !N.ops[reader].branch)
+      N.images_reader = reader;
   }
   // two kinds of tables: layers whose rows fill whole 16-byte vectors (tiled, vector kernel) and the rest
   for (int vec = 1; vec >= 0; --vec) {
@@ -440,9 +450,10 @@ struct Run {
   const float *images;
   const long long *step_dev;  // inner-step counter (dropout key); NULL outside training
   float *loss_out = nullptr;  // [n] mean losses of this step, or NULL (training with the fused classifier head)
+  bool images_direct = false;  // bf16 network whose first layer reads the fp32 images as they lie
   void *tptr(int t) const {
     const Tensor &T = N->tensors[t];
-    return T.external ? (void *)images : (void *)(ws + T.off);
+    return T.external || (images_direct && t == N->t_images) ? (void *)images : (void *)(ws + T.off);
   }
   void *gptr(int t) const { return ws + N->tensors[t].goff; }
   int64_t trs(int t) const { return (int64_t)B * N->tensors[t].H * N->tensors[t].W * N->tensors[t].C; }
@@ -453,6 +464,19 @@ struct Run {
 ConvShape shape_of(const Op &op, int B) { return ConvShape{B, op.Hin, op.Win, op.Cin, op.Cout, op.R, op.stride, op.pad}; }
 ConvGeom fwd_geom(const Op &op, int B) { return conv_fwd_geom(shape_of(op, B)); }
 ConvGeom bwd_geom(const Op &op, int B) { return conv_bwd_geom(shape_of(op, B)); }
+
+// Whether the layer that reads the images can take them as fp32 (forward, and backward-weight when training), for a
+// batch of B images per replica.
+bool images_direct_ok(const Net &N, int B, bool train, const void *images) {
+  if (N.dtype != 1 || N.images_reader < 0) return false;
+  const Op &op = N.ops[N.images_reader];
+  const ConvGeom g = fwd_geom(op, B);
+  GemmIO io{};
+  io.ldc = op.Cout;
+  io.in_bytes = (long long)B * op.Hin * op.Win * op.Cin * 4;
+  if (N.tensors[op.out].f32 || !conv_smallk_applicable(1, g, io) || !aligned_to(images, 4)) return false;
+  return !train || wgrad_smallk_applicable(1, g);
+}
 
 #define HIP_TRY(expr)                   \
   do {                                  \
@@ -490,6 +514,7 @@ hipError_t forward(const Run &r, bool train, float *bn_stats, const float *bn_ev
     io.vecB = (g.K % vw == 0) && (N.dtype == 0 || ((N.segs[op.wseg].offset % vw == 0) && (r.p_rs % vw == 0) &&
                                                    aligned_to(io.w, 16)));
     io.in_bytes = io.in_rs * N.esize;
+    if (r.images_direct && op.in == N.t_images) io.in_f32 = 1, io.vecA = 0, io.in_bytes = io.in_rs * 4;
     return io;
   };
   auto launch_pending = [&]() -> hipError_t {
@@ -662,6 +687,7 @@ hipError_t backward(const Run &r, float *grad) {
         io.x = r.tptr(op.in), io.x_rs = r.trs(op.in);
         io.pairA = (op.Cout % 2 == 0) && aligned_to(dy, 4);
         io.pairB = (op.Cin % 2 == 0) && aligned_to(io.x, 4);
+        io.x_f32 = r.images_direct && op.in == N.t_images;
         const bool bias_in_wgrad = op.bseg >= 0 && N.bias_in_wgrad && wgrad_takes_bias(N.dtype, gf, io) &&
                                    N.segs[op.bseg].offset == N.segs[op.wseg].offset + N.segs[op.wseg].size;
         if (op.bseg >= 0 && !bias_in_wgrad) {
@@ -834,7 +860,8 @@ hipError_t net_train_step(Net *net, hipStream_t st, const float *params, const v
   if (N.overlap && !N.side) HIP_TRY(make_side_stream(N, st));
   Run r{net, st, N.n, N.B, params, N.dtype ? params_bf16 : (const void *)params, N.n_pad, (char *)workspace, images,
         step_dev};
-  if (N.dtype == 1) {
+  r.images_direct = images_direct_ok(N, N.B, true, images);
+  if (N.dtype == 1 && !r.images_direct) {
     const Tensor &ti = N.tensors[N.t_images];
     HIP_TRY(launch_convert(st, 1, images, r.ws + ti.off, (long long)N.n * N.B * ti.H * ti.W * ti.C));
   }
@@ -880,7 +907,8 @@ hipError_t net_eval(Net *net, hipStream_t st, const float *param_row, const floa
     row_t = ws + N.off_rowcopy;
   }
   Run r{net, st, 1, count, param_row, row_t, N.n_pad, ws, images, nullptr};
-  if (N.dtype == 1) {
+  r.images_direct = images_direct_ok(N, count, false, images);
+  if (N.dtype == 1 && !r.images_direct) {
     const Tensor &ti = N.tensors[N.t_images];
     HIP_TRY(launch_convert(st, 1, images, ws + ti.off, (long long)count * ti.H * ti.W * ti.C));
   }
