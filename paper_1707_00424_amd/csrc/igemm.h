@@ -158,7 +158,7 @@ hipError_t launch_gemm_ksplit(hipStream_t st, int dtype, bool out_f32, int repli
 bool wgrad_small_f32_applicable(int dtype, const ConvGeom &g);
 // True when launch_wgrad would run a kernel that honours WgradIO::with_bias for this layer and these operands
 // (io.dy, io.pairA, io.pairB set): the small-window kernels when the window leaves one of their 32 contraction
-// columns unused, the stride-1 3x3 kernel and the transpose-read kernel.
+// columns unused, the stride-1 3x3 kernel, the transpose-read kernel and the generic fp32 kernel.
 bool wgrad_takes_bias(int dtype, const ConvGeom &g, const WgradIO &io);
 hipError_t launch_wgrad_small_f32(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io);
 // Backward-data of stride-2 3x3 pad-1 layers, four parity classes per workgroup (igemm_dgrad2.hip).

@@ -163,8 +163,11 @@ __global__ __launch_bounds__(kThreads) void k_igemm(const ConvGeom g, const Gemm
 // Both operands arrive contraction-major from memory; each thread loads VW consecutive rows m of a
 // 4-byte column group and writes them to LDS as 16-byte contraction-contiguous fragments.
 // ---------------------------------------------------------------------------------------------
-template <typename T, int WAVES_M, int WAVES_N, int TM, int TN>
+// BIAS (fp32): the workgroups of the first column tile also add up the dy values they stage (a thread keeps one
+// output channel) and write the bias gradient, the column sums of dy, behind the weights.
+template <typename T, int WAVES_M, int WAVES_N, int TM, int TN, bool BIAS = false>
 __global__ __launch_bounds__(kThreads) void k_wgrad(const ConvGeom g, const WgradIO io) {
+  static_assert(!BIAS || sizeof(T) == 4, "the bias sums are taken by the fp32 form only");
   constexpr int VW = 16 / sizeof(T);
   constexpr int CP = 4 / sizeof(T);  // columns per 4-byte load
   constexpr int BK = 4 * VW;
@@ -206,6 +209,12 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const ConvGeom g, const Wgra
   }
 
   uint32_t areg[A_IT][VW], breg[B_IT][VW];  // one 4-byte column group per contraction row
+  const bool tally = BIAS && blockIdx.x == 0;
+  float bsum[BIAS ? A_IT : 1];
+  if (BIAS) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) bsum[i] = 0.f;
+  }
 
   auto load_tiles = [&](int mbase) {
 #pragma unroll
@@ -295,6 +304,10 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const ConvGeom g, const Wgra
     for (int i = 0; i < A_IT; ++i) {
       const int t = i * kThreads + tid;
       if (A_TASKS % kThreads == 0 || t < A_TASKS) store_one(As[buf], BM / CP, t, areg[i], BM);
+      if (BIAS && tally) {  // masked rows and columns hold zeros
+#pragma unroll
+        for (int j = 0; j < VW; ++j) bsum[i] += __uint_as_float(areg[i][j]);
+      }
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
@@ -339,6 +352,19 @@ __global__ __launch_bounds__(kThreads) void k_wgrad(const ConvGeom g, const Wgra
         if (n < g.N) out[(long long)n * g.K + k] = acc[tm][tn][v];
       }
   }
+  if (BIAS && tally) {
+    // task t of a step holds column t % BM, rows 4 * (t / BM) .. + 3: the four row groups are added in order
+    float *bs = (float *)&As[0][0];  // [4][BM]; the last step ended with a barrier
+    static_assert(sizeof(As) >= 4 * BM * 4, "bias staging");
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+      const int t = i * kThreads + tid;
+      if (A_TASKS % kThreads == 0 || t < A_TASKS) bs[(t / BM) * BM + t % BM] = bsum[i];
+    }
+    __syncthreads();
+    for (int c = tid; c < BM; c += kThreads)
+      if (n0 + c < g.N) out[(long long)g.N * g.K + n0 + c] = bs[c] + bs[BM + c] + bs[2 * BM + c] + bs[3 * BM + c];
+  }
 }
 
 template <typename T, int WM, int WN, int TM, int TN>
@@ -356,6 +382,12 @@ template <typename T, int WM, int WN, int TM, int TN>
 hipError_t run_wgrad(hipStream_t st, int replicas, const ConvGeom &g, const WgradIO &io) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   dim3 grid((g.K + BN - 1) / BN, (g.N + BM - 1) / BM, replicas * io.splits);
+  if constexpr (sizeof(T) == 4) {
+    if (io.with_bias) {
+      hipLaunchKernelGGL((k_wgrad<T, WM, WN, TM, TN, true>), grid, dim3(kThreads), 0, st, g, io);
+      return hipGetLastError();
+    }
+  }
   hipLaunchKernelGGL((k_wgrad<T, WM, WN, TM, TN>), grid, dim3(kThreads), 0, st, g, io);
   return hipGetLastError();
 }
@@ -432,6 +464,7 @@ bool wgrad_takes_bias(int dtype, const ConvGeom &g, const WgradIO &io) {
   if (wgrad_smallk_applicable(dtype, g) && aligned_to(io.dy, 16)) return g.K < 32;
   if (wgrad_small_f32_applicable(dtype, g)) return g.K < 32;
   if (wgrad_window_applicable(dtype, g)) return false;
+  if (dtype == 0) return true;  // the generic fp32 kernel
   return (wgrad9_applicable(dtype, g) || wgrad_fast_applicable(dtype, g)) && io.pairA && io.pairB;
 }
 

@@ -135,8 +135,13 @@ def _takes_bias(case, dtype):
     transpose-read kernel (channel counts that are multiples of 8, at least 32 outputs)."""
     n, B, H, W, Cin, Cout, k, stride, pad = case
     K = k * k * Cin
-    if dtype == 0:
-        return K < 32 and Cout <= 32
+    if dtype == 0:       # every fp32 kernel but the per-image LDS one of a few-channel layer under a wide window
+        if K <= 32 and Cout <= 32:
+            return K < 32
+        P, Q = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+        window = (stride == 1 and k >= 2 and P * Q <= 64 and P * Q % 8 == 0 and 128 <= K <= 512 and Cout <= 64
+                  and (H + 2 * pad) * (W + 2 * pad) * Cin <= 6144)
+        return not window
     if K <= 32 and Cout % 8 == 0:
         return K < 32
     return Cin % 8 == 0 and Cout % 8 == 0 and Cout >= 32
