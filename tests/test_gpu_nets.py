@@ -818,6 +818,38 @@ def test_full_size_streams_change_nothing(gpu, model, monkeypatch):
 
 
 @pytest.mark.parametrize("model", ["allcnn", "wrn"])
+def test_full_size_first_layer_reading_fp32_images_changes_nothing(gpu, model, monkeypatch):
+    """In bf16 mode the first layer's kernels gather the caller's fp32 images and round each value as they gather it;
+    with that switched off a copy kernel rounds the images first.  Same values either way: two inner steps and an
+    outer step must give the same bits."""
+    torch, pb = gpu
+    a, n, B, L = onets.arch(model), 3, 128, 2
+    mdl, arch = model_pair(pb, a)
+    cfg = pb.make_config(model=mdl, n_replicas=n, batch=B, L=L, compute_bf16=1, in_h=a["H"], in_w=a["W"], in_c=a["C"],
+                         n_classes=a["classes"], arch=arch, eta_inner=0.01, eta_outer=0.01, gamma0=0.03, rho0=1.0,
+                         fuse_outer=1, graph_block=0)
+    x0 = np.tile(synth.init_params(pb.parle_query_layout(cfg), 0, "he_normal"), (n, 1))
+    X, Y = synth.image_batches(1, L, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    states = []
+    for direct in ("1", "0"):
+        monkeypatch.setenv("PARLE_IMAGES_DIRECT", direct)      # read when the context is created
+        P = pb.Parle(cfg, x0)
+        loss = torch.zeros((L, n), dtype=torch.float32, device="cuda")
+        for k in range(L):
+            P.parle_inner_step(dX[k], dY[k], loss[k])
+        P.parle_outer_step()
+        ev = P.parle_eval(-1, dX[0, 0], dY[0, 0])
+        torch.cuda.synchronize()
+        states.append([loss.clone()] + [getattr(P, t).clone() for t in ("grad", "y", "x", "x_ref")] +
+                      [torch.tensor([float(v) for v in ev[:2]])])
+        P.close()
+    for u, v in zip(*states):
+        assert torch.equal(u, v)
+    assert np.isfinite(states[0][0].cpu().numpy()).all()
+
+
+@pytest.mark.parametrize("model", ["allcnn", "wrn"])
 def test_full_size_blocks_from_the_graph_equal_step_by_step(gpu, model):
     """The launch configuration that bench.py times (n = 3, batch 128, 3x32x32, bf16 compute, blocks of L = 25
     inner steps replayed from a HIP graph, fused outer step, scoping on for WRN) against a second context that
