@@ -849,6 +849,37 @@ def test_full_size_first_layer_reading_fp32_images_changes_nothing(gpu, model, m
     assert np.isfinite(states[0][0].cpu().numpy()).all()
 
 
+@pytest.mark.parametrize("model,bf16", [("allcnn", 1), ("lenet", 0), ("mlp", 0)])
+def test_full_size_bias_gradient_inside_the_weight_gradient_kernels(gpu, model, bf16, monkeypatch):
+    """The weight-gradient kernels take a layer's bias gradient (the column sums of dy) along; switched off, the
+    column-sum kernels compute it.  Same inputs, two orders of fp32 additions: after one inner step every segment of
+    the gradient agrees to 2e-6 of its norm (a dropped row, tile or split would show as 1e-3 or more)."""
+    torch, pb = gpu
+    a = onets.arch(model)
+    n, B = (6 if model == "lenet" else 3), 128
+    mdl, arch = model_pair(pb, a)
+    cfg = pb.make_config(model=mdl, n_replicas=n, batch=B, L=1, compute_bf16=bf16, in_h=a["H"], in_w=a["W"],
+                         in_c=a["C"], n_classes=a["classes"], arch=arch, eta_inner=0.01, eta_outer=0.01, gamma0=0.03,
+                         rho0=1.0, fuse_outer=1, graph_block=0)
+    layout = pb.parle_query_layout(cfg)
+    x0 = np.tile(synth.init_params(layout, 0, "he_normal" if bf16 else "uniform"), (n, 1))
+    X, Y = synth.image_batches(3, 1, n, B, a["H"], a["W"], a["C"], a["classes"])
+    dX, dY = dev(torch, X), dev(torch, Y)
+    grads = []
+    for inside in ("1", "0"):
+        monkeypatch.setenv("PARLE_BIAS_IN_WGRAD", inside)      # read when the context is created
+        P = pb.Parle(cfg, x0)
+        loss = torch.zeros((1, n), dtype=torch.float32, device="cuda")
+        P.parle_inner_step(dX[0], dY[0], loss[0])
+        torch.cuda.synchronize()
+        grads.append(P.grad.cpu().numpy()[:, :P.sizes.n_params])
+        P.close()
+    assert any(s["kind"] == "bias" for s in layout)
+    worst = max(e for _, e, _ in segment_errors(layout, grads[0], grads[1]))
+    assert 0 < np.abs(grads[1]).max() < np.inf
+    assert worst <= 2e-6, segment_errors(layout, grads[0], grads[1])
+
+
 @pytest.mark.parametrize("model", ["allcnn", "wrn"])
 def test_full_size_blocks_from_the_graph_equal_step_by_step(gpu, model):
     """The launch configuration that bench.py times (n = 3, batch 128, 3x32x32, bf16 compute, blocks of L = 25
